@@ -1,0 +1,198 @@
+/*
+ * CPU oracle for sparse x dense products and for the position cut.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Nothing in the product path may call this file;
+ * it is used by the tests, by the smoke check and by the benchmark's CPU
+ * baseline leg.  It shares no code with the HIP kernels.
+ *
+ * The scheduled kernels of the paper compute, up to the order of the
+ * floating-point additions, exactly what the unscheduled loop nests compute
+ * (Section 5, "Parallelize": reordering only needs associativity), so the
+ * oracle is the plain definition written out:
+ *
+ *   y(i)   = sum_j A(i,j) * x(j)          (Appendix, "SPMV on a CPU")
+ *   C(i,k) = sum_j A(i,j) * B(j,k)        (Appendix, "SPMM on a CPU")
+ *
+ * over the coordinate hierarchy of a CSR matrix: a dense row level and a
+ * compressed column level whose segment for row i is pos[i]..pos[i+1]
+ * (Section 3).  Products and sums are taken in fp64 from the fp32 inputs.
+ * Besides each result the functions return mag = sum_j |A(i,j) * x(j)|, the
+ * scale of the admissible fp32 error of a row.
+ *
+ * BCSR (Section 1: a sparse matrix with dense inner dimensions) is the
+ * four-level hierarchy (dense block row, compressed block column, dense row
+ * in block, dense column in block) stored in lexicographic order (Section 3):
+ * value (p, ii, ji) of block position p lives at vals[(p*bs + ii)*bs + ji].
+ *
+ * The position cut (Section 3, tiling the position space; Section 5,
+ * "Split"; Section 6.2, coordinate recovery) splits positions 0..nnz into
+ * tiles of `tile` positions.  tile_row[t] is the row that owns position
+ * min(t*tile, nnz): the largest i with pos[i] <= that position.  The paper
+ * finds it by binary search; the oracle instead walks the rows once, the way
+ * the position loop of Section 3 advances i past row ends and empty rows.
+ *
+ * If `sel` is not NULL only the `nsel` listed rows are computed and outputs
+ * are indexed by the position in the list (used to sample very large cases).
+ * `threads` > 1 spreads rows over OpenMP threads; each row is still summed
+ * serially, in storage order, by one thread.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static int clamp_threads(int threads)
+{
+#ifdef _OPENMP
+    if (threads < 1) threads = 1;
+    int m = omp_get_max_threads();
+    return threads > m ? m : threads;
+#else
+    (void)threads;
+    return 1;
+#endif
+}
+
+/* number of threads a call with this request would really use */
+int oracle_threads(int threads) { return clamp_threads(threads); }
+
+/* y(i) = A(i,j) * x(j), CSR.  y and mag have `rows` (or nsel) doubles; mag may be NULL. */
+void oracle_spmv_csr(int64_t rows, const int32_t *pos, const int32_t *crd, const float *vals,
+                     const float *x, double *y, double *mag, const int64_t *sel, int64_t nsel,
+                     int threads)
+{
+    int64_t n = sel ? nsel : rows;
+    threads = clamp_threads(threads);
+#pragma omp parallel for schedule(dynamic, 1024) num_threads(threads)
+    for (int64_t s = 0; s < n; ++s) {
+        int64_t i = sel ? sel[s] : s;
+        double acc = 0.0, m = 0.0;
+        for (int64_t p = pos[i]; p < pos[i + 1]; ++p) {
+            double t = (double)vals[p] * (double)x[crd[p]];
+            acc += t;
+            m += fabs(t);
+        }
+        y[s] = acc;
+        if (mag) mag[s] = m;
+    }
+}
+
+/* C(i,k) = A(i,j) * B(j,k), CSR A, row-major B (ldb) and C (k doubles per row, packed). */
+void oracle_spmm_csr(int64_t rows, int64_t k, const int32_t *pos, const int32_t *crd,
+                     const float *vals, const float *B, int64_t ldb, double *C, double *mag,
+                     const int64_t *sel, int64_t nsel, int threads)
+{
+    int64_t n = sel ? nsel : rows;
+    threads = clamp_threads(threads);
+#pragma omp parallel for schedule(dynamic, 256) num_threads(threads)
+    for (int64_t s = 0; s < n; ++s) {
+        int64_t i = sel ? sel[s] : s;
+        double *c = C + s * k;
+        double *m = mag ? mag + s * k : NULL;
+        for (int64_t kk = 0; kk < k; ++kk) { c[kk] = 0.0; if (m) m[kk] = 0.0; }
+        for (int64_t p = pos[i]; p < pos[i + 1]; ++p) {
+            double a = (double)vals[p];
+            const float *b = B + (int64_t)crd[p] * ldb;
+            for (int64_t kk = 0; kk < k; ++kk) {
+                double t = a * (double)b[kk];
+                c[kk] += t;
+                if (m) m[kk] += fabs(t);
+            }
+        }
+    }
+}
+
+/* BCSR SpMV: brows block rows of bs x bs blocks; y, mag have brows*bs (or nsel*bs) doubles;
+ * sel lists BLOCK rows. */
+void oracle_spmv_bcsr(int64_t brows, int32_t bs, const int32_t *pos, const int32_t *crd,
+                      const float *vals, const float *x, double *y, double *mag,
+                      const int64_t *sel, int64_t nsel, int threads)
+{
+    int64_t n = sel ? nsel : brows;
+    threads = clamp_threads(threads);
+#pragma omp parallel for schedule(dynamic, 256) num_threads(threads)
+    for (int64_t s = 0; s < n; ++s) {
+        int64_t ib = sel ? sel[s] : s;
+        for (int32_t ii = 0; ii < bs; ++ii) {
+            double acc = 0.0, m = 0.0;
+            for (int64_t p = pos[ib]; p < pos[ib + 1]; ++p) {
+                int64_t jb = crd[p];
+                for (int32_t ji = 0; ji < bs; ++ji) {
+                    double t = (double)vals[(p * bs + ii) * bs + ji] * (double)x[jb * bs + ji];
+                    acc += t;
+                    m += fabs(t);
+                }
+            }
+            y[s * bs + ii] = acc;
+            if (mag) mag[s * bs + ii] = m;
+        }
+    }
+}
+
+/* BCSR SpMM: C((ib,ii),k) = sum over blocks p of row ib, ji: vals(p,ii,ji) * B((crd[p],ji),k). */
+void oracle_spmm_bcsr(int64_t brows, int32_t bs, int64_t k, const int32_t *pos, const int32_t *crd,
+                      const float *vals, const float *B, int64_t ldb, double *C, double *mag,
+                      const int64_t *sel, int64_t nsel, int threads)
+{
+    int64_t n = sel ? nsel : brows;
+    threads = clamp_threads(threads);
+#pragma omp parallel for schedule(dynamic, 64) num_threads(threads)
+    for (int64_t s = 0; s < n; ++s) {
+        int64_t ib = sel ? sel[s] : s;
+        for (int32_t ii = 0; ii < bs; ++ii) {
+            double *c = C + (s * bs + ii) * k;
+            double *m = mag ? mag + (s * bs + ii) * k : NULL;
+            for (int64_t kk = 0; kk < k; ++kk) { c[kk] = 0.0; if (m) m[kk] = 0.0; }
+            for (int64_t p = pos[ib]; p < pos[ib + 1]; ++p) {
+                int64_t jb = crd[p];
+                for (int32_t ji = 0; ji < bs; ++ji) {
+                    double a = (double)vals[(p * bs + ii) * bs + ji];
+                    const float *b = B + (jb * bs + ji) * ldb;
+                    for (int64_t kk = 0; kk < k; ++kk) {
+                        double t = a * (double)b[kk];
+                        c[kk] += t;
+                        if (m) m[kk] += fabs(t);
+                    }
+                }
+            }
+        }
+    }
+}
+
+/* number of position tiles: ceil(nnz / tile) */
+int64_t oracle_num_tiles(int64_t nnz, int64_t tile) { return nnz <= 0 ? 0 : (nnz + tile - 1) / tile; }
+
+/*
+ * Position cut: tile_row has oracle_num_tiles(nnz,tile)+1 entries.
+ * One pass over the rows: i only ever advances (the tracking recurrence of
+ * Section 6.2), stepping over a row when all of its positions, if it has any,
+ * lie at or before the tile's first position.
+ */
+void oracle_partition(int64_t rows, int64_t nnz, const int32_t *pos, int64_t tile, int32_t *tile_row)
+{
+    int64_t ntiles = oracle_num_tiles(nnz, tile);
+    int64_t i = 0;
+    for (int64_t t = 0; t <= ntiles; ++t) {
+        int64_t first = t * tile;
+        if (first > nnz) first = nnz;
+        while (i < rows && (int64_t)pos[i + 1] <= first) ++i;
+        tile_row[t] = (int32_t)i;
+    }
+}
+
+/*
+ * Structural validity of a CSR/BCSR index structure: pos[0]=0, pos monotone,
+ * pos[rows]=nnz, 0 <= crd < cols.  Returns 0 if valid, else a code 1..4.
+ */
+int oracle_validate_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd)
+{
+    if (pos[0] != 0) return 1;
+    for (int64_t i = 0; i < rows; ++i)
+        if (pos[i + 1] < pos[i]) return 2;
+    if (pos[rows] != nnz) return 3;
+    for (int64_t p = 0; p < nnz; ++p)
+        if (crd[p] < 0 || crd[p] >= cols) return 4;
+    return 0;
+}

@@ -1,0 +1,176 @@
+"""Seeded synthetic inputs shaped like the evaluated workloads.
+
+Inputs only: sparsity patterns, values, dense operands.  Nothing here computes
+a product, a reduction or a position cut, so the CPU oracle and the HIP path
+can both be fed from this module without sharing any of the method's logic.
+
+The paper evaluates on SuiteSparse/FROSTT collections and on synthetic
+matrices (random nonzeros, skewed row lengths, few long rows: Section 8.1,
+8.3-8.5).  The collections are not available offline; the generators below
+stand in for them with the same structural classes.
+
+Matrices are returned as a ``CSR`` tuple of numpy arrays (int32 ``pos`` and
+``crd``, float32 ``vals``); BCSR matrices use the same container with ``bs``
+set, ``pos``/``crd`` indexing blocks and ``vals`` holding ``bs*bs`` floats per
+block, row-major inside a block.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "gen.c")
+_SO = os.path.join(_HERE, "libworkloads.so")
+
+BASE_SEED = 200100532  # config n uses BASE_SEED + n
+
+# stream identifiers (which array a draw belongs to)
+S_VALS, S_COLS, S_X, S_B, S_LEN = 1, 2, 3, 4, 5
+
+
+def build(force: bool = False) -> str:
+    """Compile gen.c into libworkloads.so (host code, gcc + OpenMP)."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _SO, _SRC, "-lm"]
+        )
+    return _SO
+
+
+_lib_handle = None
+
+
+def _lib():
+    global _lib_handle
+    if _lib_handle is None:
+        lib = ctypes.CDLL(build())
+        i64, u64, f32, p = ctypes.c_int64, ctypes.c_uint64, ctypes.c_float, ctypes.c_void_p
+        lib.wl_fill_uniform.argtypes = [p, i64, u64, u64, f32, f32]
+        lib.wl_fill_uniform.restype = None
+        lib.wl_zipf_lengths.argtypes = [p, i64, ctypes.c_double, ctypes.c_int32, ctypes.c_int32, u64, u64]
+        lib.wl_zipf_lengths.restype = ctypes.c_int
+        lib.wl_csr_columns.argtypes = [p, i64, i64, u64, u64, p]
+        lib.wl_csr_columns.restype = ctypes.c_int
+        lib.wl_stencil27_nnz.argtypes = [i64]
+        lib.wl_stencil27_nnz.restype = i64
+        lib.wl_stencil27.argtypes = [i64, u64, u64, p, p, p]
+        lib.wl_stencil27.restype = ctypes.c_int
+        _lib_handle = lib
+    return _lib_handle
+
+
+def _ptr(a: np.ndarray) -> int:
+    return a.ctypes.data
+
+
+@dataclass
+class CSR:
+    rows: int          # rows (block rows when bs > 1)
+    cols: int          # columns (block columns when bs > 1)
+    pos: np.ndarray    # int32 [rows+1]
+    crd: np.ndarray    # int32 [nnz]   (block columns when bs > 1)
+    vals: np.ndarray   # float32 [nnz * bs * bs]
+    bs: int = 1        # dense block edge (1 = plain CSR)
+
+    @property
+    def nnz(self) -> int:
+        """Stored positions at the compressed level (blocks when bs > 1)."""
+        return int(self.pos[-1])
+
+
+def dense_uniform(n: int, seed: int, stream: int, lo: float = -1.0, hi: float = 1.0) -> np.ndarray:
+    out = np.empty(int(n), dtype=np.float32)
+    _lib().wl_fill_uniform(_ptr(out), int(n), seed, stream, lo, hi)
+    return out
+
+
+def csr_from_lengths(lengths, cols: int, seed: int, lo: float = -1.0, hi: float = 1.0, bs: int = 1) -> CSR:
+    """CSR/BCSR with the given number of stored entries per row; columns are
+    distinct, uniform over [0, cols) and sorted within each row."""
+    lengths = np.ascontiguousarray(lengths, dtype=np.int64)
+    rows = int(lengths.shape[0])
+    if lengths.size and (lengths.min() < 0 or lengths.max() > cols):
+        raise ValueError("row length outside [0, cols]")
+    total = int(lengths.sum())
+    if total >= 2**31:
+        raise ValueError("nnz does not fit int32 positions")
+    pos = np.zeros(rows + 1, dtype=np.int32)
+    pos[1:] = np.cumsum(lengths, dtype=np.int64).astype(np.int32)
+    crd = np.empty(total, dtype=np.int32)
+    if _lib().wl_csr_columns(_ptr(pos), rows, int(cols), seed, S_COLS, _ptr(crd)) != 0:
+        raise RuntimeError("column generation failed")
+    vals = dense_uniform(total * bs * bs, seed, S_VALS, lo, hi)
+    return CSR(rows, int(cols), pos, crd, vals, bs)
+
+
+def csr_uniform(rows: int, cols: int, per_row: int, seed: int, bs: int = 1) -> CSR:
+    """Exactly ``per_row`` stored entries in every row."""
+    return csr_from_lengths(np.full(rows, per_row, dtype=np.int64), cols, seed, bs=bs)
+
+
+def zipf_lengths(rows: int, alpha: float, kmin: int, kmax: int, seed: int) -> np.ndarray:
+    out = np.empty(rows, dtype=np.int32)
+    if _lib().wl_zipf_lengths(_ptr(out), rows, alpha, kmin, kmax, seed, S_LEN) != 0:
+        raise RuntimeError("zipf generation failed")
+    return out
+
+
+def csr_powerlaw(rows: int, cols: int, alpha: float, kmin: int, kmax: int, seed: int) -> CSR:
+    """Row lengths i.i.d. from the truncated Zipf law k^-alpha on [kmin, kmax]."""
+    return csr_from_lengths(zipf_lengths(rows, alpha, kmin, min(kmax, cols), seed), cols, seed)
+
+
+def csr_stencil27(n: int, seed: int) -> CSR:
+    """27-point stencil on an n^3 grid, clipped at the faces; diagonal 27,
+    off-diagonals uniform in [0.5, 1.5)."""
+    lib = _lib()
+    rows = n ** 3
+    nnz = int(lib.wl_stencil27_nnz(n))
+    pos = np.empty(rows + 1, dtype=np.int32)
+    crd = np.empty(nnz, dtype=np.int32)
+    vals = np.empty(nnz, dtype=np.float32)
+    if lib.wl_stencil27(n, seed, S_VALS, _ptr(pos), _ptr(crd), _ptr(vals)) != 0:
+        raise RuntimeError("stencil generation failed")
+    return CSR(rows, rows, pos, crd, vals, 1)
+
+
+def config(n: int, scale: float = 1.0) -> dict:
+    """The n-th evaluated configuration (1..5) as a dict with the matrix ``A``
+    and the dense operands (``x`` and/or ``B`` with ``k`` columns).
+
+    ``scale`` < 1 shrinks the row/column counts (and the stencil edge by its
+    cube root) for tests; the structure class is unchanged.
+    """
+    seed = BASE_SEED + n
+    s = float(scale)
+    if n == 1:
+        r = max(16, int(round(1024 * s)))
+        A = csr_uniform(r, r, min(10, r), seed)
+        return {"name": "csr_spmv_uniform10", "A": A, "x": dense_uniform(r, seed, S_X)}
+    if n == 2:
+        r = max(16, int(round(2_000_000 * s)))
+        A = csr_powerlaw(r, r, 1.8, 1, max(1, int(round(200_000 * s))), seed)
+        return {"name": "csr_spmv_powerlaw", "A": A, "x": dense_uniform(r, seed, S_X)}
+    if n == 3:
+        g = max(2, int(round(160 * s ** (1.0 / 3.0))))
+        A = csr_stencil27(g, seed)
+        return {"name": "csr_spmv_stencil27", "A": A, "x": dense_uniform(A.cols, seed, S_X), "grid": g}
+    if n == 4:
+        r = max(16, int(round(1_000_000 * s)))
+        A = csr_uniform(r, r, min(16, r), seed)
+        k = 128
+        return {"name": "csr_spmm_uniform16_k128", "A": A, "k": k,
+                "B": dense_uniform(r * k, seed, S_B).reshape(r, k)}
+    if n == 5:
+        br = max(8, int(round(250_000 * s)))
+        A = csr_uniform(br, br, min(8, br), seed, bs=4)
+        k = 64
+        return {"name": "bcsr4_spmv_spmm_n64", "A": A, "k": k,
+                "x": dense_uniform(br * 4, seed, S_X),
+                "B": dense_uniform(br * 4 * k, seed, S_B).reshape(br * 4, k)}
+    raise ValueError("config must be 1..5")
