@@ -1,0 +1,172 @@
+/*
+ * psk -- position-space sparse x dense kernels for AMD MI355X (gfx950).
+ *
+ * C ABI of the library.  The operations are the two statements of the paper's
+ * appendix, scheduled by hand the way its GPU schedules do it (fuse the row
+ * and column loops, move the fused loop into the position space of A, split
+ * it into equal tiles -- appendix "SPMV on a GPU", "SPMM on a GPU"; Sections
+ * 3 and 5):
+ *
+ *     y(i)   = A(i,j) * x(j)            SpMV
+ *     C(i,k) = A(i,j) * B(j,k)          SpMM, dense row-major B and C
+ *
+ * A is CSR (Section 3: dense row level, compressed column level; row i owns
+ * positions pos[i] .. pos[i+1] of crd/vals) or BCSR (Section 1: the same with
+ * a dense bs x bs block per stored position, row-major inside the block,
+ * vals[(p*bs + ii)*bs + ji]).
+ *
+ * Conventions for every entry point
+ *  - Every pointer is a DEVICE pointer owned by the caller.  The library does
+ *    not allocate, free or keep any of them.  Scratch memory is passed in as
+ *    `workspace` (size from psk_workspace_bytes; 256-byte aligned).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  A
+ *    call only enqueues work on that stream and returns; it never
+ *    synchronises.  Calls that share a workspace must be stream-ordered.
+ *  - Index arrays are int32, values and dense operands fp32; products and sums
+ *    are fp32 on the device (carries between tiles are combined in fp64).
+ *  - Outputs are assigned, not accumulated: rows without stored entries
+ *    become +0.0f.  Inputs and outputs must not overlap.
+ *  - Results are run-to-run deterministic: every y(i) / C(i,k) has one writer
+ *    and a fixed summation order for a given tile size.
+ *  - Preconditions that are NOT checked on the device (caller's contract):
+ *    pos[0] = 0, pos non-decreasing, pos[rows] = nnz, 0 <= crd[p] < cols.
+ *    Columns inside a row need not be sorted or distinct (duplicates add up).
+ *  - Return value: PSK_OK or an error code; nothing is enqueued on error
+ *    (except PSK_ERR_HIP, which reports a failed launch).  No call aborts.
+ *  - Sizes: 0 <= rows, cols; 0 <= nnz <= 2^31-1.  Empty problems are valid.
+ *  - `tile` is the position-tile size (the split factor of the position
+ *    loop, Section 5 "Split"): the number of stored positions per workgroup.
+ *    0 selects the library default; otherwise it must be one of the sizes
+ *    listed with each operation, else PSK_ERR_TILE.
+ *  - `phases` selects which steps run (bit mask, PSK_PHASE_ALL for a
+ *    complete product).  PSK_PHASE_PARTITION writes the tile->row table into
+ *    the workspace; it depends only on (pos, nnz, tile), so a caller that
+ *    multiplies by the same A again may leave it out.  PSK_PHASE_MAIN streams
+ *    the tiles; PSK_PHASE_FIXUP adds the carries of rows that span tiles.
+ *    A call without PSK_PHASE_FIXUP leaves those rows incomplete (useful
+ *    only for measuring the steps separately).
+ */
+#ifndef PSK_H
+#define PSK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PSK_OK = 0,
+    PSK_ERR_NULL = 1,        /* a required pointer is NULL */
+    PSK_ERR_SIZE = 2,        /* negative size, nnz > 2^31-1, k <= 0, bad leading dimension, bad block size */
+    PSK_ERR_TILE = 3,        /* tile size not supported by this operation */
+    PSK_ERR_WORKSPACE = 4,   /* workspace NULL, misaligned or smaller than psk_workspace_bytes */
+    PSK_ERR_UNSUPPORTED = 5, /* unknown op / variant / phases */
+    PSK_ERR_HIP = 6,         /* the HIP runtime reported an error at launch */
+    PSK_ERR_ALIGNMENT = 7    /* BCSR only: vals (and x for SpMV) must be 16-byte aligned */
+} psk_status;
+
+typedef enum {
+    PSK_OP_SPMV_CSR = 0,
+    PSK_OP_SPMM_CSR = 1,
+    PSK_OP_SPMV_BCSR = 2,
+    PSK_OP_SPMM_BCSR = 3
+} psk_op;
+
+enum { PSK_PHASE_PARTITION = 1, PSK_PHASE_MAIN = 2, PSK_PHASE_FIXUP = 4, PSK_PHASE_ALL = 7 };
+
+/* Row-split (coordinate-space) baselines, Section 8.3 and the appendix schedules
+ * "SpMV Thread per Row on GPU" / "SpMV Warp per Row on GPU". */
+enum { PSK_ROWSPLIT_THREAD_PER_ROW = 0, PSK_ROWSPLIT_WAVE_PER_ROW = 1 };
+
+const char *psk_status_string(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int psk_version(void);
+
+/* Default position-tile size of an operation (what tile = 0 selects); -1 for an unknown op.
+ * For the BCSR operations the unit is blocks. */
+int32_t psk_default_tile(int op);
+
+/* ceil(nnz / tile): number of tiles of the position cut; 0 when nnz <= 0; -1 when tile <= 0. */
+int64_t psk_num_tiles(int64_t nnz, int32_t tile);
+
+/*
+ * Bytes of workspace an operation needs (tile-row table + one carry record per
+ * tile).  `k` is the number of dense columns (ignored for SpMV), `bs` the BCSR
+ * block edge (ignored for CSR), `tile` as passed to the operation (0 = default).
+ * Returns 0 on invalid arguments.  Always at least 256.
+ */
+size_t psk_workspace_bytes(int op, int64_t rows, int64_t nnz, int32_t k, int32_t bs, int32_t tile);
+
+/*
+ * The position cut (Section 3 "tiling the position space"; Section 5 "Split";
+ * Section 6.2: the first coordinate of a tile is found by binary search).
+ *   tile_row[t] = max { i in [0, rows] : pos[i] <= min(t*tile, nnz) },  t = 0 .. ntiles
+ * i.e. for t < ntiles the (non-empty) row that owns the tile's first position, and
+ * tile_row[ntiles] = rows.  tile_row has psk_num_tiles(nnz, tile) + 1 int32 entries.
+ * Any tile >= 1 is accepted here.  nnz = 0 gives the single entry [rows].
+ */
+int psk_partition_csr(int64_t rows, int64_t nnz, const int32_t *pos, int32_t tile, int32_t *tile_row,
+                      void *stream);
+
+/*
+ * y = A x, CSR, position-space schedule (appendix "SPMV on a GPU"): one workgroup
+ * per tile of `tile` positions; coalesced loads of crd/vals, gather of x, products
+ * kept in registers (the schedule's precompute + unroll), reduction per row inside
+ * the tile, one carry record per tile for a row that began in an earlier tile
+ * (instead of the schedule's atomics), carries added by a second small kernel.
+ * x has cols entries, y rows entries.  tile in {0, 256, 512, 1024, 2048, 4096}.
+ */
+int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                 const float *vals, const float *x, float *y, int32_t tile, int phases,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * C = A B, CSR A, position-space schedule (appendix "SPMM on a GPU"): positions are
+ * split over workgroups and waves, the columns of B over the lanes of a wave, the
+ * loop over a wave's positions is innermost.  B is cols x k with row stride ldb
+ * (>= k), C is rows x k with row stride ldc (>= k), both in floats.  Any k >= 1.
+ * tile in {0, 256, 512, 1024, 2048}.
+ */
+int psk_spmm_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                 const float *vals, const float *B, int32_t k, int64_t ldb, float *C, int64_t ldc,
+                 int32_t tile, int phases, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * BCSR (Section 1): brows x bcols blocks of bs x bs floats, nblocks stored blocks;
+ * pos/crd index blocks; the position cut is taken at the block level (Section 3:
+ * a cut may be placed at any level of the hierarchy), `tile` counts blocks.
+ * x has bcols*bs entries, y brows*bs.  bs = 4 only (other sizes: PSK_ERR_UNSUPPORTED).
+ * vals and x must be 16-byte aligned.  tile in {0, 64, 128, 256, 512}.
+ */
+int psk_spmv_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, const int32_t *pos,
+                  const int32_t *crd, const float *vals, const float *x, float *y, int32_t tile,
+                  int phases, void *workspace, size_t workspace_bytes, void *stream);
+
+/* C = A B with BCSR A: B is (bcols*bs) x k, C is (brows*bs) x k.  bs = 4 only.
+ * vals must be 16-byte aligned.  tile in {0, 64, 128, 256, 512}. */
+int psk_spmm_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, const int32_t *pos,
+                  const int32_t *crd, const float *vals, const float *B, int32_t k, int64_t ldb,
+                  float *C, int64_t ldc, int32_t tile, int phases, void *workspace,
+                  size_t workspace_bytes, void *stream);
+
+/*
+ * Coordinate-space baselines (Section 3 "tiling the coordinate space"; Section 8.3):
+ * rows are split over workgroups, no search, unequal work per tile.  No workspace.
+ * variant = PSK_ROWSPLIT_THREAD_PER_ROW or PSK_ROWSPLIT_WAVE_PER_ROW.
+ */
+int psk_spmv_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos,
+                          const int32_t *crd, const float *vals, const float *x, float *y,
+                          int variant, void *stream);
+
+/* Row-split SpMM baseline: one wave per row, lanes over the columns of B. */
+int psk_spmm_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos,
+                          const int32_t *crd, const float *vals, const float *B, int32_t k,
+                          int64_t ldb, float *C, int64_t ldc, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSK_H */

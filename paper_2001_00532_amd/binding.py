@@ -1,0 +1,190 @@
+"""Thin ctypes binding of libpsk.so: argument marshalling only.
+
+Function names match include/psk.h.  Tensors are torch CUDA tensors (device memory and streams are
+PyTorch's only role); every computation happens inside the library's kernels.  There is no CPU
+fallback: a missing library raises at import of this module's first use.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpsk.so")
+
+PSK_OK = 0
+PSK_OP_SPMV_CSR, PSK_OP_SPMM_CSR, PSK_OP_SPMV_BCSR, PSK_OP_SPMM_BCSR = 0, 1, 2, 3
+PSK_PHASE_PARTITION, PSK_PHASE_MAIN, PSK_PHASE_FIXUP, PSK_PHASE_ALL = 1, 2, 4, 7
+PSK_ROWSPLIT_THREAD_PER_ROW, PSK_ROWSPLIT_WAVE_PER_ROW = 0, 1
+
+EXPORTS = [
+    "psk_status_string", "psk_version", "psk_default_tile", "psk_num_tiles", "psk_workspace_bytes",
+    "psk_partition_csr", "psk_spmv_csr", "psk_spmm_csr", "psk_spmv_bcsr", "psk_spmm_bcsr",
+    "psk_spmv_csr_rowsplit", "psk_spmm_csr_rowsplit",
+]
+
+
+class PskError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__("%s failed: status %d (%s)" % (what, status, status_string(status)))
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library.  Raises if it has not been built (python -m paper_2001_00532_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libpsk.so is not built; run `python -m paper_2001_00532_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, i32, p, ci, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        L.psk_status_string.argtypes, L.psk_status_string.restype = [ci], ctypes.c_char_p
+        L.psk_version.argtypes, L.psk_version.restype = [], ci
+        L.psk_default_tile.argtypes, L.psk_default_tile.restype = [ci], i32
+        L.psk_num_tiles.argtypes, L.psk_num_tiles.restype = [i64, i32], i64
+        L.psk_workspace_bytes.argtypes, L.psk_workspace_bytes.restype = [ci, i64, i64, i32, i32, i32], sz
+        L.psk_partition_csr.argtypes, L.psk_partition_csr.restype = [i64, i64, p, i32, p, p], ci
+        L.psk_spmv_csr.argtypes = [i64, i64, i64, p, p, p, p, p, i32, ci, p, sz, p]
+        L.psk_spmv_csr.restype = ci
+        L.psk_spmm_csr.argtypes = [i64, i64, i64, p, p, p, p, i32, i64, p, i64, i32, ci, p, sz, p]
+        L.psk_spmm_csr.restype = ci
+        L.psk_spmv_bcsr.argtypes = [i64, i64, i64, i32, p, p, p, p, p, i32, ci, p, sz, p]
+        L.psk_spmv_bcsr.restype = ci
+        L.psk_spmm_bcsr.argtypes = [i64, i64, i64, i32, p, p, p, p, i32, i64, p, i64, i32, ci, p, sz, p]
+        L.psk_spmm_bcsr.restype = ci
+        L.psk_spmv_csr_rowsplit.argtypes = [i64, i64, i64, p, p, p, p, p, ci, p]
+        L.psk_spmv_csr_rowsplit.restype = ci
+        L.psk_spmm_csr_rowsplit.argtypes = [i64, i64, i64, p, p, p, p, i32, i64, p, i64, p]
+        L.psk_spmm_csr_rowsplit.restype = ci
+        _lib = L
+    return _lib
+
+
+def _ptr(t, dtype=None):
+    """Device pointer of a tensor (None -> NULL).  Checks device, dtype and contiguity of the last dim."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("expected a device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("expected dtype %s, got %s" % (dtype, t.dtype))
+    if t.numel() and t.stride(-1) != 1:
+        raise ValueError("innermost dimension must be contiguous")
+    return ctypes.c_void_p(t.data_ptr()) if t.numel() else ctypes.c_void_p(t.data_ptr() or 0)
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(status: int, what: str):
+    if status != PSK_OK:
+        raise PskError(status, what)
+
+
+def status_string(status: int) -> str:
+    return lib().psk_status_string(int(status)).decode()
+
+
+def psk_version() -> int:
+    return int(lib().psk_version())
+
+
+def psk_default_tile(op: int) -> int:
+    return int(lib().psk_default_tile(int(op)))
+
+
+def psk_num_tiles(nnz: int, tile: int) -> int:
+    return int(lib().psk_num_tiles(int(nnz), int(tile)))
+
+
+def psk_workspace_bytes(op: int, rows: int, nnz: int, k: int = 1, bs: int = 1, tile: int = 0) -> int:
+    return int(lib().psk_workspace_bytes(int(op), int(rows), int(nnz), int(k), int(bs), int(tile)))
+
+
+def workspace(op: int, rows: int, nnz: int, k: int = 1, bs: int = 1, tile: int = 0, device="cuda"):
+    """A byte tensor of the size the operation needs (torch allocations are 256-byte aligned)."""
+    n = psk_workspace_bytes(op, rows, nnz, k, bs, tile)
+    if n == 0:
+        raise ValueError("invalid arguments for psk_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def psk_partition_csr(pos, nnz: int, tile: int, tile_row=None, stream=None):
+    """tile_row (int32, num_tiles+1) for the position cut of `pos` (int32 device tensor, rows+1)."""
+    rows = pos.numel() - 1
+    nt = max(psk_num_tiles(nnz, tile), 0)
+    if tile_row is None:
+        tile_row = torch.empty(nt + 1, dtype=torch.int32, device=pos.device)
+    st = lib().psk_partition_csr(rows, int(nnz), _ptr(pos, torch.int32), int(tile), _ptr(tile_row, torch.int32),
+                                 _stream(stream))
+    _check(st, "psk_partition_csr")
+    return tile_row
+
+
+def psk_spmv_csr(rows, cols, nnz, pos, crd, vals, x, y, tile=0, phases=PSK_PHASE_ALL, ws=None, stream=None):
+    if ws is None:
+        ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=tile, device=pos.device)
+    st = lib().psk_spmv_csr(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
+                            _ptr(vals, torch.float32), _ptr(x, torch.float32), _ptr(y, torch.float32), int(tile),
+                            int(phases), _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, "psk_spmv_csr")
+    return y
+
+
+def psk_spmm_csr(rows, cols, nnz, pos, crd, vals, B, C, tile=0, phases=PSK_PHASE_ALL, ws=None, stream=None):
+    k = B.shape[1]
+    if ws is None:
+        ws = workspace(PSK_OP_SPMM_CSR, rows, nnz, k=k, tile=tile, device=pos.device)
+    st = lib().psk_spmm_csr(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
+                            _ptr(vals, torch.float32), _ptr(B, torch.float32), int(k), int(B.stride(0)),
+                            _ptr(C, torch.float32), int(C.stride(0)), int(tile), int(phases), _ptr(ws),
+                            ws.numel(), _stream(stream))
+    _check(st, "psk_spmm_csr")
+    return C
+
+
+def psk_spmv_bcsr(brows, bcols, nblocks, bs, pos, crd, vals, x, y, tile=0, phases=PSK_PHASE_ALL, ws=None,
+                  stream=None):
+    if ws is None:
+        ws = workspace(PSK_OP_SPMV_BCSR, brows, nblocks, bs=bs, tile=tile, device=pos.device)
+    st = lib().psk_spmv_bcsr(int(brows), int(bcols), int(nblocks), int(bs), _ptr(pos, torch.int32),
+                             _ptr(crd, torch.int32), _ptr(vals, torch.float32), _ptr(x, torch.float32),
+                             _ptr(y, torch.float32), int(tile), int(phases), _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, "psk_spmv_bcsr")
+    return y
+
+
+def psk_spmm_bcsr(brows, bcols, nblocks, bs, pos, crd, vals, B, C, tile=0, phases=PSK_PHASE_ALL, ws=None,
+                  stream=None):
+    k = B.shape[1]
+    if ws is None:
+        ws = workspace(PSK_OP_SPMM_BCSR, brows, nblocks, k=k, bs=bs, tile=tile, device=pos.device)
+    st = lib().psk_spmm_bcsr(int(brows), int(bcols), int(nblocks), int(bs), _ptr(pos, torch.int32),
+                             _ptr(crd, torch.int32), _ptr(vals, torch.float32), _ptr(B, torch.float32), int(k),
+                             int(B.stride(0)), _ptr(C, torch.float32), int(C.stride(0)), int(tile), int(phases),
+                             _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, "psk_spmm_bcsr")
+    return C
+
+
+def psk_spmv_csr_rowsplit(rows, cols, nnz, pos, crd, vals, x, y, variant=PSK_ROWSPLIT_WAVE_PER_ROW, stream=None):
+    st = lib().psk_spmv_csr_rowsplit(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
+                                     _ptr(vals, torch.float32), _ptr(x, torch.float32), _ptr(y, torch.float32),
+                                     int(variant), _stream(stream))
+    _check(st, "psk_spmv_csr_rowsplit")
+    return y
+
+
+def psk_spmm_csr_rowsplit(rows, cols, nnz, pos, crd, vals, B, C, stream=None):
+    st = lib().psk_spmm_csr_rowsplit(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
+                                     _ptr(vals, torch.float32), _ptr(B, torch.float32), int(B.shape[1]),
+                                     int(B.stride(0)), _ptr(C, torch.float32), int(C.stride(0)), _stream(stream))
+    _check(st, "psk_spmm_csr_rowsplit")
+    return C

@@ -1,0 +1,235 @@
+// C-ABI layer: argument validation, workspace carving, phase dispatch.  No kernels here.
+#include "../../include/psk.h"
+#include "psk_internal.h"
+
+using namespace psk;
+
+namespace {
+
+constexpr int64_t kMaxI32 = 2147483647ll;
+
+int32_t default_tile(int op)
+{
+    switch (op) {
+        case PSK_OP_SPMV_CSR: return 2048;
+        case PSK_OP_SPMM_CSR: return 1024;
+        case PSK_OP_SPMV_BCSR: return 256;
+        case PSK_OP_SPMM_BCSR: return 256;
+        default: return -1;
+    }
+}
+
+bool tile_ok(int op, int32_t tile)
+{
+    switch (op) {
+        case PSK_OP_SPMV_CSR: return spmv_csr_tile_ok(tile);
+        case PSK_OP_SPMM_CSR: return spmm_csr_tile_ok(tile);
+        case PSK_OP_SPMV_BCSR:
+        case PSK_OP_SPMM_BCSR: return bcsr_tile_ok(tile);
+        default: return false;
+    }
+}
+
+int64_t carry_width(int op, int32_t k, int32_t bs)
+{
+    switch (op) {
+        case PSK_OP_SPMV_CSR: return 1;
+        case PSK_OP_SPMM_CSR: return k;
+        case PSK_OP_SPMV_BCSR: return bs;
+        case PSK_OP_SPMM_BCSR: return (int64_t)bs * k;
+        default: return 0;
+    }
+}
+
+// Common checks of the sparse operand and the execution arguments.  On success *tile holds the
+// effective tile size and *ws the carved workspace.
+int check_common(int op, int64_t rows, int64_t cols, int64_t nnz, const void *pos, const void *crd,
+                 const void *vals, int32_t k, int32_t bs, int32_t *tile, int phases, void *workspace,
+                 size_t workspace_bytes, Workspace *ws)
+{
+    if (rows < 0 || cols < 0 || nnz < 0 || nnz > kMaxI32 || rows > kMaxI32 - 1 || cols > kMaxI32) return PSK_ERR_SIZE;
+    if (nnz > 0 && (rows == 0 || cols == 0)) return PSK_ERR_SIZE;
+    if (!pos) return PSK_ERR_NULL;
+    if (nnz > 0 && (!crd || !vals)) return PSK_ERR_NULL;
+    if (phases <= 0 || (phases & ~PSK_PHASE_ALL)) return PSK_ERR_UNSUPPORTED;
+    if (*tile == 0) *tile = default_tile(op);
+    if (!tile_ok(op, *tile)) return PSK_ERR_TILE;
+    const size_t need = psk_workspace_bytes(op, rows, nnz, k, bs, *tile);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < need) return PSK_ERR_WORKSPACE;
+    const int64_t ntiles = psk_num_tiles(nnz, *tile);
+    *ws = carve(workspace, ntiles, carry_width(op, k, bs));
+    return PSK_OK;
+}
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? PSK_OK : PSK_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char *psk_status_string(int status)
+{
+    switch (status) {
+        case PSK_OK: return "ok";
+        case PSK_ERR_NULL: return "a required pointer is NULL";
+        case PSK_ERR_SIZE: return "invalid size argument";
+        case PSK_ERR_TILE: return "unsupported position-tile size";
+        case PSK_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case PSK_ERR_UNSUPPORTED: return "unsupported operation, variant or phase mask";
+        case PSK_ERR_HIP: return "HIP runtime error at kernel launch";
+        case PSK_ERR_ALIGNMENT: return "operand not 16-byte aligned";
+        default: return "unknown status";
+    }
+}
+
+int psk_version(void) { return 100; }
+
+int32_t psk_default_tile(int op) { return default_tile(op); }
+
+int64_t psk_num_tiles(int64_t nnz, int32_t tile)
+{
+    if (tile <= 0) return -1;
+    return nnz <= 0 ? 0 : (nnz + tile - 1) / tile;
+}
+
+size_t psk_workspace_bytes(int op, int64_t rows, int64_t nnz, int32_t k, int32_t bs, int32_t tile)
+{
+    (void)rows;
+    if (tile == 0) tile = default_tile(op);
+    if (tile <= 0 || nnz < 0 || nnz > kMaxI32) return 0;
+    if ((op == PSK_OP_SPMM_CSR || op == PSK_OP_SPMM_BCSR) && k <= 0) return 0;
+    if ((op == PSK_OP_SPMV_BCSR || op == PSK_OP_SPMM_BCSR) && bs <= 0) return 0;
+    const int64_t width = carry_width(op, k, bs);
+    if (width <= 0) return 0;
+    return carve(nullptr, psk_num_tiles(nnz, tile), width).bytes;
+}
+
+int psk_partition_csr(int64_t rows, int64_t nnz, const int32_t *pos, int32_t tile, int32_t *tile_row,
+                      void *stream)
+{
+    if (rows < 0 || nnz < 0 || nnz > kMaxI32 || rows > kMaxI32 - 1) return PSK_ERR_SIZE;
+    if (tile <= 0) return PSK_ERR_TILE;
+    if (!pos || !tile_row) return PSK_ERR_NULL;
+    return hip_status(launch_partition(rows, nnz, pos, tile, tile_row, static_cast<hipStream_t>(stream)));
+}
+
+int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                 const float *vals, const float *x, float *y, int32_t tile, int phases, void *workspace,
+                 size_t workspace_bytes, void *stream)
+{
+    Workspace ws;
+    int st = check_common(PSK_OP_SPMV_CSR, rows, cols, nnz, pos, crd, vals, 1, 1, &tile, phases, workspace,
+                          workspace_bytes, &ws);
+    if (st != PSK_OK) return st;
+    if ((rows > 0 && !y) || (nnz > 0 && !x)) return PSK_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int32_t ntiles = (int32_t)psk_num_tiles(nnz, tile);
+    hipError_t e = hipSuccess;
+    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, ws.tile_row, s);
+    if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
+        if (ntiles == 0) e = launch_fill_zero(y, rows, s);
+        else e = launch_spmv_csr_main((int32_t)rows, (int32_t)nnz, pos, crd, vals, x, y, tile, ws, s);
+    }
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, 1, 1, ws, y, s);
+    return hip_status(e);
+}
+
+int psk_spmm_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                 const float *vals, const float *B, int32_t k, int64_t ldb, float *C, int64_t ldc,
+                 int32_t tile, int phases, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (k <= 0 || ldb < k || ldc < k) return PSK_ERR_SIZE;
+    Workspace ws;
+    int st = check_common(PSK_OP_SPMM_CSR, rows, cols, nnz, pos, crd, vals, k, 1, &tile, phases, workspace,
+                          workspace_bytes, &ws);
+    if (st != PSK_OK) return st;
+    if ((rows > 0 && !C) || (nnz > 0 && !B)) return PSK_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int32_t ntiles = (int32_t)psk_num_tiles(nnz, tile);
+    hipError_t e = hipSuccess;
+    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, ws.tile_row, s);
+    if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
+        if (ntiles == 0) {
+            if (ldc == k) e = launch_fill_zero(C, rows * (int64_t)k, s);
+            else for (int64_t r = 0; r < rows && e == hipSuccess; ++r) e = launch_fill_zero(C + r * ldc, k, s);
+        } else {
+            e = launch_spmm_csr_main((int32_t)rows, (int32_t)nnz, pos, crd, vals, B, k, ldb, C, ldc, tile, ws, s);
+        }
+    }
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, k, ldc, ws, C, s);
+    return hip_status(e);
+}
+
+int psk_spmv_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, const int32_t *pos,
+                  const int32_t *crd, const float *vals, const float *x, float *y, int32_t tile, int phases,
+                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (bs != 4) return bs <= 0 ? PSK_ERR_SIZE : PSK_ERR_UNSUPPORTED;
+    if (brows > (kMaxI32 - 1) / bs || bcols > kMaxI32 / bs || nblocks > kMaxI32 / (bs * bs)) return PSK_ERR_SIZE;
+    Workspace ws;
+    int st = check_common(PSK_OP_SPMV_BCSR, brows, bcols, nblocks, pos, crd, vals, 1, bs, &tile, phases,
+                          workspace, workspace_bytes, &ws);
+    if (st != PSK_OK) return st;
+    if ((brows > 0 && !y) || (nblocks > 0 && !x)) return PSK_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(vals) | reinterpret_cast<uintptr_t>(x)) & 15) return PSK_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int32_t ntiles = (int32_t)psk_num_tiles(nblocks, tile);
+    hipError_t e = hipSuccess;
+    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(brows, nblocks, pos, tile, ws.tile_row, s);
+    if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
+        if (ntiles == 0) e = launch_fill_zero(y, brows * bs, s);
+        else e = launch_spmv_bcsr4_main((int32_t)brows, (int32_t)nblocks, pos, crd, vals, x, y, tile, ws, s);
+    }
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, bs, bs, ws, y, s);
+    return hip_status(e);
+}
+
+int psk_spmm_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, const int32_t *pos,
+                  const int32_t *crd, const float *vals, const float *B, int32_t k, int64_t ldb, float *C,
+                  int64_t ldc, int32_t tile, int phases, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (bs != 4) return bs <= 0 ? PSK_ERR_SIZE : PSK_ERR_UNSUPPORTED;
+    if (k <= 0 || ldb < k || ldc < k) return PSK_ERR_SIZE;
+    if (brows > (kMaxI32 - 1) / bs || bcols > kMaxI32 / bs || nblocks > kMaxI32 / (bs * bs)) return PSK_ERR_SIZE;
+    Workspace ws;
+    int st = check_common(PSK_OP_SPMM_BCSR, brows, bcols, nblocks, pos, crd, vals, k, bs, &tile, phases,
+                          workspace, workspace_bytes, &ws);
+    if (st != PSK_OK) return st;
+    if ((brows > 0 && !C) || (nblocks > 0 && !B)) return PSK_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(vals) & 15) return PSK_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int32_t ntiles = (int32_t)psk_num_tiles(nblocks, tile);
+    hipError_t e = hipSuccess;
+    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(brows, nblocks, pos, tile, ws.tile_row, s);
+    if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
+        if (ntiles == 0) {
+            if (ldc == k) e = launch_fill_zero(C, brows * bs * (int64_t)k, s);
+            else for (int64_t r = 0; r < brows * bs && e == hipSuccess; ++r) e = launch_fill_zero(C + r * ldc, k, s);
+        } else {
+            e = launch_spmm_bcsr4_main((int32_t)brows, (int32_t)nblocks, pos, crd, vals, B, k, ldb, C, ldc, tile, ws, s);
+        }
+    }
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, bs, k, ldc, ws, C, s);
+    return hip_status(e);
+}
+
+int psk_spmv_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                          const float *vals, const float *x, float *y, int variant, void *stream)
+{
+    if (rows < 0 || cols < 0 || nnz < 0 || nnz > kMaxI32 || rows > kMaxI32 - 1) return PSK_ERR_SIZE;
+    if (variant != PSK_ROWSPLIT_THREAD_PER_ROW && variant != PSK_ROWSPLIT_WAVE_PER_ROW) return PSK_ERR_UNSUPPORTED;
+    if (!pos || (rows > 0 && !y) || (nnz > 0 && (!crd || !vals || !x))) return PSK_ERR_NULL;
+    return hip_status(launch_spmv_rowsplit((int32_t)rows, pos, crd, vals, x, y, variant, static_cast<hipStream_t>(stream)));
+}
+
+int psk_spmm_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                          const float *vals, const float *B, int32_t k, int64_t ldb, float *C, int64_t ldc,
+                          void *stream)
+{
+    if (rows < 0 || cols < 0 || nnz < 0 || nnz > kMaxI32 || rows > kMaxI32 - 1) return PSK_ERR_SIZE;
+    if (k <= 0 || ldb < k || ldc < k) return PSK_ERR_SIZE;
+    if (!pos || (rows > 0 && !C) || (nnz > 0 && (!crd || !vals || !B))) return PSK_ERR_NULL;
+    return hip_status(launch_spmm_rowsplit((int32_t)rows, pos, crd, vals, B, k, ldb, C, ldc, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,59 @@
+// Device-side helpers shared by the kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace psk {
+
+constexpr int WAVE = 64;
+constexpr int NUM_XCD = 8;   // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
+
+typedef int   v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+
+// Streamed-once data (crd, vals): mark the loads non-temporal so they do not push
+// the gathered operand out of L2.
+template <typename T>
+__device__ __forceinline__ T ld_stream(const T *p) { return __builtin_nontemporal_load(p); }
+
+// DPP cross-lane move inside a row of 16 lanes; CTRL is the dpp_ctrl immediate.
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+// Sum over the 64 lanes of a wave; every lane receives the same bits.
+// Butterfly: quad_perm xor1, quad_perm xor2, row_half_mirror, row_mirror (DPP),
+// then xor16 / xor32 through the LDS crossbar.
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += dpp_mov<0xB1>(v);    // quad_perm [1,0,3,2]
+    v += dpp_mov<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_mov<0x141>(v);   // row_half_mirror
+    v += dpp_mov<0x140>(v);   // row_mirror
+    v += __shfl_xor(v, 16, WAVE);
+    v += __shfl_xor(v, 32, WAVE);
+    return v;
+}
+
+// Tile handled by a workgroup.  Workgroup b runs on die b % 8; give every die one
+// contiguous eighth of the tiles so that the part of the dense operand a die
+// gathers stays in that die's L2.  Returns -1 for the padding workgroups.
+__device__ __forceinline__ int xcd_tile(int bid, int ntiles)
+{
+    const int per = (ntiles + NUM_XCD - 1) / NUM_XCD;
+    const int t = (bid % NUM_XCD) * per + bid / NUM_XCD;
+    return (bid / NUM_XCD < per && t < ntiles) ? t : -1;
+}
+__host__ __device__ __forceinline__ int xcd_grid(int ntiles) { return ((ntiles + NUM_XCD - 1) / NUM_XCD) * NUM_XCD; }
+
+// LDS index skew: one group of `W` words of padding after every 32 words, so that
+// per-lane runs whose starts are a multiple of 8/16/32 words apart spread over the banks.
+template <int W>
+__device__ __forceinline__ int skew(int i) { return i + (i >> 5) * W; }
+template <int W>
+constexpr int skewed_size(int n) { return n + ((n + 31) >> 5) * W; }
+
+}  // namespace psk

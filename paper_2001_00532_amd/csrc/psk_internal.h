@@ -1,0 +1,67 @@
+// Host-side declarations shared between the C-ABI layer (api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace psk {
+
+// Workspace carving: [tile_row: ntiles+1 int32][carry_row: ntiles int32][carry_val: ntiles*width float],
+// each part starting on a 256-byte boundary.
+struct Workspace {
+    int32_t *tile_row;
+    int32_t *carry_row;
+    float   *carry_val;
+    size_t   bytes;
+};
+inline size_t align256(size_t n) { return (n + 255) & ~size_t(255); }
+inline Workspace carve(void *base, int64_t ntiles, int64_t width)
+{
+    Workspace w;
+    char *p = static_cast<char *>(base);
+    size_t a = align256(size_t(ntiles + 1) * 4), b = align256(size_t(ntiles) * 4 + 4),
+           c = align256(size_t(ntiles) * size_t(width) * 4 + 4);
+    w.tile_row = reinterpret_cast<int32_t *>(p);
+    w.carry_row = reinterpret_cast<int32_t *>(p + a);
+    w.carry_val = reinterpret_cast<float *>(p + a + b);
+    w.bytes = a + b + c;
+    return w;
+}
+
+// Every launcher enqueues on `s` and returns hipGetLastError() of its launches.
+
+hipError_t launch_partition(int64_t rows, int64_t nnz, const int32_t *pos, int32_t tile, int32_t *tile_row,
+                            hipStream_t s);
+hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s);
+// Adds the per-tile carry records to the output: element e of a record of `nsub*k` floats goes to
+// out[(row*nsub + e / k) * ld + e % k].
+hipError_t launch_carry_fixup(int32_t ntiles, int32_t nsub, int32_t k, int64_t ld, const Workspace &w,
+                              float *out, hipStream_t s);
+
+// CSR SpMV
+bool spmv_csr_tile_ok(int32_t tile);
+hipError_t launch_spmv_csr_main(int32_t rows, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                                const float *vals, const float *x, float *y, int32_t tile,
+                                const Workspace &w, hipStream_t s);
+hipError_t launch_spmv_rowsplit(int32_t rows, const int32_t *pos, const int32_t *crd, const float *vals,
+                                const float *x, float *y, int variant, hipStream_t s);
+
+// CSR SpMM
+bool spmm_csr_tile_ok(int32_t tile);
+hipError_t launch_spmm_csr_main(int32_t rows, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                                const float *vals, const float *B, int32_t k, int64_t ldb, float *C,
+                                int64_t ldc, int32_t tile, const Workspace &w, hipStream_t s);
+hipError_t launch_spmm_rowsplit(int32_t rows, const int32_t *pos, const int32_t *crd, const float *vals,
+                                const float *B, int32_t k, int64_t ldb, float *C, int64_t ldc,
+                                hipStream_t s);
+
+// BCSR (bs = 4)
+bool bcsr_tile_ok(int32_t tile);
+hipError_t launch_spmv_bcsr4_main(int32_t brows, int32_t nblocks, const int32_t *pos, const int32_t *crd,
+                                  const float *vals, const float *x, float *y, int32_t tile,
+                                  const Workspace &w, hipStream_t s);
+hipError_t launch_spmm_bcsr4_main(int32_t brows, int32_t nblocks, const int32_t *pos, const int32_t *crd,
+                                  const float *vals, const float *B, int32_t k, int64_t ldb, float *C,
+                                  int64_t ldc, int32_t tile, const Workspace &w, hipStream_t s);
+
+}  // namespace psk
