@@ -1,0 +1,315 @@
+#!/usr/bin/env python3
+"""Benchmark of the position-space sparse x dense path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--tile T]
+
+A step is one complete product through the C ABI: position cut, tile kernel, carry fix-up.  Inputs
+are synthetic, seeded, resident in HBM before the timed region.  One JSON line is printed:
+whole-job throughput (`value`, GFLOP/s = 2*nnz*k / time), the roofline record of the dominant
+kernel (algorithmic bytes / its own event-timed duration, against 8 TB/s) and the CPU oracle timed
+on the host cores of the same machine.
+
+Workloads (names of the evaluated configurations):
+  powerlaw (default)  CSR SpMV, 2M x 2M, truncated Zipf(1.8) row lengths in [1, 200000]
+  stencil             CSR SpMV, 27-point stencil on 160^3
+  uniform10           CSR SpMV, 1024 x 1024, 10 per row (launch-latency bound)
+  spmm                CSR SpMM, 1M x 1M with 16 per row, B 1M x 128
+  bcsr_spmv           BCSR 4x4 SpMV, 250k x 250k blocks, 8 blocks per block row
+  bcsr_spmm           BCSR 4x4 SpMM with 64 dense columns
+  uniform28           CSR SpMV, 2M x 2M, exactly 28 per row at uniform random columns (the uniform
+                      matrix of the power-law matrix's size class, for the per-nnz comparison)
+  copy                not a product: a plain device copy of 1 GiB, the calibration kernel for the
+                      rocprofv3 FETCH_SIZE / WRITE_SIZE counters and the practical HBM ceiling
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
+# scaled by the copy-kernel calibration; the summaries are under profiles/.  None = not measured.
+MEASURED_TRAFFIC_BYTES = {
+}
+
+WORKLOADS = {
+    "uniform10": (1, "csr_spmv"),
+    "powerlaw": (2, "csr_spmv"),
+    "stencil": (3, "csr_spmv"),
+    "spmm": (4, "csr_spmm"),
+    "bcsr_spmv": (5, "bcsr_spmv"),
+    "bcsr_spmm": (5, "bcsr_spmm"),
+    "uniform28": (0, "csr_spmv"),
+    "copy": (0, "copy"),
+}
+
+
+def algorithmic_bytes(kind, A, k):
+    """Bytes the method must move once: the sparse operand, the dense operand once, the output once.
+    For SpMM / BCSR SpMM the second figure charges one dense row per stored position (no reuse)."""
+    rows, cols, nnz = A.rows, A.cols, A.nnz
+    if kind == "csr_spmv":
+        b = 8 * nnz + 4 * (rows + 1) + 4 * cols + 4 * rows
+        return b, b
+    if kind == "csr_spmm":
+        a = 8 * nnz + 4 * (rows + 1)
+        return a + 4 * k * cols + 4 * k * rows, a + 4 * k * nnz + 4 * k * rows
+    if kind == "bcsr_spmv":
+        b = 68 * nnz + 4 * (rows + 1) + 16 * cols + 16 * rows
+        return b, b
+    if kind == "bcsr_spmm":
+        a = 68 * nnz + 4 * (rows + 1)
+        return a + 16 * k * cols + 16 * k * rows, a + 16 * k * nnz + 16 * k * rows
+    raise ValueError(kind)
+
+
+def flops(kind, A, k):
+    per = 2 * (A.bs * A.bs)
+    return per * A.nnz * (k if kind.endswith("spmm") else 1)
+
+
+def bench_copy(args, torch):
+    """Plain copy of 2^28 floats (1 GiB read + 1 GiB written per launch) with torch's copy kernel."""
+    n = 1 << 28
+    src = torch.ones(n, device="cuda:0")
+    dst = torch.empty(n, device="cuda:0")
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(args.steps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        dst.copy_(src)
+        e1.record(stream)
+        e1.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    avg = sum(ts) / len(ts)
+    print(json.dumps({"metric": "device copy GB/s (read + written bytes)", "value": round(8.0 * n / (avg * 1e-3) / 1e9, 2),
+                      "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                      "ms_per_step": round(avg, 6), "bytes_read": 4 * n, "bytes_written": 4 * n,
+                      "config": {"workload": "copy: 2^28 fp32 elements, torch copy kernel"}}))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="powerlaw", choices=sorted(WORKLOADS))
+    ap.add_argument("--tile", type=int, default=0, help="position-tile size (0 = library default)")
+    ap.add_argument("--copies", type=int, default=0, help="operand copies rotated between steps (0 = auto)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--baselines", action="store_true", help="also time the row-split kernels")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.stderr.write("bench.py: this build is single-GPU (no sharding, no collectives); run with --gpus 1\n")
+        sys.exit(2)
+
+    import torch
+
+    import paper_2001_00532_amd as psk
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible\n")
+        sys.exit(1)
+    psk.lib()   # fail loudly when the HIP library is missing
+
+    cfg_no, kind = WORKLOADS[args.workload]
+    if kind == "copy":
+        return bench_copy(args, torch)
+    t_gen = time.time()
+    if args.workload == "uniform28":
+        A28 = wl.csr_uniform(2_000_000, 2_000_000, 28, wl.BASE_SEED + 6)
+        cfg = {"A": A28, "x": wl.dense_uniform(2_000_000, wl.BASE_SEED + 6, wl.S_X)}
+    else:
+        cfg = wl.config(cfg_no)
+    A = cfg["A"]
+    k = cfg.get("k", 1) if kind.endswith("spmm") else 1
+    dense_h = cfg["B"] if kind.endswith("spmm") else cfg["x"]
+    t_gen = time.time() - t_gen
+    out_rows = A.rows * A.bs
+    L = np.diff(A.pos)
+    comp_bytes, noreuse_bytes = algorithmic_bytes(kind, A, k)
+    fl = flops(kind, A, k)
+
+    op = {"csr_spmv": psk.PSK_OP_SPMV_CSR, "csr_spmm": psk.PSK_OP_SPMM_CSR, "bcsr_spmv": psk.PSK_OP_SPMV_BCSR,
+          "bcsr_spmm": psk.PSK_OP_SPMM_BCSR}[kind]
+    tile = args.tile or psk.psk_default_tile(op)
+
+    # rotate over enough operand copies that a step never finds its inputs in the 256 MB memory-side cache
+    copies = args.copies or max(2, min(8, int(np.ceil(1.0e9 / comp_bytes))))
+    dev = torch.device("cuda:0")
+    sets = []
+    for _ in range(copies):
+        s = {"pos": torch.from_numpy(A.pos).to(dev), "crd": torch.from_numpy(A.crd).to(dev),
+             "vals": torch.from_numpy(A.vals).to(dev), "dense": torch.from_numpy(dense_h).to(dev)}
+        s["out"] = torch.empty((out_rows, k) if kind.endswith("spmm") else (out_rows,), device=dev)
+        s["ws"] = psk.workspace(op, A.rows, A.nnz, k=k, bs=A.bs, tile=tile, device=dev)
+        sets.append(s)
+    stream = torch.cuda.current_stream()
+
+    def step(s, phases=psk.PSK_PHASE_ALL):
+        if kind == "csr_spmv":
+            psk.psk_spmv_csr(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"], tile=tile,
+                             phases=phases, ws=s["ws"], stream=stream)
+        elif kind == "csr_spmm":
+            psk.psk_spmm_csr(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"], tile=tile,
+                             phases=phases, ws=s["ws"], stream=stream)
+        elif kind == "bcsr_spmv":
+            psk.psk_spmv_bcsr(A.rows, A.cols, A.nnz, 4, s["pos"], s["crd"], s["vals"], s["dense"], s["out"],
+                              tile=tile, phases=phases, ws=s["ws"], stream=stream)
+        else:
+            psk.psk_spmm_bcsr(A.rows, A.cols, A.nnz, 4, s["pos"], s["crd"], s["vals"], s["dense"], s["out"],
+                              tile=tile, phases=phases, ws=s["ws"], stream=stream)
+
+    # ---- warm-up, then exactly K timed steps bracketed by synchronize
+    for i in range(args.warmup):
+        step(sets[i % copies])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(sets[i % copies])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+
+    # ---- the phases on their own, HIP events on the stream the kernels run on (median of 16, 8 warm-ups)
+    def time_phase(phases, reps=16, warm=8):
+        ts = []
+        for i in range(warm + reps):
+            s = sets[i % copies]
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            step(s, phases)
+            e1.record(stream)
+            e1.synchronize()
+            if i >= warm:
+                ts.append(e0.elapsed_time(e1))
+        return ts
+
+    main_ms = time_phase(psk.PSK_PHASE_MAIN)
+    part_ms = time_phase(psk.PSK_PHASE_PARTITION)
+    fix_ms = time_phase(psk.PSK_PHASE_FIXUP)
+    all_ms = time_phase(psk.PSK_PHASE_ALL)
+    main_avg = sum(main_ms) / len(main_ms)
+    kernel_bytes = noreuse_bytes if kind.endswith("spmm") else comp_bytes
+    achieved = kernel_bytes / (main_avg * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, tile))
+
+    rec = {
+        "metric": "SpMV/SpMM GFLOP/s and achieved HBM GB/s (% of MI355X peak), 1 GPU",
+        "value": round(fl / (wall / args.steps) / 1e9, 3),
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "%s: %s, %d x %d%s, nnz %d (max row %d, mean %.2f), tile %d, k %d, %d operand copies rotated"
+                        % (args.workload, kind, A.rows * A.bs, A.cols * A.bs, " in 4x4 blocks" if A.bs > 1 else "",
+                           A.nnz * A.bs * A.bs, int(L.max()) if L.size else 0, float(L.mean()) if L.size else 0.0,
+                           tile, k, copies),
+            "rows": A.rows * A.bs, "cols": A.cols * A.bs, "nnz": A.nnz * A.bs * A.bs, "k": k, "tile": tile,
+            "seed": wl.BASE_SEED + cfg_no,
+        },
+        "gbps_algorithmic_whole_step": round(comp_bytes / (wall / args.steps) / 1e9, 2),
+        "pct_of_hbm_peak_whole_step": round(100.0 * comp_bytes / (wall / args.steps) / 1e9 / HBM_PEAK_GBS, 2),
+        "ns_per_nnz": round(wall / args.steps * 1e9 / max(1, A.nnz * A.bs * A.bs), 6),
+        "phases_us_median": {
+            "partition": round(statistics.median(part_ms) * 1e3, 2),
+            "main": round(statistics.median(main_ms) * 1e3, 2),
+            "fixup": round(statistics.median(fix_ms) * 1e3, 2),
+            "all": round(statistics.median(all_ms) * 1e3, 2),
+            "all_min": round(min(all_ms) * 1e3, 2),
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": {"csr_spmv": "k_spmv_pos", "csr_spmm": "k_spmm_pos<1,*>", "bcsr_spmv": "k_spmv_bcsr4",
+                       "bcsr_spmm": "k_spmm_pos<4,*>"}[kind],
+            "achieved": round(achieved, 2),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": traffic,
+            "algorithmic_bytes": kernel_bytes,
+            "avg_launch_us": round(main_avg * 1e3, 2),
+            "byte_model": ("one dense row per stored position (no reuse)" if kind.endswith("spmm")
+                           else "A once + dense operand once + output once"),
+        },
+    }
+
+    if args.baselines and kind == "csr_spmv":
+        base = {}
+        for name, variant in (("thread_per_row", 0), ("wave_per_row", 1)):
+            ts = []
+            for i in range(12):
+                s = sets[i % copies]
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                psk.psk_spmv_csr_rowsplit(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"],
+                                          variant=variant, stream=stream)
+                e1.record(stream)
+                e1.synchronize()
+                if i >= 4:
+                    ts.append(e0.elapsed_time(e1))
+            base[name + "_us_median"] = round(statistics.median(ts) * 1e3, 2)
+        rec["rowsplit_baselines"] = base
+
+    # ---- the CPU oracle on this machine's host cores (a baseline, not a target)
+    if not args.no_cpu:
+        import oracle
+
+        cores = oracle.threads_used(len(os.sched_getaffinity(0)))
+        sel = None
+        sample = "full workload"
+        if kind == "csr_spmm":
+            sel = np.arange(0, A.rows, 8, dtype=np.int64)           # every 8th row
+            sample = "every 8th row of the workload (1/8 of the flops)"
+        elif kind == "bcsr_spmm":
+            sel = np.arange(0, A.rows, 4, dtype=np.int64)
+            sample = "every 4th block row of the workload (1/4 of the flops)"
+        frac = 1.0 if sel is None else len(sel) / A.rows
+
+        def run_oracle():
+            if kind == "csr_spmv":
+                oracle.spmv_csr(A.pos, A.crd, A.vals, dense_h, threads=cores)
+            elif kind == "csr_spmm":
+                oracle.spmm_csr(A.pos, A.crd, A.vals, dense_h, sel=sel, threads=cores)
+            elif kind == "bcsr_spmv":
+                oracle.spmv_bcsr(A.pos, A.crd, A.vals, dense_h, 4, threads=cores)
+            else:
+                oracle.spmm_bcsr(A.pos, A.crd, A.vals, dense_h, 4, sel=sel, threads=cores)
+
+        run_oracle()
+        ts = []
+        for _ in range(3):
+            t = time.perf_counter()
+            run_oracle()
+            ts.append(time.perf_counter() - t)
+        tmed = statistics.median(ts)
+        rec["cpu_baseline"] = {
+            "value": round(fl * frac / tmed / 1e9, 3),
+            "unit": "GFLOP/s",
+            "cores": cores,
+            "kind": "oracle",
+            "sample": "%s, fp64 accumulation, OpenMP over rows, 1 warm-up + 3 runs, median %.3f s" % (sample, tmed),
+        }
+    rec["generate_s"] = round(t_gen, 2)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

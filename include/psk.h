@@ -76,6 +76,10 @@ typedef enum {
 
 enum { PSK_PHASE_PARTITION = 1, PSK_PHASE_MAIN = 2, PSK_PHASE_FIXUP = 4, PSK_PHASE_ALL = 7 };
 
+/* How psk_partition_csr locates the tile starts (Section 5, "Divide": an O(log n) search per tile or an
+ * O(n) walk).  Both give the same table. */
+enum { PSK_PARTITION_AUTO = 0, PSK_PARTITION_SEARCH = 1, PSK_PARTITION_SCAN = 2 };
+
 /* Row-split (coordinate-space) baselines, Section 8.3 and the appendix schedules
  * "SpMV Thread per Row on GPU" / "SpMV Warp per Row on GPU". */
 enum { PSK_ROWSPLIT_THREAD_PER_ROW = 0, PSK_ROWSPLIT_WAVE_PER_ROW = 1 };
@@ -107,9 +111,13 @@ size_t psk_workspace_bytes(int op, int64_t rows, int64_t nnz, int32_t k, int32_t
  * i.e. for t < ntiles the (non-empty) row that owns the tile's first position, and
  * tile_row[ntiles] = rows.  tile_row has psk_num_tiles(nnz, tile) + 1 int32 entries.
  * Any tile >= 1 is accepted here.  nnz = 0 gives the single entry [rows].
+ * method: PSK_PARTITION_SEARCH runs one binary search over pos per table entry;
+ * PSK_PARTITION_SCAN reads pos once and lets every non-empty row write the entries of the tile
+ * starts it contains (no dependent loads; faster unless pos is very large and the tiles are few);
+ * PSK_PARTITION_AUTO picks one from rows and the number of tiles.  The operations below use AUTO.
  */
-int psk_partition_csr(int64_t rows, int64_t nnz, const int32_t *pos, int32_t tile, int32_t *tile_row,
-                      void *stream);
+int psk_partition_csr(int64_t rows, int64_t nnz, const int32_t *pos, int32_t tile, int method,
+                      int32_t *tile_row, void *stream);
 
 /*
  * y = A x, CSR, position-space schedule (appendix "SPMV on a GPU"): one workgroup

@@ -48,7 +48,7 @@ def lib() -> ctypes.CDLL:
         L.psk_default_tile.argtypes, L.psk_default_tile.restype = [ci], i32
         L.psk_num_tiles.argtypes, L.psk_num_tiles.restype = [i64, i32], i64
         L.psk_workspace_bytes.argtypes, L.psk_workspace_bytes.restype = [ci, i64, i64, i32, i32, i32], sz
-        L.psk_partition_csr.argtypes, L.psk_partition_csr.restype = [i64, i64, p, i32, p, p], ci
+        L.psk_partition_csr.argtypes, L.psk_partition_csr.restype = [i64, i64, p, i32, ci, p, p], ci
         L.psk_spmv_csr.argtypes = [i64, i64, i64, p, p, p, p, p, i32, ci, p, sz, p]
         L.psk_spmv_csr.restype = ci
         L.psk_spmm_csr.argtypes = [i64, i64, i64, p, p, p, p, i32, i64, p, i64, i32, ci, p, sz, p]
@@ -116,14 +116,17 @@ def workspace(op: int, rows: int, nnz: int, k: int = 1, bs: int = 1, tile: int =
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
-def psk_partition_csr(pos, nnz: int, tile: int, tile_row=None, stream=None):
+PSK_PARTITION_AUTO, PSK_PARTITION_SEARCH, PSK_PARTITION_SCAN = 0, 1, 2
+
+
+def psk_partition_csr(pos, nnz: int, tile: int, method: int = 0, tile_row=None, stream=None):
     """tile_row (int32, num_tiles+1) for the position cut of `pos` (int32 device tensor, rows+1)."""
     rows = pos.numel() - 1
     nt = max(psk_num_tiles(nnz, tile), 0)
     if tile_row is None:
         tile_row = torch.empty(nt + 1, dtype=torch.int32, device=pos.device)
-    st = lib().psk_partition_csr(rows, int(nnz), _ptr(pos, torch.int32), int(tile), _ptr(tile_row, torch.int32),
-                                 _stream(stream))
+    st = lib().psk_partition_csr(rows, int(nnz), _ptr(pos, torch.int32), int(tile), int(method),
+                                 _ptr(tile_row, torch.int32), _stream(stream))
     _check(st, "psk_partition_csr")
     return tile_row
 

@@ -104,13 +104,14 @@ size_t psk_workspace_bytes(int op, int64_t rows, int64_t nnz, int32_t k, int32_t
     return carve(nullptr, psk_num_tiles(nnz, tile), width).bytes;
 }
 
-int psk_partition_csr(int64_t rows, int64_t nnz, const int32_t *pos, int32_t tile, int32_t *tile_row,
-                      void *stream)
+int psk_partition_csr(int64_t rows, int64_t nnz, const int32_t *pos, int32_t tile, int method,
+                      int32_t *tile_row, void *stream)
 {
     if (rows < 0 || nnz < 0 || nnz > kMaxI32 || rows > kMaxI32 - 1) return PSK_ERR_SIZE;
     if (tile <= 0) return PSK_ERR_TILE;
+    if (method < PSK_PARTITION_AUTO || method > PSK_PARTITION_SCAN) return PSK_ERR_UNSUPPORTED;
     if (!pos || !tile_row) return PSK_ERR_NULL;
-    return hip_status(launch_partition(rows, nnz, pos, tile, tile_row, static_cast<hipStream_t>(stream)));
+    return hip_status(launch_partition(rows, nnz, pos, tile, method, tile_row, static_cast<hipStream_t>(stream)));
 }
 
 int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
@@ -125,12 +126,12 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int32_t ntiles = (int32_t)psk_num_tiles(nnz, tile);
     hipError_t e = hipSuccess;
-    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, ws.tile_row, s);
+    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, 0, ws.tile_row, s);
     if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
         if (ntiles == 0) e = launch_fill_zero(y, rows, s);
-        else e = launch_spmv_csr_main((int32_t)rows, (int32_t)nnz, pos, crd, vals, x, y, tile, ws, s);
+        else e = launch_spmv_csr_main((int32_t)rows, (int32_t)cols, (int32_t)nnz, pos, crd, vals, x, y, tile, ws, s);
     }
-    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, 1, 1, ws, y, s);
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, 1, 1, tile, pos, ws, y, s);
     return hip_status(e);
 }
 
@@ -147,7 +148,7 @@ int psk_spmm_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int32_t ntiles = (int32_t)psk_num_tiles(nnz, tile);
     hipError_t e = hipSuccess;
-    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, ws.tile_row, s);
+    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, 0, ws.tile_row, s);
     if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
         if (ntiles == 0) {
             if (ldc == k) e = launch_fill_zero(C, rows * (int64_t)k, s);
@@ -156,7 +157,7 @@ int psk_spmm_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
             e = launch_spmm_csr_main((int32_t)rows, (int32_t)nnz, pos, crd, vals, B, k, ldb, C, ldc, tile, ws, s);
         }
     }
-    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, k, ldc, ws, C, s);
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, k, ldc, tile, pos, ws, C, s);
     return hip_status(e);
 }
 
@@ -175,12 +176,12 @@ int psk_spmv_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, con
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int32_t ntiles = (int32_t)psk_num_tiles(nblocks, tile);
     hipError_t e = hipSuccess;
-    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(brows, nblocks, pos, tile, ws.tile_row, s);
+    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(brows, nblocks, pos, tile, 0, ws.tile_row, s);
     if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
         if (ntiles == 0) e = launch_fill_zero(y, brows * bs, s);
         else e = launch_spmv_bcsr4_main((int32_t)brows, (int32_t)nblocks, pos, crd, vals, x, y, tile, ws, s);
     }
-    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, bs, bs, ws, y, s);
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, bs, bs, tile, pos, ws, y, s);
     return hip_status(e);
 }
 
@@ -200,7 +201,7 @@ int psk_spmm_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, con
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int32_t ntiles = (int32_t)psk_num_tiles(nblocks, tile);
     hipError_t e = hipSuccess;
-    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(brows, nblocks, pos, tile, ws.tile_row, s);
+    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(brows, nblocks, pos, tile, 0, ws.tile_row, s);
     if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
         if (ntiles == 0) {
             if (ldc == k) e = launch_fill_zero(C, brows * bs * (int64_t)k, s);
@@ -209,7 +210,7 @@ int psk_spmm_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, con
             e = launch_spmm_bcsr4_main((int32_t)brows, (int32_t)nblocks, pos, crd, vals, B, k, ldb, C, ldc, tile, ws, s);
         }
     }
-    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, bs, k, ldc, ws, C, s);
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, bs, k, ldc, tile, pos, ws, C, s);
     return hip_status(e);
 }
 

@@ -22,10 +22,72 @@ __global__ __launch_bounds__(256) void k_partition(int rows, int nnz, const int 
     tile_row[t] = lo;
 }
 
-hipError_t launch_partition(int64_t rows, int64_t nnz, const int32_t *pos, int32_t tile, int32_t *tile_row,
-                            hipStream_t s)
+// The same table from one pass over the rows instead of one search per tile (Section 5, "Divide",
+// names both ways of locating a tile's start: an O(log n) search or an O(n) walk).  Row r owns the
+// first position of every tile t with pos[r] <= t*tile < pos[r+1]; each non-empty row writes those
+// entries.  Every tile start lies in exactly one non-empty row, so the table is filled exactly once.
+// No dependent loads: the kernel streams pos at memory speed, which beats the search's chain of
+// log2(rows) cache misses as long as pos itself is not huge.  Rows that own many tile starts are
+// written by their whole wave.
+__global__ __launch_bounds__(256) void k_partition_scan(int rows, int nnz, const int *__restrict__ pos, int tile,
+                                                        int shift, int ntiles, int *__restrict__ tile_row,
+                                                        int vec_ok)
+{
+    constexpr int RPT = 4;                                   // rows per thread
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int rbase = g * RPT;
+    if (g == 0) tile_row[ntiles] = rows;
+    int p[RPT + 1];
+    if (vec_ok && rbase + RPT <= rows) {
+        const v4i v = *reinterpret_cast<const v4i *>(pos + rbase);
+        p[0] = v.x; p[1] = v.y; p[2] = v.z; p[3] = v.w;
+        p[4] = pos[rbase + RPT];
+    } else {
+#pragma unroll
+        for (int i = 0; i <= RPT; ++i) p[i] = rbase + i <= rows ? pos[rbase + i] : nnz;
+    }
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+        const int r = rbase + i;
+        int t_lo = 0, t_hi = -1;
+        if (r < rows && p[i + 1] > p[i]) {
+            if (shift >= 0) {
+                t_lo = (int)(((long long)p[i] + tile - 1) >> shift);
+                t_hi = (p[i + 1] - 1) >> shift;
+            } else {
+                t_lo = (int)(((long long)p[i] + tile - 1) / tile);
+                t_hi = (p[i + 1] - 1) / tile;
+            }
+        }
+        const int n = t_hi - t_lo + 1;                       // tile starts inside this row
+        if (n > 0 && n <= 16)
+            for (int t = t_lo; t <= t_hi; ++t) tile_row[t] = r;
+        unsigned long long big = __ballot(n > 16);
+        while (big) {
+            const int src = __ffsll((long long)big) - 1;
+            big &= big - 1;
+            const int lo = __shfl(t_lo, src, WAVE), hi = __shfl(t_hi, src, WAVE), row = __shfl(r, src, WAVE);
+            for (int t = lo + lane; t <= hi; t += WAVE) tile_row[t] = row;
+        }
+    }
+}
+
+// method: 0 = choose, 1 = binary search per tile, 2 = one scan over the rows
+hipError_t launch_partition(int64_t rows, int64_t nnz, const int32_t *pos, int32_t tile, int method,
+                            int32_t *tile_row, hipStream_t s)
 {
     const int64_t ntiles = nnz <= 0 ? 0 : (nnz + tile - 1) / tile;
+    if (method == 0) method = (ntiles > 0 && rows <= (int64_t(1) << 23)) ? 2 : 1;
+    if (method == 2 && ntiles > 0) {
+        int shift = -1;
+        if ((tile & (tile - 1)) == 0) { shift = 0; while ((1 << shift) < tile) ++shift; }
+        const int vec_ok = (reinterpret_cast<uintptr_t>(pos) & 15) == 0;
+        const int64_t threads = (rows + 3) / 4;
+        hipLaunchKernelGGL(k_partition_scan, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, (int)rows,
+                           (int)nnz, pos, tile, shift, (int)ntiles, tile_row, vec_ok);
+        return hipGetLastError();
+    }
     const int64_t n = ntiles + 1;
     hipLaunchKernelGGL(k_partition, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (int)rows, (int)nnz, pos,
                        tile, (int)ntiles, tile_row);
@@ -49,11 +111,60 @@ hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s)
 }
 
 // Carry fix-up.  Tile t left carry_row[t] = r >= 0 when its first positions belong to a row r that
-// began in an earlier tile, together with `width` partial sums.  Carry rows are non-decreasing in t
-// and the tiles of one row are consecutive, so the records of a row form a run; the lane that sees
-// the head of a run adds the whole run, in tile order and in fp64, to the owner's partial result.
-// out element (r, e) lives at out[(r*nsub + e / k) * ld + e % k].
-__global__ __launch_bounds__(256) void k_carry_fixup(int ntiles, int width, int nsub, int k, long long ld,
+// began in an earlier tile, together with `width` partial sums.  The records of one row sit in
+// consecutive tiles: from the tile after the one holding pos[r] to the tile holding the row's last
+// position, so the lane that sees the head of a run knows its length from pos[r+1] alone and no load
+// in the walk depends on another.  The run is added in tile order, in fp64, to the owner's partial
+// result.  out element (r, e) lives at out[(r*nsub + e / k) * ld + e % k].
+__device__ __forceinline__ int run_length(const int *__restrict__ pos, int r, int t, int tile, int shift, int ntiles)
+{
+    const int last = pos[r + 1] - 1;
+    int e = shift >= 0 ? last >> shift : last / tile;
+    int len = e - t + 1;
+    len = len < 1 ? 1 : len;
+    return len > ntiles - t ? ntiles - t : len;
+}
+
+// width = 1 (SpMV): a lane per tile; runs of more than 8 records are summed by the whole wave.
+__global__ __launch_bounds__(256) void k_carry_fixup1(int ntiles, long long ld, int tile, int shift,
+                                                      const int *__restrict__ pos,
+                                                      const int *__restrict__ carry_row,
+                                                      const float *__restrict__ carry_val,
+                                                      float *__restrict__ out)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & (WAVE - 1);
+    int r = -1, len = 0;
+    if (t < ntiles) {
+        r = carry_row[t];
+        const int prev = t > 0 ? carry_row[t - 1] : -1;
+        if (r >= 0 && prev != r) len = run_length(pos, r, t, tile, shift, ntiles);
+    }
+    if (len > 0 && len <= 8) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = i < len ? carry_val[t + i] : 0.0f;
+        double sum = 0.0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sum += (double)v[i];
+        out[r * ld] = (float)((double)out[r * ld] + sum);
+    }
+    unsigned long long big = __ballot(len > 8);
+    while (big) {
+        const int src = __ffsll((long long)big) - 1;
+        big &= big - 1;
+        const int t0 = __shfl(t, src, WAVE), n = __shfl(len, src, WAVE), row = __shfl(r, src, WAVE);
+        double acc = 0.0;
+        for (int u = lane; u < n; u += WAVE) acc += (double)carry_val[t0 + u];
+#pragma unroll
+        for (int m = 1; m < WAVE; m <<= 1) acc += __shfl_xor(acc, m, WAVE);
+        if (lane == src) out[row * ld] = (float)((double)out[row * ld] + acc);
+    }
+}
+
+// any width: a lane per (tile, element); the run is walked eight records at a time.
+__global__ __launch_bounds__(256) void k_carry_fixup(int ntiles, int width, int nsub, int k, long long ld, int tile,
+                                                     int shift, const int *__restrict__ pos,
                                                      const int *__restrict__ carry_row,
                                                      const float *__restrict__ carry_val,
                                                      float *__restrict__ out)
@@ -64,20 +175,34 @@ __global__ __launch_bounds__(256) void k_carry_fixup(int ntiles, int width, int 
     const int r = carry_row[t];
     if (r < 0) return;
     if (t > 0 && carry_row[t - 1] == r) return;
+    const int len = run_length(pos, r, t, tile, shift, ntiles);
     double sum = 0.0;
-    for (int u = t; u < ntiles && carry_row[u] == r; ++u) sum += (double)carry_val[(long long)u * width + e];
+    for (int u = 0; u < len; u += 8) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = u + i < len ? carry_val[(long long)(t + u + i) * width + e] : 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sum += (double)v[i];
+    }
     float *dst = out + ((long long)r * nsub + e / k) * ld + e % k;
     *dst = (float)((double)*dst + sum);
 }
 
-hipError_t launch_carry_fixup(int32_t ntiles, int32_t nsub, int32_t k, int64_t ld, const Workspace &w,
-                              float *out, hipStream_t s)
+hipError_t launch_carry_fixup(int32_t ntiles, int32_t nsub, int32_t k, int64_t ld, int32_t tile, const int32_t *pos,
+                              const Workspace &w, float *out, hipStream_t s)
 {
     if (ntiles <= 1) return hipSuccess;   // tile 0 never has a carry
+    int shift = -1;
+    if ((tile & (tile - 1)) == 0) { shift = 0; while ((1 << shift) < tile) ++shift; }
     const int width = nsub * k;
+    if (width == 1) {
+        hipLaunchKernelGGL(k_carry_fixup1, dim3((unsigned)((ntiles + 255) / 256)), dim3(256), 0, s, ntiles,
+                           (long long)ld, tile, shift, pos, w.carry_row, w.carry_val, out);
+        return hipGetLastError();
+    }
     const int64_t n = (int64_t)ntiles * width;
     hipLaunchKernelGGL(k_carry_fixup, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, ntiles, width, nsub, k,
-                       (long long)ld, w.carry_row, w.carry_val, out);
+                       (long long)ld, tile, shift, pos, w.carry_row, w.carry_val, out);
     return hipGetLastError();
 }
 

@@ -19,9 +19,47 @@ namespace psk {
 //                   segments of >= LONG positions are queued and summed by a whole wave each.
 //     Every row segment has a fixed summation order, so results are deterministic.
 //
-// VEC: 16-byte loads (needs 16-byte aligned crd/vals); otherwise 4-byte loads, lane-consecutive.
-template <int THREADS, int NPT, bool VEC>
-__global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int nnz, const int *__restrict__ pos,
+// MODE 0: 4-byte loads, lane-consecutive positions (works for any alignment).
+// MODE 1: 16-byte loads (crd and vals 16-byte aligned), each lane keeps four consecutive positions.
+template <int MODE, int THREADS>
+__device__ __forceinline__ int tile_index(int g, int tid)
+{
+    if (MODE == 0) return g * THREADS + tid;
+    return ((g / 4) * THREADS + tid) * 4 + (g & 3);
+}
+
+// Gathering x for four consecutive positions held by one lane.
+//
+// The vector-memory address unit takes about one clock per active lane for a gather whatever the
+// width of the access (4, 8 or 16 bytes per lane cost the same), so the cheapest gather is the one
+// with the fewest lane requests.  Positions whose columns are contiguous (c, c+1, ...: stencils,
+// bands, dense blocks) can be served by one 16-byte load of their lane.  run_plan() looks at a lane's
+// four columns: run A starts at position 0, run B right after it; if A and B together cover all four
+// positions two wide loads replace four narrow ones.  The choice is made per wave (one ballot) so that
+// both variants stay straight-line code with every load issued before the first use; unstructured
+// matrices never take the wide path and keep their 4-byte gathers.
+typedef float v4f_u __attribute__((ext_vector_type(4), aligned(4)));
+struct RunPlan { int lenA; int colB; bool ok; };
+__device__ __forceinline__ RunPlan run_plan(v4i c, int cols)
+{
+    const bool e1 = c.y == c.x + 1, e2 = c.z == c.y + 1, e3 = c.w == c.z + 1;
+    RunPlan p;
+    p.lenA = e1 ? (e2 ? (e3 ? 4 : 3) : 2) : 1;
+    p.colB = p.lenA == 1 ? c.y : (p.lenA == 2 ? c.z : c.w);
+    const bool covered = p.lenA >= 3 || (p.lenA == 2 && e3) || (p.lenA == 1 && e2 && e3);
+    p.ok = covered && c.x <= cols - 4 && p.colB <= cols - 4;
+    return p;
+}
+__device__ __forceinline__ void run_select(const RunPlan &p, v4f_u wA, v4f_u wB, float (&g)[4])
+{
+    g[0] = wA.x;
+    g[1] = p.lenA >= 2 ? wA.y : wB.x;
+    g[2] = p.lenA >= 3 ? wA.z : (p.lenA == 2 ? wB.x : wB.y);
+    g[3] = p.lenA == 4 ? wA.w : (p.lenA == 3 ? wB.x : (p.lenA == 2 ? wB.y : wB.z));
+}
+
+template <int THREADS, int NPT, int MODE>
+__global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nnz, const int *__restrict__ pos,
                                                       const int *__restrict__ crd,
                                                       const float *__restrict__ vals,
                                                       const float *__restrict__ x, float *__restrict__ y,
@@ -33,6 +71,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int nnz, const i
     constexpr int NW = THREADS / WAVE;
     constexpr int LONG = 32;
     constexpr int MAXLONG = T / LONG;
+    constexpr bool VEC = MODE != 0;
     static_assert(NPT % 4 == 0, "NPT must be a multiple of 4");
     __shared__ float sprod[skewed_size<1>(T)];
     __shared__ int slong[MAXLONG * 3];
@@ -46,49 +85,93 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int nnz, const i
     const int cnt = (nnz - t0 < T) ? nnz - t0 : T;
     const int t1 = t0 + cnt;
 
+    // Issue order matters more than anything else here: the tile's row bounds hang off a chain of
+    // dependent loads (tile_row -> pos), so that chain is started first and runs underneath the
+    // streaming loads and the gather instead of after them.
+    const int r0 = tile_row[t], r1 = tile_row[t + 1];
+
     // ---- 1. stream + gather + multiply
     float prod[NPT];
-    if (cnt == T) {
+    v4i cv[VEC ? NPT / 4 : 1];
+    v4f vv[VEC ? NPT / 4 : 1];
+    int cs[MODE == 1 ? 1 : NPT];
+    float vs[MODE == 1 ? 1 : NPT];
+    const bool full = (cnt == T);
+    if (full) {
         if (VEC) {
-            v4i c[NPT / 4];
-            v4f v[NPT / 4];
 #pragma unroll
             for (int g = 0; g < NPT / 4; ++g) {
                 const int off = t0 + (g * THREADS + tid) * 4;
-                c[g] = ld_stream(reinterpret_cast<const v4i *>(crd + off));
-                v[g] = ld_stream(reinterpret_cast<const v4f *>(vals + off));
+                cv[g] = ld_stream(reinterpret_cast<const v4i *>(crd + off));
+                vv[g] = ld_stream(reinterpret_cast<const v4f *>(vals + off));
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < NPT; ++g) {
+                cs[g] = ld_stream(crd + t0 + g * THREADS + tid);
+                vs[g] = ld_stream(vals + t0 + g * THREADS + tid);
+            }
+        }
+    }
+
+    // ---- 2. rows of this tile (loads issued before the gather)
+    const int p_r0 = pos[r0], p_r1 = pos[r1];
+    const int rbeg = (t == 0) ? 0 : r0;
+    int my_lo = 0, my_hi = 0;                       // pos pair of the first row this thread will look at
+    if (rbeg + tid < rows) {
+        my_lo = pos[rbeg + tid];
+        my_hi = pos[rbeg + tid + 1];
+    }
+
+    if (full) {
+        if (MODE == 1) {
+            float xg[NPT / 4][4];
+            RunPlan plan[NPT / 4];
+            bool ok = true;
+#pragma unroll
+            for (int g = 0; g < NPT / 4; ++g) {
+                plan[g] = run_plan(cv[g], cols);
+                ok = ok && plan[g].ok;
+            }
+            if (__ballot(!ok) == 0ull) {
+                v4f_u wA[NPT / 4], wB[NPT / 4];
+#pragma unroll
+                for (int g = 0; g < NPT / 4; ++g) {
+                    wA[g] = *reinterpret_cast<const v4f_u *>(x + cv[g].x);
+                    wB[g] = *reinterpret_cast<const v4f_u *>(x + plan[g].colB);
+                }
+#pragma unroll
+                for (int g = 0; g < NPT / 4; ++g) run_select(plan[g], wA[g], wB[g], xg[g]);
+            } else {
+#pragma unroll
+                for (int g = 0; g < NPT / 4; ++g) {
+                    xg[g][0] = x[cv[g].x];
+                    xg[g][1] = x[cv[g].y];
+                    xg[g][2] = x[cv[g].z];
+                    xg[g][3] = x[cv[g].w];
+                }
             }
 #pragma unroll
             for (int g = 0; g < NPT / 4; ++g) {
-                prod[4 * g + 0] = v[g].x * x[c[g].x];
-                prod[4 * g + 1] = v[g].y * x[c[g].y];
-                prod[4 * g + 2] = v[g].z * x[c[g].z];
-                prod[4 * g + 3] = v[g].w * x[c[g].w];
+                prod[4 * g + 0] = vv[g].x * xg[g][0];
+                prod[4 * g + 1] = vv[g].y * xg[g][1];
+                prod[4 * g + 2] = vv[g].z * xg[g][2];
+                prod[4 * g + 3] = vv[g].w * xg[g][3];
             }
         } else {
-            int c[NPT];
-            float v[NPT];
 #pragma unroll
-            for (int g = 0; g < NPT; ++g) {
-                c[g] = ld_stream(crd + t0 + g * THREADS + tid);
-                v[g] = ld_stream(vals + t0 + g * THREADS + tid);
-            }
-#pragma unroll
-            for (int g = 0; g < NPT; ++g) prod[g] = v[g] * x[c[g]];
+            for (int g = 0; g < NPT; ++g) prod[g] = vs[g] * x[cs[g]];
         }
     } else {   // last tile: guarded
 #pragma unroll
         for (int g = 0; g < NPT; ++g) {
-            const int i = VEC ? ((g / 4) * THREADS + tid) * 4 + (g & 3) : g * THREADS + tid;
+            const int i = tile_index<MODE, THREADS>(g, tid);
             prod[g] = (i < cnt) ? vals[t0 + i] * x[crd[t0 + i]] : 0.0f;
         }
     }
 
-    // ---- 2. rows of this tile
-    const int r0 = tile_row[t], r1 = tile_row[t + 1];
-    const bool has_carry = (t > 0) && (pos[r0] < t0);
-    const int rbeg = (t == 0) ? 0 : r0;
-    const int rend = (pos[r1] == t1) ? r1 : r1 + 1;   // last tile: r1 = rows and pos[rows] = nnz = t1
+    const bool has_carry = (t > 0) && (p_r0 < t0);
+    const int rend = (p_r1 == t1) ? r1 : r1 + 1;   // last tile: r1 = rows and pos[rows] = nnz = t1
     if (tid == 0 && !has_carry) carry_row[t] = -1;
 
     // ---- 3a. the tile lies inside a single row
@@ -113,12 +196,12 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int nnz, const i
     if (tid == 0) nlong = 0;
 #pragma unroll
     for (int g = 0; g < NPT; ++g) {
-        const int i = VEC ? ((g / 4) * THREADS + tid) * 4 + (g & 3) : g * THREADS + tid;
-        sprod[skew<1>(i)] = prod[g];
+        sprod[skew<1>(tile_index<MODE, THREADS>(g, tid))] = prod[g];
     }
     __syncthreads();
     for (int r = rbeg + tid; r < rend; r += THREADS) {
-        int lo = pos[r] - t0, hi = pos[r + 1] - t0;
+        int lo = my_lo - t0, hi = my_hi - t0;
+        if (r + THREADS < rend) { my_lo = pos[r + THREADS]; my_hi = pos[r + THREADS + 1]; }
         lo = lo < 0 ? 0 : lo;
         hi = hi > cnt ? cnt : hi;
         if (hi - lo < LONG) {
@@ -151,31 +234,32 @@ bool spmv_csr_tile_ok(int32_t tile)
 }
 
 template <int THREADS, int NPT>
-static void launch_pos(bool vec, int grid, hipStream_t s, int rows, int nnz, const int *pos, const int *crd,
+static void launch_pos(int mode, int grid, hipStream_t s, int rows, int cols, int nnz, const int *pos, const int *crd,
                        const float *vals, const float *x, float *y, const Workspace &w, int ntiles)
 {
-    if (vec)
-        hipLaunchKernelGGL((k_spmv_pos<THREADS, NPT, true>), dim3(grid), dim3(THREADS), 0, s, rows, nnz, pos, crd,
-                           vals, x, y, w.tile_row, w.carry_row, w.carry_val, ntiles);
-    else
-        hipLaunchKernelGGL((k_spmv_pos<THREADS, NPT, false>), dim3(grid), dim3(THREADS), 0, s, rows, nnz, pos, crd,
-                           vals, x, y, w.tile_row, w.carry_row, w.carry_val, ntiles);
+#define PSK_GO(M)                                                                                               \
+    hipLaunchKernelGGL((k_spmv_pos<THREADS, NPT, M>), dim3(grid), dim3(THREADS), 0, s, rows, cols, nnz, pos, crd, \
+                       vals, x, y, w.tile_row, w.carry_row, w.carry_val, ntiles)
+    if (mode == 1) PSK_GO(1);
+    else PSK_GO(0);
+#undef PSK_GO
 }
 
-hipError_t launch_spmv_csr_main(int32_t rows, int32_t nnz, const int32_t *pos, const int32_t *crd,
+hipError_t launch_spmv_csr_main(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
                                 const float *vals, const float *x, float *y, int32_t tile,
                                 const Workspace &w, hipStream_t s)
 {
     const int ntiles = (int)(((int64_t)nnz + tile - 1) / tile);
     if (ntiles == 0) return hipSuccess;
     const int grid = xcd_grid(ntiles);
-    const bool vec = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
+    const bool aligned = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
+    const int vec = aligned ? 1 : 0;
     switch (tile) {
-        case 256:  launch_pos<64, 4>(vec, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles); break;
-        case 512:  launch_pos<128, 4>(vec, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles); break;
-        case 1024: launch_pos<256, 4>(vec, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles); break;
-        case 2048: launch_pos<256, 8>(vec, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles); break;
-        case 4096: launch_pos<256, 16>(vec, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles); break;
+        case 256:  launch_pos<64, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles); break;
+        case 512:  launch_pos<128, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles); break;
+        case 1024: launch_pos<256, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles); break;
+        case 2048: launch_pos<256, 8>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles); break;
+        case 4096: launch_pos<256, 16>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -61,11 +61,12 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.psk_spmv_csr(4, 4, 4, one, null, one, one, one, 0, 7, one, big, null) == 1
     assert L.psk_spmv_csr(4, 4, 4, one, one, one, null, one, 0, 7, one, big, null) == 1
     assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, null, 0, 7, one, big, null) == 1
-    assert L.psk_partition_csr(4, 4, null, 4, one, null) == 1
+    assert L.psk_partition_csr(4, 4, null, 4, 0, one, null) == 1
     # TILE
     assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 1000, 7, one, big, null) == 3
     assert L.psk_spmm_csr(4, 4, 4, one, one, one, one, 8, 8, one, 8, 4096, 7, one, big, null) == 3
-    assert L.psk_partition_csr(4, 4, one, 0, one, null) == 3
+    assert L.psk_partition_csr(4, 4, one, 0, 0, one, null) == 3
+    assert L.psk_partition_csr(4, 4, one, 4, 3, one, null) == 5
     # WORKSPACE
     assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 7, null, big, null) == 4
     assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 7, one, 16, null) == 4

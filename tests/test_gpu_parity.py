@@ -55,8 +55,10 @@ def test_partition_bit_exact_configs(tile):
     for n, scale in [(1, 1.0), (2, 0.01), (3, 0.003), (4, 0.005), (5, 0.01)]:
         A = wl.config(n, scale)["A"]
         say("partition config", n, "tile", tile, "nnz", A.nnz)
-        got = psk.psk_partition_csr(dev(A.pos), A.nnz, tile).cpu().numpy()
-        assert (got == oracle.partition(A.pos, tile)).all()
+        want = oracle.partition(A.pos, tile)
+        for method in (0, 1, 2):
+            got = psk.psk_partition_csr(dev(A.pos), A.nnz, tile, method=method).cpu().numpy()
+            assert (got == want).all(), "method %d" % method
 
 
 @pytest.mark.parametrize("kind", ADVERSARIAL_KINDS)
@@ -66,8 +68,10 @@ def test_partition_bit_exact_adversarial(kind):
     pos = np.concatenate([[0], np.cumsum(L)]).astype(np.int32)
     for tile in (1, 5, 256, 1000, 2048):
         say("partition", kind, "tile", tile)
-        got = psk.psk_partition_csr(dev(pos), int(pos[-1]), tile).cpu().numpy()
-        assert (got == oracle.partition(pos, tile)).all()
+        want = oracle.partition(pos, tile)
+        for method in (0, 1, 2):
+            got = psk.psk_partition_csr(dev(pos), int(pos[-1]), tile, method=method).cpu().numpy()
+            assert (got == want).all(), "method %d" % method
 
 
 # ------------------------------------------------------------------ CSR SpMV
