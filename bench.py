@@ -35,6 +35,12 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
 # scaled by the copy-kernel calibration; the summaries are under profiles/.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
+    ("powerlaw", 2048): 3563010542,     # profiles/k_spmv_pos_powerlaw.txt
+    ("stencil", 2048): 929657400,       # profiles/k_spmv_pos_stencil.txt
+    ("uniform28", 2048): 3981942000,    # profiles/k_spmv_pos_uniform28.txt
+    ("spmm", 1024): 8772500000,         # profiles/k_spmm_pos_csr_spmm_k128.txt
+    ("bcsr_spmv", 256): 199010000,      # profiles/k_spmv_bcsr4_bcsr_spmv.txt
+    ("bcsr_spmm", 256): 2411000000,     # profiles/k_spmm_pos_bcsr_spmm_n64.txt
 }
 
 WORKLOADS = {
