@@ -1,0 +1,101 @@
+"""Parity at the full sizes of the evaluated configurations, in the launch configuration bench.py
+times (default tiles, all three phases).  SpMV outputs are compared in full (the oracle does 10^8
+nonzeros in about a second); SpMM outputs on sampled rows the oracle computes one by one."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import paper_2001_00532_amd as psk  # noqa: E402
+
+REL, FLOOR = 1e-5, 1e-30
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def sample_rows(rows, n, seed):
+    rng = np.random.default_rng(seed)
+    edge = np.concatenate([np.arange(min(64, rows)), np.arange(max(0, rows - 64), rows)])
+    return np.unique(np.concatenate([edge, rng.integers(0, rows, size=n)])).astype(np.int64)
+
+
+def check(got, ref, mag, what):
+    ok, worst = oracle.within_tolerance(got, ref, mag, REL, FLOOR)
+    assert ok, "%s: worst |err|/bound = %.3g" % (what, worst)
+    say(what, "worst |err|/bound = %.3g" % worst)
+
+
+@pytest.mark.parametrize("n", [2, 3])
+def test_spmv_full_size(n):
+    c = wl.config(n)
+    A = c["A"]
+    say("config", n, "rows", A.rows, "nnz", A.nnz)
+    pos, crd, vals, x = dev(A.pos), dev(A.crd), dev(A.vals), dev(c["x"])
+    tile = psk.psk_default_tile(psk.PSK_OP_SPMV_CSR)
+    want = oracle.partition(A.pos, tile)
+    for method in (1, 2):
+        got = psk.psk_partition_csr(pos, A.nnz, tile, method=method).cpu().numpy()
+        assert (got == want).all(), "partition method %d" % method
+    y = torch.full((A.rows,), float("nan"), device="cuda")
+    ws = psk.workspace(psk.PSK_OP_SPMV_CSR, A.rows, A.nnz)
+    psk.psk_spmv_csr(A.rows, A.cols, A.nnz, pos, crd, vals, x, y, ws=ws)
+    torch.cuda.synchronize()
+    first = y.clone()
+    ref, mag = oracle.spmv_csr(A.pos, A.crd, A.vals, c["x"], threads=16)
+    check(y.cpu().numpy(), ref, mag, "config %d full" % n)
+    # deterministic: a second run gives the same bits
+    y.fill_(float("nan"))
+    psk.psk_spmv_csr(A.rows, A.cols, A.nnz, pos, crd, vals, x, y, ws=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(first, y)
+    if n == 2:   # the wave-per-row baseline agrees within twice the bound (three-way check)
+        psk.psk_spmv_csr_rowsplit(A.rows, A.cols, A.nnz, pos, crd, vals, x, y, variant=1)
+        torch.cuda.synchronize()
+        d = np.abs(y.cpu().numpy().astype(np.float64) - first.cpu().numpy().astype(np.float64))
+        assert (d <= 2 * (REL * mag + FLOOR)).all()
+
+
+def test_spmm_full_size():
+    c = wl.config(4)
+    A, B = c["A"], c["B"]
+    say("config 4 rows", A.rows, "nnz", A.nnz)
+    C = torch.full((A.rows, 128), float("nan"), device="cuda")
+    psk.psk_spmm_csr(A.rows, A.cols, A.nnz, dev(A.pos), dev(A.crd), dev(A.vals), dev(B), C)
+    torch.cuda.synchronize()
+    assert not torch.isnan(C).any()
+    sel = sample_rows(A.rows, 20000, 4)
+    ref, mag = oracle.spmm_csr(A.pos, A.crd, A.vals, B, sel=sel, threads=16)
+    check(C[torch.from_numpy(sel).cuda()].cpu().numpy(), ref, mag, "config 4 sampled rows")
+
+
+def test_bcsr_full_size():
+    c = wl.config(5)
+    A = c["A"]
+    say("config 5 block rows", A.rows, "blocks", A.nnz)
+    pos, crd, vals = dev(A.pos), dev(A.crd), dev(A.vals)
+    y = torch.full((A.rows * 4,), float("nan"), device="cuda")
+    psk.psk_spmv_bcsr(A.rows, A.cols, A.nnz, 4, pos, crd, vals, dev(c["x"]), y)
+    torch.cuda.synchronize()
+    ref, mag = oracle.spmv_bcsr(A.pos, A.crd, A.vals, c["x"], 4, threads=16)
+    check(y.cpu().numpy(), ref, mag, "config 5 spmv full")
+    C = torch.full((A.rows * 4, 64), float("nan"), device="cuda")
+    psk.psk_spmm_bcsr(A.rows, A.cols, A.nnz, 4, pos, crd, vals, dev(c["B"]), C)
+    torch.cuda.synchronize()
+    assert not torch.isnan(C).any()
+    sel = sample_rows(A.rows, 10000, 5)
+    ref, mag = oracle.spmm_bcsr(A.pos, A.crd, A.vals, c["B"], 4, sel=sel, threads=16)
+    got = C.view(A.rows, 4, 64)[torch.from_numpy(sel).cuda()].reshape(-1, 64).cpu().numpy()
+    check(got, ref, mag, "config 5 spmm sampled block rows")
