@@ -126,10 +126,30 @@ int psk_partition_csr(int64_t rows, int64_t nnz, const int32_t *pos, int32_t til
  * the tile, one carry record per tile for a row that began in an earlier tile
  * (instead of the schedule's atomics), carries added by a second small kernel.
  * x has cols entries, y rows entries.  tile in {0, 256, 512, 1024, 2048, 4096}.
+ *
+ * col_passes (0 or 1 = off, at most PSK_MAX_COL_PASSES): the main step is run that many times, pass q
+ * gathering only the columns of the q-th equal slice of [0, cols) and adding to what the earlier passes
+ * stored.  A and the row bounds are streamed once per pass; in exchange the slice of x a pass gathers
+ * from can stay in the 4 MB L2 of a die.  Worth it only for matrices whose columns are scattered over
+ * an x larger than that (a gather that misses L2 moves a 128-byte line for 4 useful bytes); it is a
+ * loss for banded or otherwise local matrices.  psk_analyze_csr suggests a value.  Results stay
+ * deterministic; they differ from the single-pass result within the usual fp32 reassociation.
  */
 int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
-                 const float *vals, const float *x, float *y, int32_t tile, int phases,
+                 const float *vals, const float *x, float *y, int32_t tile, int32_t col_passes, int phases,
                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Suggests col_passes for psk_spmv_csr on this matrix (like the tile->row table it depends only on A and
+ * can be kept).  Answers 1 when x fits a die's L2 or the matrix is small; otherwise it samples up to
+ * 16384 positions and, if fewer than half of them have their successor's column in the same 128-byte
+ * line of x, suggests ceil(4*cols bytes / 4 MiB), at most PSK_MAX_COL_PASSES.
+ * `col_passes` is a HOST pointer.  Unlike every other call this one SYNCHRONISES `stream` (it reads the
+ * sample count back); `workspace` needs 256 bytes.
+ */
+#define PSK_MAX_COL_PASSES 4
+int psk_analyze_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                    void *workspace, size_t workspace_bytes, int32_t *col_passes, void *stream);
 
 /*
  * C = A B, CSR A, position-space schedule (appendix "SPMM on a GPU"): positions are

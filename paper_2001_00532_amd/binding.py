@@ -21,7 +21,7 @@ PSK_ROWSPLIT_THREAD_PER_ROW, PSK_ROWSPLIT_WAVE_PER_ROW = 0, 1
 
 EXPORTS = [
     "psk_status_string", "psk_version", "psk_default_tile", "psk_num_tiles", "psk_workspace_bytes",
-    "psk_partition_csr", "psk_spmv_csr", "psk_spmm_csr", "psk_spmv_bcsr", "psk_spmm_bcsr",
+    "psk_partition_csr", "psk_analyze_csr", "psk_spmv_csr", "psk_spmm_csr", "psk_spmv_bcsr", "psk_spmm_bcsr",
     "psk_spmv_csr_rowsplit", "psk_spmm_csr_rowsplit",
 ]
 
@@ -49,7 +49,9 @@ def lib() -> ctypes.CDLL:
         L.psk_num_tiles.argtypes, L.psk_num_tiles.restype = [i64, i32], i64
         L.psk_workspace_bytes.argtypes, L.psk_workspace_bytes.restype = [ci, i64, i64, i32, i32, i32], sz
         L.psk_partition_csr.argtypes, L.psk_partition_csr.restype = [i64, i64, p, i32, ci, p, p], ci
-        L.psk_spmv_csr.argtypes = [i64, i64, i64, p, p, p, p, p, i32, ci, p, sz, p]
+        L.psk_analyze_csr.argtypes = [i64, i64, i64, p, p, p, sz, ctypes.POINTER(i32), p]
+        L.psk_analyze_csr.restype = ci
+        L.psk_spmv_csr.argtypes = [i64, i64, i64, p, p, p, p, p, i32, i32, ci, p, sz, p]
         L.psk_spmv_csr.restype = ci
         L.psk_spmm_csr.argtypes = [i64, i64, i64, p, p, p, p, i32, i64, p, i64, i32, ci, p, sz, p]
         L.psk_spmm_csr.restype = ci
@@ -131,12 +133,24 @@ def psk_partition_csr(pos, nnz: int, tile: int, method: int = 0, tile_row=None, 
     return tile_row
 
 
-def psk_spmv_csr(rows, cols, nnz, pos, crd, vals, x, y, tile=0, phases=PSK_PHASE_ALL, ws=None, stream=None):
+def psk_analyze_csr(rows, cols, nnz, pos, crd, ws=None, stream=None) -> int:
+    """Suggested col_passes for psk_spmv_csr (synchronises the stream)."""
+    if ws is None:
+        ws = torch.empty(256, dtype=torch.uint8, device=pos.device)
+    out = ctypes.c_int32(0)
+    st = lib().psk_analyze_csr(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
+                               _ptr(ws), ws.numel(), ctypes.byref(out), _stream(stream))
+    _check(st, "psk_analyze_csr")
+    return int(out.value)
+
+
+def psk_spmv_csr(rows, cols, nnz, pos, crd, vals, x, y, tile=0, col_passes=1, phases=PSK_PHASE_ALL, ws=None,
+                 stream=None):
     if ws is None:
         ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=tile, device=pos.device)
     st = lib().psk_spmv_csr(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                             _ptr(vals, torch.float32), _ptr(x, torch.float32), _ptr(y, torch.float32), int(tile),
-                            int(phases), _ptr(ws), ws.numel(), _stream(stream))
+                            int(col_passes), int(phases), _ptr(ws), ws.numel(), _stream(stream))
     _check(st, "psk_spmv_csr")
     return y
 

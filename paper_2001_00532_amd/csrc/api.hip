@@ -12,9 +12,9 @@ int32_t default_tile(int op)
 {
     switch (op) {
         case PSK_OP_SPMV_CSR: return 2048;
-        case PSK_OP_SPMM_CSR: return 1024;
-        case PSK_OP_SPMV_BCSR: return 256;
-        case PSK_OP_SPMM_BCSR: return 256;
+        case PSK_OP_SPMM_CSR: return 512;
+        case PSK_OP_SPMV_BCSR: return 512;
+        case PSK_OP_SPMM_BCSR: return 64;
         default: return -1;
     }
 }
@@ -114,10 +114,34 @@ int psk_partition_csr(int64_t rows, int64_t nnz, const int32_t *pos, int32_t til
     return hip_status(launch_partition(rows, nnz, pos, tile, method, tile_row, static_cast<hipStream_t>(stream)));
 }
 
-int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
-                 const float *vals, const float *x, float *y, int32_t tile, int phases, void *workspace,
-                 size_t workspace_bytes, void *stream)
+int psk_analyze_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                    void *workspace, size_t workspace_bytes, int32_t *col_passes, void *stream)
 {
+    if (rows < 0 || cols < 0 || nnz < 0 || nnz > kMaxI32 || rows > kMaxI32 - 1 || cols > kMaxI32) return PSK_ERR_SIZE;
+    if (!col_passes || !pos || (nnz > 0 && !crd)) return PSK_ERR_NULL;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < 256) return PSK_ERR_WORKSPACE;
+    *col_passes = 1;
+    const int64_t x_bytes = cols * 4;
+    // x fits the 4 MB L2 of a die (with room for the streams), or the problem is too small to matter
+    if (x_bytes <= (int64_t(6) << 20) || nnz < (int64_t(1) << 20)) return PSK_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t *dev = static_cast<int32_t *>(workspace);
+    int32_t host[2] = {0, 0};
+    if (launch_probe_locality((int32_t)nnz, crd, dev, s) != hipSuccess) return PSK_ERR_HIP;
+    if (hipMemcpyAsync(host, dev, sizeof(host), hipMemcpyDeviceToHost, s) != hipSuccess) return PSK_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return PSK_ERR_HIP;
+    if (host[1] > 0 && 2 * (int64_t)host[0] < host[1]) {   // fewer than half of the gathers stay in their line
+        const int64_t want = (x_bytes + (int64_t(4) << 20) - 1) / (int64_t(4) << 20);
+        *col_passes = (int32_t)(want > PSK_MAX_COL_PASSES ? PSK_MAX_COL_PASSES : want);
+    }
+    return PSK_OK;
+}
+
+int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                 const float *vals, const float *x, float *y, int32_t tile, int32_t col_passes, int phases,
+                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (col_passes < 0 || col_passes > PSK_MAX_COL_PASSES) return PSK_ERR_SIZE;
     Workspace ws;
     int st = check_common(PSK_OP_SPMV_CSR, rows, cols, nnz, pos, crd, vals, 1, 1, &tile, phases, workspace,
                           workspace_bytes, &ws);
@@ -129,7 +153,7 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
     if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, 0, ws.tile_row, s);
     if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
         if (ntiles == 0) e = launch_fill_zero(y, rows, s);
-        else e = launch_spmv_csr_main((int32_t)rows, (int32_t)cols, (int32_t)nnz, pos, crd, vals, x, y, tile, ws, s);
+        else e = launch_spmv_csr_main((int32_t)rows, (int32_t)cols, (int32_t)nnz, pos, crd, vals, x, y, tile, col_passes, ws, s);
     }
     if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, 1, 1, tile, pos, ws, y, s);
     return hip_status(e);

@@ -94,6 +94,38 @@ hipError_t launch_partition(int64_t rows, int64_t nnz, const int32_t *pos, int32
     return hipGetLastError();
 }
 
+// Gather-locality probe: of up to 16384 evenly spaced positions p, how many have their successor's
+// column within the same 128-byte line of x (0 <= crd[p+1] - crd[p] < 32)?  One workgroup; result[0] =
+// hits, result[1] = samples.
+__global__ __launch_bounds__(1024) void k_probe_locality(int nnz, const int *__restrict__ crd, int *__restrict__ result)
+{
+    __shared__ int swave[1024 / WAVE];
+    const int samples = nnz - 1 < 16384 ? nnz - 1 : 16384;
+    const long long stride = samples > 0 ? (long long)(nnz - 1) / samples : 1;
+    int hits = 0;
+    for (int i = threadIdx.x; i < samples; i += 1024) {
+        const long long p = i * stride;
+        const int d = crd[p + 1] - crd[p];
+        hits += (d >= 0 && d < 32) ? 1 : 0;
+    }
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) hits += __shfl_xor(hits, m, WAVE);
+    if ((threadIdx.x & (WAVE - 1)) == 0) swave[threadIdx.x / WAVE] = hits;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int tot = 0;
+        for (int w = 0; w < 1024 / WAVE; ++w) tot += swave[w];
+        result[0] = tot;
+        result[1] = samples;
+    }
+}
+
+hipError_t launch_probe_locality(int32_t nnz, const int32_t *crd, int32_t *result, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_probe_locality, dim3(1), dim3(1024), 0, s, nnz, crd, result);
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void k_fill_zero(float *__restrict__ p, long long n)
 {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;

@@ -33,6 +33,7 @@ inline Workspace carve(void *base, int64_t ntiles, int64_t width)
 hipError_t launch_partition(int64_t rows, int64_t nnz, const int32_t *pos, int32_t tile, int method,
                             int32_t *tile_row, hipStream_t s);
 hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s);
+hipError_t launch_probe_locality(int32_t nnz, const int32_t *crd, int32_t *result, hipStream_t s);
 // Adds the per-tile carry records to the output: element e of a record of `nsub*k` floats goes to
 // out[(row*nsub + e / k) * ld + e % k].
 hipError_t launch_carry_fixup(int32_t ntiles, int32_t nsub, int32_t k, int64_t ld, int32_t tile, const int32_t *pos,
@@ -41,7 +42,7 @@ hipError_t launch_carry_fixup(int32_t ntiles, int32_t nsub, int32_t k, int64_t l
 // CSR SpMV
 bool spmv_csr_tile_ok(int32_t tile);
 hipError_t launch_spmv_csr_main(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
-                                const float *vals, const float *x, float *y, int32_t tile,
+                                const float *vals, const float *x, float *y, int32_t tile, int32_t col_passes,
                                 const Workspace &w, hipStream_t s);
 hipError_t launch_spmv_rowsplit(int32_t rows, const int32_t *pos, const int32_t *crd, const float *vals,
                                 const float *x, float *y, int variant, hipStream_t s);

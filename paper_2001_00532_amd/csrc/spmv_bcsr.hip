@@ -45,24 +45,44 @@ __global__ __launch_bounds__(256) void k_spmv_bcsr4(int brows, int nblocks, cons
     const int cnt = (nblocks - t0 < TB) ? nblocks - t0 : TB;
     const int t1 = t0 + cnt;
 
+    // the dependent chain tile_row -> pos is started first and runs underneath the streaming loads
+    const int r0 = tile_row[t], r1 = tile_row[t + 1];
+
+    v4f a[NPASS];
+    int jb[NPASS];
+#pragma unroll
+    for (int g = 0; g < NPASS; ++g) {
+        const int i = g * 64 + (tid >> 2);
+        a[g] = v4f{0.f, 0.f, 0.f, 0.f};
+        jb[g] = 0;
+        if (i < cnt) {
+            const long long p = t0 + i;
+            a[g] = ld_stream(reinterpret_cast<const v4f *>(vals + p * 16 + ii * 4));
+            jb[g] = ld_stream(crd + p);
+        }
+    }
+
+    const int p_r0 = pos[r0], p_r1 = pos[r1];
+    const int rbeg = (t == 0) ? 0 : r0;
+    int my_lo = 0, my_hi = 0;                     // pos pair of the first block row this lane looks at
+    if (rbeg + (tid >> 2) < brows) {
+        my_lo = pos[rbeg + (tid >> 2)];
+        my_hi = pos[rbeg + (tid >> 2) + 1];
+    }
+
     float prod[NPASS];
 #pragma unroll
     for (int g = 0; g < NPASS; ++g) {
         const int i = g * 64 + (tid >> 2);
         prod[g] = 0.0f;
         if (i < cnt) {
-            const long long p = t0 + i;
-            const v4f a = ld_stream(reinterpret_cast<const v4f *>(vals + p * 16 + ii * 4));
-            const int jb = ld_stream(crd + p);
-            const v4f b = *reinterpret_cast<const v4f *>(x + (long long)jb * 4);
-            prod[g] = a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+            const v4f b = *reinterpret_cast<const v4f *>(x + (long long)jb[g] * 4);
+            prod[g] = a[g].x * b.x + a[g].y * b.y + a[g].z * b.z + a[g].w * b.w;
         }
     }
 
-    const int r0 = tile_row[t], r1 = tile_row[t + 1];
-    const bool has_carry = (t > 0) && (pos[r0] < t0);
-    const int rbeg = (t == 0) ? 0 : r0;
-    const int rend = (pos[r1] == t1) ? r1 : r1 + 1;
+    const bool has_carry = (t > 0) && (p_r0 < t0);
+    const int rend = (p_r1 == t1) ? r1 : r1 + 1;
     if (tid == 0 && !has_carry) carry_row[t] = -1;
 
     if (rend - rbeg == 1) {   // the tile lies inside one block row
@@ -89,7 +109,8 @@ __global__ __launch_bounds__(256) void k_spmv_bcsr4(int brows, int nblocks, cons
     for (int rb = rbeg; rb < rend; rb += THREADS / 4) {
         const int r = rb + (tid >> 2);
         if (r < rend) {
-            int lo = pos[r] - t0, hi = pos[r + 1] - t0;
+            int lo = my_lo - t0, hi = my_hi - t0;
+            if (r + THREADS / 4 < rend) { my_lo = pos[r + THREADS / 4]; my_hi = pos[r + THREADS / 4 + 1]; }
             lo = lo < 0 ? 0 : lo;
             hi = hi > cnt ? cnt : hi;
             if (hi - lo < LONG) {

@@ -58,14 +58,15 @@ __device__ __forceinline__ void run_select(const RunPlan &p, v4f_u wA, v4f_u wB,
     g[3] = p.lenA == 4 ? wA.w : (p.lenA == 3 ? wB.x : (p.lenA == 2 ? wB.y : wB.z));
 }
 
-template <int THREADS, int NPT, int MODE>
+template <int THREADS, int NPT, int MODE, bool WIN>
 __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nnz, const int *__restrict__ pos,
                                                       const int *__restrict__ crd,
                                                       const float *__restrict__ vals,
                                                       const float *__restrict__ x, float *__restrict__ y,
                                                       const int *__restrict__ tile_row,
                                                       int *__restrict__ carry_row,
-                                                      float *__restrict__ carry_val, int ntiles)
+                                                      float *__restrict__ carry_val, int ntiles, int clo,
+                                                      int chi, int accum)
 {
     constexpr int T = THREADS * NPT;
     constexpr int NW = THREADS / WAVE;
@@ -133,7 +134,15 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
                 plan[g] = run_plan(cv[g], cols);
                 ok = ok && plan[g].ok;
             }
-            if (__ballot(!ok) == 0ull) {
+            if (WIN) {      // a column pass: only columns in [clo, chi)
+#pragma unroll
+                for (int g = 0; g < NPT / 4; ++g) {
+                    xg[g][0] = (cv[g].x >= clo && cv[g].x < chi) ? x[cv[g].x] : 0.0f;
+                    xg[g][1] = (cv[g].y >= clo && cv[g].y < chi) ? x[cv[g].y] : 0.0f;
+                    xg[g][2] = (cv[g].z >= clo && cv[g].z < chi) ? x[cv[g].z] : 0.0f;
+                    xg[g][3] = (cv[g].w >= clo && cv[g].w < chi) ? x[cv[g].w] : 0.0f;
+                }
+            } else if (__ballot(!ok) == 0ull) {
                 v4f_u wA[NPT / 4], wB[NPT / 4];
 #pragma unroll
                 for (int g = 0; g < NPT / 4; ++g) {
@@ -160,19 +169,34 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
             }
         } else {
 #pragma unroll
-            for (int g = 0; g < NPT; ++g) prod[g] = vs[g] * x[cs[g]];
+            for (int g = 0; g < NPT; ++g)
+                prod[g] = (!WIN || (cs[g] >= clo && cs[g] < chi)) ? vs[g] * x[cs[g]] : 0.0f;
         }
     } else {   // last tile: guarded
 #pragma unroll
         for (int g = 0; g < NPT; ++g) {
             const int i = tile_index<MODE, THREADS>(g, tid);
-            prod[g] = (i < cnt) ? vals[t0 + i] * x[crd[t0 + i]] : 0.0f;
+            float pr = 0.0f;
+            if (i < cnt) {
+                const int c = crd[t0 + i];
+                if (!WIN || (c >= clo && c < chi)) pr = vals[t0 + i] * x[c];
+            }
+            prod[g] = pr;
         }
     }
 
     const bool has_carry = (t > 0) && (p_r0 < t0);
     const int rend = (p_r1 == t1) ? r1 : r1 + 1;   // last tile: r1 = rows and pos[rows] = nnz = t1
     if (tid == 0 && !has_carry) carry_row[t] = -1;
+    // a later column pass adds to what the first one stored (same lane, same order: deterministic)
+    auto emit = [&](int r, float v) {
+        if (has_carry && r == r0) {
+            carry_row[t] = r;
+            carry_val[t] = (WIN && accum) ? carry_val[t] + v : v;
+        } else {
+            y[r] = (WIN && accum) ? y[r] + v : v;
+        }
+    };
 
     // ---- 3a. the tile lies inside a single row
     if (rend - rbeg == 1) {
@@ -186,8 +210,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
             float tot = swave[0];
 #pragma unroll
             for (int w = 1; w < NW; ++w) tot += swave[w];
-            if (has_carry) { carry_row[t] = rbeg; carry_val[t] = tot; }
-            else y[rbeg] = tot;
+            emit(rbeg, tot);
         }
         return;
     }
@@ -205,10 +228,17 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
         lo = lo < 0 ? 0 : lo;
         hi = hi > cnt ? cnt : hi;
         if (hi - lo < LONG) {
+            // serial, in position order; four reads are issued before their adds so that the LDS
+            // latency is paid once per four elements
             float s = 0.0f;
-            for (int i = lo; i < hi; ++i) s += sprod[skew<1>(i)];
-            if (has_carry && r == r0) { carry_row[t] = r; carry_val[t] = s; }
-            else y[r] = s;
+            int i = lo;
+            for (; i + 4 <= hi; i += 4) {
+                const float a = sprod[skew<1>(i)], b = sprod[skew<1>(i + 1)], c = sprod[skew<1>(i + 2)],
+                            d = sprod[skew<1>(i + 3)];
+                s += a; s += b; s += c; s += d;
+            }
+            for (; i < hi; ++i) s += sprod[skew<1>(i)];
+            emit(r, s);
         } else {
             const int e = atomicAdd(&nlong, 1);
             if (e < MAXLONG) { slong[3 * e] = r; slong[3 * e + 1] = lo; slong[3 * e + 2] = hi; }
@@ -221,10 +251,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
         float s = 0.0f;
         for (int i = lo + lane; i < hi; i += WAVE) s += sprod[skew<1>(i)];
         s = wave_sum(s);
-        if (lane == 0) {
-            if (has_carry && r == r0) { carry_row[t] = r; carry_val[t] = s; }
-            else y[r] = s;
-        }
+        if (lane == 0) emit(r, s);
     }
 }
 
@@ -235,32 +262,39 @@ bool spmv_csr_tile_ok(int32_t tile)
 
 template <int THREADS, int NPT>
 static void launch_pos(int mode, int grid, hipStream_t s, int rows, int cols, int nnz, const int *pos, const int *crd,
-                       const float *vals, const float *x, float *y, const Workspace &w, int ntiles)
+                       const float *vals, const float *x, float *y, const Workspace &w, int ntiles, int clo, int chi,
+                       int accum)
 {
-#define PSK_GO(M)                                                                                               \
-    hipLaunchKernelGGL((k_spmv_pos<THREADS, NPT, M>), dim3(grid), dim3(THREADS), 0, s, rows, cols, nnz, pos, crd, \
-                       vals, x, y, w.tile_row, w.carry_row, w.carry_val, ntiles)
-    if (mode == 1) PSK_GO(1);
-    else PSK_GO(0);
+#define PSK_GO(M, W)                                                                                             \
+    hipLaunchKernelGGL((k_spmv_pos<THREADS, NPT, M, W>), dim3(grid), dim3(THREADS), 0, s, rows, cols, nnz, pos,  \
+                       crd, vals, x, y, w.tile_row, w.carry_row, w.carry_val, ntiles, clo, chi, accum)
+    const bool win = clo > 0 || chi < cols;
+    if (mode == 1) { if (win) PSK_GO(1, true); else PSK_GO(1, false); }
+    else { if (win) PSK_GO(0, true); else PSK_GO(0, false); }
 #undef PSK_GO
 }
 
 hipError_t launch_spmv_csr_main(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
-                                const float *vals, const float *x, float *y, int32_t tile,
+                                const float *vals, const float *x, float *y, int32_t tile, int32_t col_passes,
                                 const Workspace &w, hipStream_t s)
 {
     const int ntiles = (int)(((int64_t)nnz + tile - 1) / tile);
     if (ntiles == 0) return hipSuccess;
     const int grid = xcd_grid(ntiles);
+    if (col_passes < 1) col_passes = 1;
+    for (int p = 0; p < col_passes; ++p) {
+    const int clo = (int)((int64_t)cols * p / col_passes), chi = (int)((int64_t)cols * (p + 1) / col_passes);
+    const int accum = p > 0;
     const bool aligned = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
     const int vec = aligned ? 1 : 0;
     switch (tile) {
-        case 256:  launch_pos<64, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles); break;
-        case 512:  launch_pos<128, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles); break;
-        case 1024: launch_pos<256, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles); break;
-        case 2048: launch_pos<256, 8>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles); break;
-        case 4096: launch_pos<256, 16>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles); break;
+        case 256:  launch_pos<64, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
+        case 512:  launch_pos<128, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
+        case 1024: launch_pos<256, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
+        case 2048: launch_pos<256, 8>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
+        case 4096: launch_pos<256, 16>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
         default: return hipErrorInvalidValue;
+    }
     }
     return hipGetLastError();
 }

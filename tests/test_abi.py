@@ -50,32 +50,37 @@ def test_argument_errors_are_reported_before_any_launch():
     null = ctypes.c_void_p(0)
     big = 1 << 20
     # SIZE
-    assert L.psk_spmv_csr(-1, 4, 0, one, one, one, one, one, 0, 7, one, big, null) == 2
-    assert L.psk_spmv_csr(4, 4, 2 ** 31, one, one, one, one, one, 0, 7, one, big, null) == 2
-    assert L.psk_spmv_csr(0, 4, 5, one, one, one, one, one, 0, 7, one, big, null) == 2
+    assert L.psk_spmv_csr(-1, 4, 0, one, one, one, one, one, 0, 1, 7, one, big, null) == 2
+    assert L.psk_spmv_csr(4, 4, 2 ** 31, one, one, one, one, one, 0, 1, 7, one, big, null) == 2
+    assert L.psk_spmv_csr(0, 4, 5, one, one, one, one, one, 0, 1, 7, one, big, null) == 2
     assert L.psk_spmm_csr(4, 4, 4, one, one, one, one, 0, 8, one, 8, 0, 7, one, big, null) == 2       # k = 0
     assert L.psk_spmm_csr(4, 4, 4, one, one, one, one, 8, 4, one, 8, 0, 7, one, big, null) == 2       # ldb < k
     assert L.psk_spmv_bcsr(4, 4, 4, 0, one, one, one, one, one, 0, 7, one, big, null) == 2            # bs = 0
     # NULL
-    assert L.psk_spmv_csr(4, 4, 4, null, one, one, one, one, 0, 7, one, big, null) == 1
-    assert L.psk_spmv_csr(4, 4, 4, one, null, one, one, one, 0, 7, one, big, null) == 1
-    assert L.psk_spmv_csr(4, 4, 4, one, one, one, null, one, 0, 7, one, big, null) == 1
-    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, null, 0, 7, one, big, null) == 1
+    assert L.psk_spmv_csr(4, 4, 4, null, one, one, one, one, 0, 1, 7, one, big, null) == 1
+    assert L.psk_spmv_csr(4, 4, 4, one, null, one, one, one, 0, 1, 7, one, big, null) == 1
+    assert L.psk_spmv_csr(4, 4, 4, one, one, one, null, one, 0, 1, 7, one, big, null) == 1
+    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, null, 0, 1, 7, one, big, null) == 1
     assert L.psk_partition_csr(4, 4, null, 4, 0, one, null) == 1
     # TILE
-    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 1000, 7, one, big, null) == 3
+    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 1000, 1, 7, one, big, null) == 3
     assert L.psk_spmm_csr(4, 4, 4, one, one, one, one, 8, 8, one, 8, 4096, 7, one, big, null) == 3
     assert L.psk_partition_csr(4, 4, one, 0, 0, one, null) == 3
     assert L.psk_partition_csr(4, 4, one, 4, 3, one, null) == 5
     # WORKSPACE
-    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 7, null, big, null) == 4
-    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 7, one, 16, null) == 4
-    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 7, ctypes.c_void_p(264), big, null) == 4
+    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 1, 7, null, big, null) == 4
+    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 1, 7, one, 16, null) == 4
+    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 1, 7, ctypes.c_void_p(264), big, null) == 4
     # UNSUPPORTED
-    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 0, one, big, null) == 5
-    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 8, one, big, null) == 5
+    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 1, 0, one, big, null) == 5
+    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 1, 8, one, big, null) == 5
     assert L.psk_spmv_bcsr(4, 4, 4, 2, one, one, one, one, one, 0, 7, one, big, null) == 5
     assert L.psk_spmv_csr_rowsplit(4, 4, 4, one, one, one, one, one, 2, null) == 5
+    assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 9, 7, one, big, null) == 2                # col_passes
+    out = ctypes.c_int32(-1)
+    assert L.psk_analyze_csr(4, 4, 4, one, one, null, 0, ctypes.byref(out), null) == 4
+    assert L.psk_analyze_csr(4, 4, 4, one, one, one, 256, None, null) == 1
+    assert L.psk_analyze_csr(4, 4, 4, one, one, one, 256, ctypes.byref(out), null) == 0 and out.value == 1   # small: no launch
     # ALIGNMENT (BCSR)
     assert L.psk_spmv_bcsr(4, 4, 4, 4, one, one, ctypes.c_void_p(260), one, one, 0, 7, one, big, null) == 7
 

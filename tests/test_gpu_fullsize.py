@@ -61,6 +61,12 @@ def test_spmv_full_size(n):
     psk.psk_spmv_csr(A.rows, A.cols, A.nnz, pos, crd, vals, x, y, ws=ws)
     torch.cuda.synchronize()
     assert torch.equal(first, y)
+    passes = psk.psk_analyze_csr(A.rows, A.cols, A.nnz, pos, crd)
+    if passes > 1:
+        y.fill_(float("nan"))
+        psk.psk_spmv_csr(A.rows, A.cols, A.nnz, pos, crd, vals, x, y, col_passes=passes, ws=ws)
+        torch.cuda.synchronize()
+        check(y.cpu().numpy(), ref, mag, "config %d full, %d column passes" % (n, passes))
     if n == 2:   # the wave-per-row baseline agrees within twice the bound (three-way check)
         psk.psk_spmv_csr_rowsplit(A.rows, A.cols, A.nnz, pos, crd, vals, x, y, variant=1)
         torch.cuda.synchronize()
@@ -99,3 +105,11 @@ def test_bcsr_full_size():
     ref, mag = oracle.spmm_bcsr(A.pos, A.crd, A.vals, c["B"], 4, sel=sel, threads=16)
     got = C.view(A.rows, 4, 64)[torch.from_numpy(sel).cuda()].reshape(-1, 64).cpu().numpy()
     check(got, ref, mag, "config 5 spmm sampled block rows")
+
+
+def test_analyze_full_size():
+    """Scattered columns over an x of 8 MB: two passes; the banded stencil (x of 16 MB): one."""
+    A = wl.config(2)["A"]
+    assert psk.psk_analyze_csr(A.rows, A.cols, A.nnz, dev(A.pos), dev(A.crd)) == 2
+    A = wl.config(3)["A"]
+    assert psk.psk_analyze_csr(A.rows, A.cols, A.nnz, dev(A.pos), dev(A.crd)) == 1

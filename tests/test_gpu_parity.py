@@ -290,3 +290,28 @@ def test_three_way_agreement_and_tile_invariance():
     ys.append(yw.cpu().numpy())
     for a in ys[1:]:
         assert (np.abs(a.astype(np.float64) - ys[0].astype(np.float64)) <= bound).all()
+
+
+# ------------------------------------------------------------------ column passes
+@pytest.mark.parametrize("passes", [2, 3, 4])
+def test_spmv_column_passes(passes):
+    rng = np.random.default_rng(passes)
+    cases = [("powerlaw", wl.config(2, 0.02)["A"])]
+    for kind in ("mixed", "one_row_has_all", "mostly_empty", "all_empty", "single_long_rows"):
+        cases.append((kind, wl.csr_from_lengths(adversarial_lengths(rng, 3001, 5003, kind), 5003, seed=61)))
+    for name, A in cases:
+        x = wl.dense_uniform(A.cols, 61, wl.S_X)
+        ref, mag = oracle.spmv_csr(A.pos, A.crd, A.vals, x, threads=8)
+        D, xd = DevCSR(A), dev(x)
+        for tile in (0, 256, 4096):
+            say("column passes", passes, name, "tile", tile)
+            got = run_spmv(D, xd, tile, col_passes=passes)
+            check(got, ref, mag, "passes %d %s tile %d" % (passes, name, tile))
+            again = run_spmv(D, xd, tile, col_passes=passes)
+            assert (got == again).all()          # still deterministic
+
+
+def test_analyze_small_problems_need_no_passes():
+    A = wl.config(2, 0.02)["A"]
+    D = DevCSR(A)
+    assert psk.psk_analyze_csr(A.rows, A.cols, A.nnz, D.pos, D.crd) == 1
