@@ -18,6 +18,10 @@ Workloads (names of the evaluated configurations):
   bcsr_spmm           BCSR 4x4 SpMM with 64 dense columns
   uniform28           CSR SpMV, 2M x 2M, exactly 28 per row at uniform random columns (the uniform
                       matrix of the power-law matrix's size class, for the per-nnz comparison)
+  fewlong             CSR SpMV, 100 x 100000 with 10000 per row (Section 8.5: too few rows for a
+                      row-split kernel to fill the GPU)
+  expskew             CSR SpMV, 65536 x 1M, 4M nonzeros, row lengths ~ base**rank shuffled
+                      (Section 8.4; --skew-base, default 1.00256)
   copy                not a product: a plain device copy of 1 GiB, the calibration kernel for the
                       rocprofv3 FETCH_SIZE / WRITE_SIZE counters and the practical HBM ceiling
 """
@@ -48,6 +52,8 @@ WORKLOADS = {
     "bcsr_spmv": (5, "bcsr_spmv"),
     "bcsr_spmm": (5, "bcsr_spmm"),
     "uniform28": (0, "csr_spmv"),
+    "fewlong": (0, "csr_spmv"),
+    "expskew": (0, "csr_spmv"),
     "copy": (0, "copy"),
 }
 
@@ -109,6 +115,7 @@ def main():
     ap.add_argument("--tile", type=int, default=0, help="position-tile size (0 = library default)")
     ap.add_argument("--col-passes", type=int, default=0,
                     help="column passes of the CSR SpMV (0 = ask psk_analyze_csr)")
+    ap.add_argument("--skew-base", type=float, default=1.00256, help="base of the expskew workload")
     ap.add_argument("--copies", type=int, default=0, help="operand copies rotated between steps (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--baselines", action="store_true", help="also time the row-split kernels")
@@ -134,6 +141,13 @@ def main():
     if args.workload == "uniform28":
         A28 = wl.csr_uniform(2_000_000, 2_000_000, 28, wl.BASE_SEED + 6)
         cfg = {"A": A28, "x": wl.dense_uniform(2_000_000, wl.BASE_SEED + 6, wl.S_X)}
+    elif args.workload == "fewlong":
+        Af = wl.csr_uniform(100, 100_000, 10_000, wl.BASE_SEED + 7)
+        cfg = {"A": Af, "x": wl.dense_uniform(100_000, wl.BASE_SEED + 7, wl.S_X)}
+    elif args.workload == "expskew":
+        Ls = wl.exponential_lengths(65536, 4_000_000, args.skew_base, 1_000_000, wl.BASE_SEED + 8)
+        Ae = wl.csr_from_lengths(Ls, 1_000_000, wl.BASE_SEED + 8)
+        cfg = {"A": Ae, "x": wl.dense_uniform(1_000_000, wl.BASE_SEED + 8, wl.S_X)}
     else:
         cfg = wl.config(cfg_no)
     A = cfg["A"]

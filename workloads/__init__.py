@@ -125,6 +125,17 @@ def csr_powerlaw(rows: int, cols: int, alpha: float, kmin: int, kmax: int, seed:
     return csr_from_lengths(zipf_lengths(rows, alpha, kmin, min(kmax, cols), seed), cols, seed)
 
 
+def exponential_lengths(rows: int, total: int, base: float, cols: int, seed: int) -> np.ndarray:
+    """Row lengths proportional to base**rank, scaled to about `total` stored entries, capped at
+    `cols`, then shuffled (the skew experiment of Section 8.4: nnz fixed, skew set by the base of an
+    exponential, rows in random order).  base = 1 gives equal rows."""
+    rank = np.arange(rows, dtype=np.float64)
+    w = np.exp((rank - (rows - 1)) * np.log(base)) if base > 1.0 else np.ones(rows)
+    L = np.minimum(np.floor(w / w.sum() * total + 0.5), cols).astype(np.int64)
+    order = np.argsort(dense_uniform(rows, seed, S_LEN), kind="stable")
+    return L[order]
+
+
 def csr_stencil27(n: int, seed: int) -> CSR:
     """27-point stencil on an n^3 grid, clipped at the faces; diagonal 27,
     off-diagonals uniform in [0.5, 1.5)."""
