@@ -39,9 +39,14 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
 # scaled by the copy-kernel calibration; the summaries are under profiles/.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # (workload, tile, col_passes): bytes
-    ("powerlaw", 2048, 1): 3563010542,     # profiles/k_spmv_pos_powerlaw_1pass.txt
-    ("stencil", 2048, 1): 929657400,       # profiles/k_spmv_pos_stencil.txt
+    # (workload, tile, col_passes): bytes per launch of the tile kernel
+    ("powerlaw", 2048, 2): 699619113,      # profiles/k_spmv_pos_powerlaw_2passes.txt
+    ("powerlaw", 2048, 1): 3559120490,     # profiles/k_spmv_pos_powerlaw_1pass.txt
+    ("uniform28", 2048, 2): 678257792,     # profiles/k_spmv_pos_uniform28.txt
+    ("stencil", 2048, 1): 929642938,       # profiles/k_spmv_pos_stencil.txt
+    ("spmm", 512, 1): 8774441013,          # profiles/k_spmm_pos_csr_spmm_k128.txt
+    ("bcsr_spmv", 512, 1): 191984843,      # profiles/k_spmv_bcsr4_bcsr_spmv.txt
+    ("bcsr_spmm", 64, 1): 2411752469,      # profiles/k_spmm_pos_bcsr_spmm_n64.txt
 }
 
 WORKLOADS = {
@@ -231,6 +236,8 @@ def main():
     kernel_bytes = noreuse_bytes if kind.endswith("spmm") else comp_bytes
     achieved = kernel_bytes / (main_avg * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, tile, col_passes))
+    if traffic is not None:
+        traffic *= col_passes           # like `achieved`: all launches of the tile kernel in one product
 
     rec = {
         "metric": "SpMV/SpMM GFLOP/s and achieved HBM GB/s (% of MI355X peak), 1 GPU",
