@@ -40,9 +40,9 @@ HBM_PEAK_GBS = 8000.0
 # scaled by the copy-kernel calibration; the summaries are under profiles/.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
     # (workload, tile, col_passes): bytes per launch of the tile kernel
-    ("powerlaw", 2048, 2): 699619113,      # profiles/k_spmv_pos_powerlaw_2passes.txt
+    ("powerlaw", 1024, 2): 699619113,      # profiles/k_spmv_pos_powerlaw_2passes.txt
     ("powerlaw", 2048, 1): 3559120490,     # profiles/k_spmv_pos_powerlaw_1pass.txt
-    ("uniform28", 2048, 2): 678257792,     # profiles/k_spmv_pos_uniform28.txt
+    ("uniform28", 1024, 2): 678257792,     # profiles/k_spmv_pos_uniform28.txt
     ("stencil", 2048, 1): 929642938,       # profiles/k_spmv_pos_stencil.txt
     ("spmm", 512, 1): 8774441013,          # profiles/k_spmm_pos_csr_spmm_k128.txt
     ("bcsr_spmv", 512, 1): 191984843,      # profiles/k_spmv_bcsr4_bcsr_spmv.txt
@@ -167,6 +167,7 @@ def main():
     op = {"csr_spmv": psk.PSK_OP_SPMV_CSR, "csr_spmm": psk.PSK_OP_SPMM_CSR, "bcsr_spmv": psk.PSK_OP_SPMV_BCSR,
           "bcsr_spmm": psk.PSK_OP_SPMM_BCSR}[kind]
     tile = args.tile or psk.psk_default_tile(op)
+    tile_given = bool(args.tile)
 
     # rotate over enough operand copies that a step never finds its inputs in the 256 MB memory-side cache
     copies = args.copies or max(2, min(8, int(np.ceil(1.0e9 / comp_bytes))))
@@ -176,7 +177,6 @@ def main():
         s = {"pos": torch.from_numpy(A.pos).to(dev), "crd": torch.from_numpy(A.crd).to(dev),
              "vals": torch.from_numpy(A.vals).to(dev), "dense": torch.from_numpy(dense_h).to(dev)}
         s["out"] = torch.empty((out_rows, k) if kind.endswith("spmm") else (out_rows,), device=dev)
-        s["ws"] = psk.workspace(op, A.rows, A.nnz, k=k, bs=A.bs, tile=tile, device=dev)
         sets.append(s)
     stream = torch.cuda.current_stream()
 
@@ -185,6 +185,10 @@ def main():
     if kind == "csr_spmv":
         col_passes = args.col_passes or psk.psk_analyze_csr(A.rows, A.cols, A.nnz, sets[0]["pos"], sets[0]["crd"],
                                                             stream=stream)
+        if col_passes > 1 and not tile_given:
+            tile = 1024      # what tile = 0 selects inside the library when column passes are on
+    for s in sets:
+        s["ws"] = psk.workspace(op, A.rows, A.nnz, k=k, bs=A.bs, tile=tile, device=dev)
 
     def step(s, phases=psk.PSK_PHASE_ALL):
         if kind == "csr_spmv":

@@ -95,7 +95,8 @@ int64_t psk_num_tiles(int64_t nnz, int32_t tile)
 size_t psk_workspace_bytes(int op, int64_t rows, int64_t nnz, int32_t k, int32_t bs, int32_t tile)
 {
     (void)rows;
-    if (tile == 0) tile = default_tile(op);
+    // CSR SpMV picks 2048, or 1024 with column passes: size for the smaller one, which needs more
+    if (tile == 0) tile = op == PSK_OP_SPMV_CSR ? 1024 : default_tile(op);
     if (tile <= 0 || nnz < 0 || nnz > kMaxI32) return 0;
     if ((op == PSK_OP_SPMM_CSR || op == PSK_OP_SPMM_BCSR) && k <= 0) return 0;
     if ((op == PSK_OP_SPMV_BCSR || op == PSK_OP_SPMM_BCSR) && bs <= 0) return 0;
@@ -142,6 +143,7 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
                  void *workspace, size_t workspace_bytes, void *stream)
 {
     if (col_passes < 0 || col_passes > PSK_MAX_COL_PASSES) return PSK_ERR_SIZE;
+    if (tile == 0 && col_passes > 1) tile = 1024;   // gather-bound passes prefer the smaller tile (measured)
     Workspace ws;
     int st = check_common(PSK_OP_SPMV_CSR, rows, cols, nnz, pos, crd, vals, 1, 1, &tile, phases, workspace,
                           workspace_bytes, &ws);
