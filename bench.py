@@ -307,6 +307,18 @@ def main():
                 if i >= 4:
                     ts.append(e0.elapsed_time(e1))
             base[name + "_us_median"] = round(statistics.median(ts) * 1e3, 2)
+        ts = []
+        for i in range(12):     # the schedule's atomics strategy: zero-fill + tile kernel, no fix-up
+            s = sets[i % copies]
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            psk.psk_spmv_csr_atomics(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"],
+                                     tile=args.tile, ws=s["ws"], stream=stream)
+            e1.record(stream)
+            e1.synchronize()
+            if i >= 4:
+                ts.append(e0.elapsed_time(e1))
+        base["position_space_atomics_us_median"] = round(statistics.median(ts) * 1e3, 2)
         rec["rowsplit_baselines"] = base
 
     # ---- the CPU oracle on this machine's host cores (a baseline, not a target)

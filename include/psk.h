@@ -190,6 +190,19 @@ int psk_spmv_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t
                           const int32_t *crd, const float *vals, const float *x, float *y,
                           int variant, void *stream);
 
+/*
+ * Baseline with the schedule's own race strategy (appendix "SPMV on a GPU": the thread level is
+ * parallelised with OutputRaceStrategy::Atomics; Section 6.3, first strategy): same position cut and tile
+ * kernel as psk_spmv_csr, but y is zero-filled first and the part of a row that other tiles also hold is
+ * added with a floating-point atomic instead of going through a carry record.  No fix-up step
+ * (PSK_PHASE_FIXUP is ignored).  The order of the atomic adds is not fixed, so rows that span tiles are
+ * NOT bit-reproducible from run to run; they stay within the fp32 tolerance.  Same workspace as
+ * psk_spmv_csr (only the tile->row table is used).
+ */
+int psk_spmv_csr_atomics(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                         const float *vals, const float *x, float *y, int32_t tile, int phases,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
 /* Row-split SpMM baseline: one wave per row, lanes over the columns of B. */
 int psk_spmm_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos,
                           const int32_t *crd, const float *vals, const float *B, int32_t k,

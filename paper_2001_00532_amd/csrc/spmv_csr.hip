@@ -58,7 +58,9 @@ __device__ __forceinline__ void run_select(const RunPlan &p, v4f_u wA, v4f_u wB,
     g[3] = p.lenA == 4 ? wA.w : (p.lenA == 3 ? wB.x : (p.lenA == 2 ? wB.y : wB.z));
 }
 
-template <int THREADS, int NPT, int MODE, bool WIN>
+// VARIANT 0: one pass, carries.  1: a column pass (window [clo, chi), accum adds to earlier passes).
+// 2: one pass with the schedule's atomics instead of carries (baseline).
+template <int THREADS, int NPT, int MODE, int VARIANT>
 __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nnz, const int *__restrict__ pos,
                                                       const int *__restrict__ crd,
                                                       const float *__restrict__ vals,
@@ -73,6 +75,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
     constexpr int LONG = 32;
     constexpr int MAXLONG = T / LONG;
     constexpr bool VEC = MODE != 0;
+    constexpr bool WIN = VARIANT == 1, ATOM = VARIANT == 2;
     static_assert(NPT % 4 == 0, "NPT must be a multiple of 4");
     __shared__ float sprod[skewed_size<1>(T)];
     __shared__ int slong[MAXLONG * 3];
@@ -187,9 +190,16 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
 
     const bool has_carry = (t > 0) && (p_r0 < t0);
     const int rend = (p_r1 == t1) ? r1 : r1 + 1;   // last tile: r1 = rows and pos[rows] = nnz = t1
-    if (tid == 0 && !has_carry) carry_row[t] = -1;
+    if (tid == 0 && !has_carry && !ATOM) carry_row[t] = -1;
     // a later column pass adds to what the first one stored (same lane, same order: deterministic)
     auto emit = [&](int r, float v) {
+        if (ATOM) {
+            // the schedule's own race strategy (appendix "SPMV on a GPU": Atomics): y was zero-filled;
+            // a row that other tiles also hold part of is added atomically, the rest is stored
+            if ((has_carry && r == r0) || (p_r1 != t1 && r == r1)) unsafeAtomicAdd(&y[r], v);
+            else y[r] = v;
+            return;
+        }
         if (has_carry && r == r0) {
             carry_row[t] = r;
             carry_val[t] = (WIN && accum) ? carry_val[t] + v : v;
@@ -268,9 +278,9 @@ static void launch_pos(int mode, int grid, hipStream_t s, int rows, int cols, in
 #define PSK_GO(M, W)                                                                                             \
     hipLaunchKernelGGL((k_spmv_pos<THREADS, NPT, M, W>), dim3(grid), dim3(THREADS), 0, s, rows, cols, nnz, pos,  \
                        crd, vals, x, y, w.tile_row, w.carry_row, w.carry_val, ntiles, clo, chi, accum)
-    const bool win = clo > 0 || chi < cols;
-    if (mode == 1) { if (win) PSK_GO(1, true); else PSK_GO(1, false); }
-    else { if (win) PSK_GO(0, true); else PSK_GO(0, false); }
+    const int variant = accum == 2 ? 2 : ((clo > 0 || chi < cols) ? 1 : 0);
+    if (mode == 1) { if (variant == 2) PSK_GO(1, 2); else if (variant == 1) PSK_GO(1, 1); else PSK_GO(1, 0); }
+    else { if (variant == 2) PSK_GO(0, 2); else if (variant == 1) PSK_GO(0, 1); else PSK_GO(0, 0); }
 #undef PSK_GO
 }
 
@@ -281,10 +291,11 @@ hipError_t launch_spmv_csr_main(int32_t rows, int32_t cols, int32_t nnz, const i
     const int ntiles = (int)(((int64_t)nnz + tile - 1) / tile);
     if (ntiles == 0) return hipSuccess;
     const int grid = xcd_grid(ntiles);
+    const bool atomics = col_passes < 0;          // baseline: one pass, atomic adds for rows that span tiles
     if (col_passes < 1) col_passes = 1;
     for (int p = 0; p < col_passes; ++p) {
     const int clo = (int)((int64_t)cols * p / col_passes), chi = (int)((int64_t)cols * (p + 1) / col_passes);
-    const int accum = p > 0;
+    const int accum = atomics ? 2 : (p > 0);
     const bool aligned = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
     const int vec = aligned ? 1 : 0;
     switch (tile) {

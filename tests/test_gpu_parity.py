@@ -315,3 +315,21 @@ def test_analyze_small_problems_need_no_passes():
     A = wl.config(2, 0.02)["A"]
     D = DevCSR(A)
     assert psk.psk_analyze_csr(A.rows, A.cols, A.nnz, D.pos, D.crd) == 1
+
+
+# ------------------------------------------------------------------ the schedule's atomics strategy (baseline)
+def test_spmv_atomics_baseline():
+    rng = np.random.default_rng(8)
+    cases = [("powerlaw", wl.config(2, 0.02)["A"]), ("stencil", wl.config(3, 0.01)["A"])]
+    for kind in ("mixed", "one_row_has_all", "all_empty", "single_long_rows", "empty_head_tail"):
+        cases.append((kind, wl.csr_from_lengths(adversarial_lengths(rng, 3001, 5003, kind), 5003, seed=71)))
+    for name, A in cases:
+        x = wl.dense_uniform(A.cols, 71, wl.S_X)
+        ref, mag = oracle.spmv_csr(A.pos, A.crd, A.vals, x, threads=8)
+        D, xd = DevCSR(A), dev(x)
+        for tile in (0, 256, 1024):
+            say("atomics", name, "tile", tile)
+            y = torch.full((A.rows,), float("nan"), device="cuda")
+            psk.psk_spmv_csr_atomics(A.rows, A.cols, A.nnz, D.pos, D.crd, D.vals, xd, y, tile=tile)
+            torch.cuda.synchronize()
+            check(y.cpu().numpy(), ref, mag, "atomics %s tile %d" % (name, tile))
