@@ -333,3 +333,59 @@ def test_spmv_atomics_baseline():
             psk.psk_spmv_csr_atomics(A.rows, A.cols, A.nnz, D.pos, D.crd, D.vals, xd, y, tile=tile)
             torch.cuda.synchronize()
             check(y.cpu().numpy(), ref, mag, "atomics %s tile %d" % (name, tile))
+
+
+# ------------------------------------------------------------------ randomised shapes
+def test_random_shapes_all_operations():
+    """Sixty seeded random problems: sizes, row-length mixes, tiles, dense widths and pass counts drawn
+    at random; every operation against the oracle."""
+    rng = np.random.default_rng(20010532)
+    for case in range(60):
+        rows = int(rng.integers(1, 4000))
+        cols = int(rng.integers(1, 6000))
+        style = rng.integers(0, 4)
+        if style == 0:
+            L = rng.integers(0, min(cols, 12) + 1, size=rows)
+        elif style == 1:
+            L = np.where(rng.random(rows) < 0.9, 0, rng.integers(0, min(cols, 400) + 1, size=rows))
+        elif style == 2:
+            L = np.minimum(rng.zipf(1.6, size=rows), cols)
+        else:
+            L = np.zeros(rows, dtype=np.int64)
+            L[rng.integers(0, rows, size=3)] = min(cols, int(rng.integers(1, 6000)))
+        seed = 1000 + case
+        A = wl.csr_from_lengths(L, cols, seed=seed)
+        x = wl.dense_uniform(cols, seed, wl.S_X)
+        k = int(rng.choice([1, 3, 32, 64, 65, 128, 200]))
+        B = wl.dense_uniform(cols * k, seed, wl.S_B).reshape(cols, k)
+        tile_v = int(rng.choice([0, 256, 512, 1024, 2048, 4096]))
+        tile_m = int(rng.choice([0, 256, 512, 1024, 2048]))
+        passes = int(rng.choice([1, 1, 2, 3, 4]))
+        say("random case", case, "rows", rows, "cols", cols, "nnz", A.nnz, "style", int(style), "k", k,
+            "tiles", tile_v, tile_m, "passes", passes)
+        D, xd, Bd = DevCSR(A), dev(x), dev(B)
+        want = oracle.partition(A.pos, tile_v or 2048)
+        got = psk.psk_partition_csr(D.pos, A.nnz, tile_v or 2048).cpu().numpy()
+        assert (got == want).all()
+        ref, mag = oracle.spmv_csr(A.pos, A.crd, A.vals, x)
+        check(run_spmv(D, xd, tile_v, col_passes=passes), ref, mag, "random %d spmv" % case)
+        refC, magC = oracle.spmm_csr(A.pos, A.crd, A.vals, B)
+        check(run_spmm(D, Bd, tile_m), refC, magC, "random %d spmm" % case)
+        # the same pattern as a BCSR matrix of 4x4 blocks
+        Ab = wl.csr_from_lengths(L, cols, seed=seed, bs=4)
+        xb = wl.dense_uniform(cols * 4, seed, wl.S_X)
+        tile_b = int(rng.choice([0, 64, 128, 256, 512]))
+        Db = DevCSR(Ab)
+        yb = torch.full((rows * 4,), float("nan"), device="cuda")
+        psk.psk_spmv_bcsr(rows, cols, Ab.nnz, 4, Db.pos, Db.crd, Db.vals, dev(xb), yb, tile=tile_b)
+        torch.cuda.synchronize()
+        refb, magb = oracle.spmv_bcsr(Ab.pos, Ab.crd, Ab.vals, xb, 4)
+        check(yb.cpu().numpy(), refb, magb, "random %d bcsr spmv" % case)
+        if case % 4 == 0:
+            kb = int(rng.choice([8, 64, 100]))
+            Bb = wl.dense_uniform(cols * 4 * kb, seed, wl.S_B).reshape(cols * 4, kb)
+            Cb = torch.full((rows * 4, kb), float("nan"), device="cuda")
+            psk.psk_spmm_bcsr(rows, cols, Ab.nnz, 4, Db.pos, Db.crd, Db.vals, dev(Bb), Cb, tile=tile_b)
+            torch.cuda.synchronize()
+            refCb, magCb = oracle.spmm_bcsr(Ab.pos, Ab.crd, Ab.vals, Bb, 4)
+            check(Cb.cpu().numpy(), refCb, magCb, "random %d bcsr spmm" % case)
