@@ -18,6 +18,9 @@ Workloads (names of the evaluated configurations):
   bcsr_spmm           BCSR 4x4 SpMM with 64 dense columns
   uniform28           CSR SpMV, 2M x 2M, exactly 28 per row at uniform random columns (the uniform
                       matrix of the power-law matrix's size class, for the per-nnz comparison)
+  mttkrp              MTTKRP A(i,j) = B(i,k,l) C(k,j) D(l,j): B 500k x 100k x 100k in three compressed levels,
+                      ~4M fibers, ~46M nonzeros (Zipf leaves per fiber), j = 64 (the paper's third kernel;
+                      synthetic stand-in for the FROSTT tensors it uses)
   fewlong             CSR SpMV, 100 x 100000 with 10000 per row (Section 8.5: too few rows for a
                       row-split kernel to fill the GPU)
   expskew             CSR SpMV, 65536 x 1M, 4M nonzeros, row lengths ~ base**rank shuffled
@@ -57,6 +60,7 @@ WORKLOADS = {
     "bcsr_spmv": (5, "bcsr_spmv"),
     "bcsr_spmm": (5, "bcsr_spmm"),
     "uniform28": (0, "csr_spmv"),
+    "mttkrp": (0, "mttkrp"),
     "fewlong": (0, "csr_spmv"),
     "expskew": (0, "csr_spmv"),
     "copy": (0, "copy"),
@@ -111,6 +115,99 @@ def bench_copy(args, torch):
                       "config": {"workload": "copy: 2^28 fp32 elements, torch copy kernel"}}))
 
 
+def bench_mttkrp(args, torch, psk, wl):
+    """MTTKRP on the synthetic three-level tensor; same record layout as the matrix workloads."""
+    J = 64
+    t_gen = time.time()
+    T = wl.csf3_powerlaw(500_000, 100_000, 100_000, 8, 1.8, 4096, wl.BASE_SEED + 9)
+    I, K, L = T.dims
+    Ch = wl.dense_uniform(K * J, wl.BASE_SEED + 9, wl.S_B).reshape(K, J)
+    Dh = wl.dense_uniform(L * J, wl.BASE_SEED + 10, wl.S_B).reshape(L, J)
+    t_gen = time.time() - t_gen
+    nnz, nfib = T.nnz, T.nfibers
+    tile = args.tile or psk.psk_default_tile(psk.PSK_OP_MTTKRP_CSF3)
+    comp = 8 * nnz + 8 * nfib + 4 * (I + 1) + 4 * J * (K + L) + 4 * J * I
+    noreuse = 8 * nnz + 4 * J * nnz + 4 * J * nfib + 8 * nfib + 4 * (I + 1) + 4 * J * I
+    fl = 3 * J * nnz
+    dev = torch.device("cuda:0")
+    copies = args.copies or 2
+    sets = []
+    for _ in range(copies):
+        s = {k_: torch.from_numpy(getattr(T, k_)).to(dev) for k_ in ("pos_k", "crd_k", "pos_l", "crd_l", "vals")}
+        s["C"], s["D"] = torch.from_numpy(Ch).to(dev), torch.from_numpy(Dh).to(dev)
+        s["A"] = torch.empty((I, J), device=dev)
+        s["ws"] = psk.workspace(psk.PSK_OP_MTTKRP_CSF3, T.nslices, nnz, k=J, tile=tile, device=dev)
+        sets.append(s)
+    stream = torch.cuda.current_stream()
+
+    def step(s, phases=psk.PSK_PHASE_ALL):
+        psk.psk_mttkrp_csf3(T.dims, None, s["pos_k"], s["crd_k"], s["pos_l"], s["crd_l"], s["vals"], s["C"], s["D"],
+                            s["A"], tile=tile, phases=phases, ws=s["ws"], stream=stream)
+
+    for i in range(args.warmup):
+        step(sets[i % copies])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(sets[i % copies])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    def time_phase(phases, reps=16, warm=8):
+        ts = []
+        for i in range(warm + reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            step(sets[i % copies], phases)
+            e1.record(stream)
+            e1.synchronize()
+            if i >= warm:
+                ts.append(e0.elapsed_time(e1))
+        return ts
+
+    main_ms = time_phase(psk.PSK_PHASE_MAIN)
+    all_ms = time_phase(psk.PSK_PHASE_ALL)
+    main_avg = sum(main_ms) / len(main_ms)
+    achieved = noreuse / (main_avg * 1e-3) / 1e9
+    rec = {
+        "metric": "SpMV/SpMM GFLOP/s and achieved HBM GB/s (% of MI355X peak), 1 GPU",
+        "value": round(fl / (wall / args.steps) / 1e9, 3), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(wall / args.steps * 1e3, 6), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "mttkrp: %d x %d x %d, %d fibers, nnz %d, j %d, tile %d, %d operand copies rotated"
+                               % (I, K, L, nfib, nnz, J, tile, copies),
+                   "dims": [I, K, L], "fibers": nfib, "nnz": nnz, "j": J, "tile": tile, "seed": wl.BASE_SEED + 9},
+        "ns_per_nnz": round(wall / args.steps * 1e9 / nnz, 6),
+        "phases_us_median": {"main": round(statistics.median(main_ms) * 1e3, 2),
+                             "all": round(statistics.median(all_ms) * 1e3, 2)},
+        "roofline": {"bound": "hbm", "kernel": "k_mttkrp_pos", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(("mttkrp", tile, 1)), "algorithmic_bytes": noreuse,
+                     "compulsory_bytes": comp, "avg_launch_us": round(main_avg * 1e3, 2), "launches_per_step": 1,
+                     "byte_model": "one D row per nonzero and one C row per fiber (no reuse)"},
+    }
+    if not args.no_cpu:
+        import oracle
+
+        cores = oracle.threads_used(len(os.sched_getaffinity(0)))
+        sel = np.arange(0, T.nslices, 8, dtype=np.int64)
+        leaves_per_slice = T.pos_l[T.pos_k[1:]] - T.pos_l[T.pos_k[:-1]]
+        frac = float(leaves_per_slice[sel].sum()) / max(1, nnz)
+        ts = []
+        for r in range(4):
+            t = time.perf_counter()
+            oracle.mttkrp_csf3(T.pos_k, T.crd_k, T.pos_l, T.crd_l, T.vals, Ch, Dh, sel=sel, threads=cores)
+            if r:
+                ts.append(time.perf_counter() - t)
+        tmed = statistics.median(ts)
+        rec["cpu_baseline"] = {"value": round(fl * frac / tmed / 1e9, 3), "unit": "GFLOP/s", "cores": cores,
+                               "kind": "oracle",
+                               "sample": "every 8th slice (%.3f of the nonzeros), fp64, OpenMP over slices, 1 warm-up + "
+                                         "3 runs, median %.3f s" % (frac, tmed)}
+    rec["generate_s"] = round(t_gen, 2)
+    print(json.dumps(rec))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -142,6 +239,8 @@ def main():
     cfg_no, kind = WORKLOADS[args.workload]
     if kind == "copy":
         return bench_copy(args, torch)
+    if kind == "mttkrp":
+        return bench_mttkrp(args, torch, psk, wl)
     t_gen = time.time()
     if args.workload == "uniform28":
         A28 = wl.csr_uniform(2_000_000, 2_000_000, 28, wl.BASE_SEED + 6)

@@ -71,7 +71,8 @@ typedef enum {
     PSK_OP_SPMV_CSR = 0,
     PSK_OP_SPMM_CSR = 1,
     PSK_OP_SPMV_BCSR = 2,
-    PSK_OP_SPMM_BCSR = 3
+    PSK_OP_SPMM_BCSR = 3,
+    PSK_OP_MTTKRP_CSF3 = 4
 } psk_op;
 
 enum { PSK_PHASE_PARTITION = 1, PSK_PHASE_MAIN = 2, PSK_PHASE_FIXUP = 4, PSK_PHASE_ALL = 7 };
@@ -180,6 +181,38 @@ int psk_spmm_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, con
                   const int32_t *crd, const float *vals, const float *B, int32_t k, int64_t ldb,
                   float *C, int64_t ldc, int32_t tile, int phases, void *workspace,
                   size_t workspace_bytes, void *stream);
+
+/*
+ * MTTKRP, A(i,j) = B(i,k,l) * C(k,j) * D(l,j)  (appendix "MTTKRP on a GPU"), B an order-3 tensor stored as a
+ * three-level coordinate hierarchy (Section 3), one level per mode:
+ *   slices  s = 0 .. nslices-1 (mode i): coordinate crd_i[s], or s itself when crd_i is NULL (dense first
+ *           level; then nslices must equal dim_i); slice s owns fibers pos_k[s] .. pos_k[s+1];
+ *   fibers  q = 0 .. nfibers-1 (mode k): coordinate crd_k[q]; fiber q owns leaves pos_l[q] .. pos_l[q+1];
+ *   leaves  p = 0 .. nnz-1     (mode l): coordinate crd_l[p], value vals[p].
+ * Preconditions like CSR at each level: pos_k[0] = 0, pos_k[nslices] = nfibers, pos_l[0] = 0,
+ * pos_l[nfibers] = nnz, both non-decreasing, coordinates in range; crd_i (if given) distinct.  Empty slices
+ * and empty fibers are allowed.
+ * C is dim_k x j (row stride ldc), D is dim_l x j (ldd), A is dim_i x j (lda), all row-major fp32.  Every
+ * row of A is assigned (rows without leaves become 0).  Schedule: fuse (k,l), fuse with i, cut the fused loop
+ * in the position space of the LEAF level into tiles of `tile` leaves, j over the lanes of a wave; the two
+ * levels above the cut are tracked per tile (psk_partition_csf3) and inside the tile.
+ * tile in {0, 256, 512, 1024, 2048}; workspace from psk_workspace_bytes(PSK_OP_MTTKRP_CSF3, nslices, nnz, j, 1, tile).
+ */
+int psk_mttkrp_csf3(int64_t dim_i, int64_t dim_k, int64_t dim_l, int64_t nslices, int64_t nfibers, int64_t nnz,
+                    const int32_t *crd_i, const int32_t *pos_k, const int32_t *crd_k, const int32_t *pos_l,
+                    const int32_t *crd_l, const float *vals, const float *C, int64_t ldc, const float *D,
+                    int64_t ldd, int32_t j, float *A, int64_t lda, int32_t tile, int phases, void *workspace,
+                    size_t workspace_bytes, void *stream);
+
+/*
+ * The position cut of the leaf level of that hierarchy.  For t = 0 .. ntiles (ntiles = ceil(nnz / tile)):
+ *   tile_fiber[t] = max { q in [0, nfibers] : pos_l[q] <= min(t*tile, nnz) }
+ *   tile_slice[t] = max { s in [0, nslices] : pos_k[s] <= tile_fiber[t] }
+ * i.e. the fiber and the slice that own the tile's first leaf (two chained binary searches, Section 6.2),
+ * with the sentinels (nfibers, nslices) in the last entry.  Both tables have ntiles + 1 int32 entries.
+ */
+int psk_partition_csf3(int64_t nslices, int64_t nfibers, int64_t nnz, const int32_t *pos_k, const int32_t *pos_l,
+                       int32_t tile, int32_t *tile_slice, int32_t *tile_fiber, void *stream);
 
 /*
  * Coordinate-space baselines (Section 3 "tiling the coordinate space"; Section 8.3):

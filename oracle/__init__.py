@@ -50,6 +50,10 @@ def _lib():
         lib.oracle_spmv_bcsr.restype = None
         lib.oracle_spmm_bcsr.argtypes = [i64, i32, i64, p, p, p, p, i64, p, p, p, i64, ci]
         lib.oracle_spmm_bcsr.restype = None
+        lib.oracle_mttkrp_csf3.argtypes = [i64, i64, p, p, p, p, p, p, i64, p, i64, p, p, p, i64, ci]
+        lib.oracle_mttkrp_csf3.restype = None
+        lib.oracle_partition_csf3.argtypes = [i64, i64, i64, p, p, i64, p, p]
+        lib.oracle_partition_csf3.restype = None
         lib.oracle_num_tiles.argtypes = [i64, i64]
         lib.oracle_num_tiles.restype = i64
         lib.oracle_partition.argtypes = [i64, i64, p, i64, p]
@@ -136,6 +140,41 @@ def spmm_bcsr(pos, crd, vals, B, bs: int, sel=None, threads: int = 1):
     _lib().oracle_spmm_bcsr(brows, bs, k, pos.ctypes.data, crd.ctypes.data, vals.ctypes.data, B.ctypes.data,
                             ldb, C.ctypes.data, mag.ctypes.data, sp, ns, int(threads))
     return C, mag
+
+
+def mttkrp_csf3(pos_k, crd_k, pos_l, crd_l, vals, C, D, sel=None, threads: int = 1):
+    """A(s, j) = sum over the fibers and leaves of slice s of vals * C[k, j] * D[l, j]; returns (A, mag)
+    with one row per slice (or per selected slice)."""
+    pos_k, crd_k, pos_l, crd_l, vals = _i32(pos_k), _i32(crd_k), _i32(pos_l), _i32(crd_l), _f32(vals)
+    C = np.asarray(C, dtype=np.float32)
+    D = np.asarray(D, dtype=np.float32)
+    if C.ndim != 2 or C.strides[1] != 4:
+        C = np.ascontiguousarray(C)
+    if D.ndim != 2 or D.strides[1] != 4:
+        D = np.ascontiguousarray(D)
+    j = C.shape[1]
+    assert D.shape[1] == j
+    nslices = pos_k.size - 1
+    keep, sp, ns = _sel(sel)
+    n = ns if keep is not None else nslices
+    A = np.empty((n, j), dtype=np.float64)
+    mag = np.empty((n, j), dtype=np.float64)
+    _lib().oracle_mttkrp_csf3(nslices, j, pos_k.ctypes.data, crd_k.ctypes.data, pos_l.ctypes.data, crd_l.ctypes.data,
+                              vals.ctypes.data, C.ctypes.data, C.strides[0] // 4, D.ctypes.data, D.strides[0] // 4,
+                              A.ctypes.data, mag.ctypes.data, sp, ns, int(threads))
+    return A, mag
+
+
+def partition_csf3(pos_k, pos_l, tile: int):
+    """Leaf-level position cut of a three-level hierarchy: (tile_slice, tile_fiber), num_tiles+1 entries each."""
+    pos_k, pos_l = _i32(pos_k), _i32(pos_l)
+    nslices, nfibers, nnz = pos_k.size - 1, pos_l.size - 1, int(pos_l[-1])
+    nt = num_tiles(nnz, tile)
+    ts = np.empty(nt + 1, dtype=np.int32)
+    tf = np.empty(nt + 1, dtype=np.int32)
+    _lib().oracle_partition_csf3(nslices, nfibers, nnz, pos_k.ctypes.data, pos_l.ctypes.data, int(tile),
+                                 ts.ctypes.data, tf.ctypes.data)
+    return ts, tf
 
 
 def num_tiles(nnz: int, tile: int) -> int:

@@ -183,6 +183,64 @@ void oracle_partition(int64_t rows, int64_t nnz, const int32_t *pos, int64_t til
 }
 
 /*
+ * MTTKRP on a three-level compressed tensor (appendix "MTTKRP on a GPU": A(i,j) = B(i,k,l) * C(k,j) * D(l,j)).
+ * B is stored as a coordinate hierarchy (Section 3) with one level per mode: slice s (mode i; its
+ * coordinate is crd_i[s], or s itself when crd_i is NULL = dense first level) owns fibers
+ * pos_k[s] .. pos_k[s+1]; fiber q has coordinate crd_k[q] in mode k and owns leaf positions
+ * pos_l[q] .. pos_l[q+1]; leaf p has coordinate crd_l[p] in mode l and value vals[p].
+ * C is K x J (row stride ldc), D is L x J (row stride ldd).  out has J doubles per slice (or per
+ * selected slice), indexed by SLICE, not by the slice's coordinate; mag likewise.
+ */
+void oracle_mttkrp_csf3(int64_t nslices, int64_t j, const int32_t *pos_k, const int32_t *crd_k,
+                        const int32_t *pos_l, const int32_t *crd_l, const float *vals, const float *C,
+                        int64_t ldc, const float *D, int64_t ldd, double *out, double *mag,
+                        const int64_t *sel, int64_t nsel, int threads)
+{
+    int64_t n = sel ? nsel : nslices;
+    threads = clamp_threads(threads);
+#pragma omp parallel for schedule(dynamic, 64) num_threads(threads)
+    for (int64_t t = 0; t < n; ++t) {
+        int64_t s = sel ? sel[t] : t;
+        double *a = out + t * j;
+        double *m = mag ? mag + t * j : NULL;
+        for (int64_t jj = 0; jj < j; ++jj) { a[jj] = 0.0; if (m) m[jj] = 0.0; }
+        for (int64_t q = pos_k[s]; q < pos_k[s + 1]; ++q) {
+            const float *c = C + (int64_t)crd_k[q] * ldc;
+            for (int64_t p = pos_l[q]; p < pos_l[q + 1]; ++p) {
+                const float *d = D + (int64_t)crd_l[p] * ldd;
+                double v = (double)vals[p];
+                for (int64_t jj = 0; jj < j; ++jj) {
+                    double term = v * (double)c[jj] * (double)d[jj];
+                    a[jj] += term;
+                    if (m) m[jj] += fabs(term);
+                }
+            }
+        }
+    }
+}
+
+/*
+ * Position cut of the leaf level of the three-level hierarchy (Section 3: a position loop keeps track of
+ * every coordinate above the cut the same way).  For tile t with first leaf position min(t*tile, nnz):
+ * tile_fiber[t] = largest q in [0, nfibers] with pos_l[q] <= that position, tile_slice[t] = largest s in
+ * [0, nslices] with pos_k[s] <= tile_fiber[t].  Both tables have num_tiles + 1 entries.  One walk per level.
+ */
+void oracle_partition_csf3(int64_t nslices, int64_t nfibers, int64_t nnz, const int32_t *pos_k,
+                           const int32_t *pos_l, int64_t tile, int32_t *tile_slice, int32_t *tile_fiber)
+{
+    int64_t ntiles = oracle_num_tiles(nnz, tile);
+    int64_t q = 0, s = 0;
+    for (int64_t t = 0; t <= ntiles; ++t) {
+        int64_t first = t * tile;
+        if (first > nnz) first = nnz;
+        while (q < nfibers && (int64_t)pos_l[q + 1] <= first) ++q;
+        while (s < nslices && (int64_t)pos_k[s + 1] <= q) ++s;
+        tile_fiber[t] = (int32_t)q;
+        tile_slice[t] = (int32_t)s;
+    }
+}
+
+/*
  * Structural validity of a CSR/BCSR index structure: pos[0]=0, pos monotone,
  * pos[rows]=nnz, 0 <= crd < cols.  Returns 0 if valid, else a code 1..4.
  */

@@ -15,14 +15,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpsk.so")
 
 PSK_OK = 0
-PSK_OP_SPMV_CSR, PSK_OP_SPMM_CSR, PSK_OP_SPMV_BCSR, PSK_OP_SPMM_BCSR = 0, 1, 2, 3
+PSK_OP_SPMV_CSR, PSK_OP_SPMM_CSR, PSK_OP_SPMV_BCSR, PSK_OP_SPMM_BCSR, PSK_OP_MTTKRP_CSF3 = 0, 1, 2, 3, 4
 PSK_PHASE_PARTITION, PSK_PHASE_MAIN, PSK_PHASE_FIXUP, PSK_PHASE_ALL = 1, 2, 4, 7
 PSK_ROWSPLIT_THREAD_PER_ROW, PSK_ROWSPLIT_WAVE_PER_ROW = 0, 1
 
 EXPORTS = [
     "psk_status_string", "psk_version", "psk_default_tile", "psk_num_tiles", "psk_workspace_bytes",
     "psk_partition_csr", "psk_analyze_csr", "psk_spmv_csr", "psk_spmm_csr", "psk_spmv_bcsr", "psk_spmm_bcsr",
-    "psk_spmv_csr_rowsplit", "psk_spmm_csr_rowsplit", "psk_spmv_csr_atomics",
+    "psk_spmv_csr_rowsplit", "psk_spmm_csr_rowsplit", "psk_spmv_csr_atomics", "psk_mttkrp_csf3",
+    "psk_partition_csf3",
 ]
 
 
@@ -59,6 +60,11 @@ def lib() -> ctypes.CDLL:
         L.psk_spmv_bcsr.restype = ci
         L.psk_spmm_bcsr.argtypes = [i64, i64, i64, i32, p, p, p, p, i32, i64, p, i64, i32, ci, p, sz, p]
         L.psk_spmm_bcsr.restype = ci
+        L.psk_partition_csf3.argtypes = [i64, i64, i64, p, p, i32, p, p, p]
+        L.psk_partition_csf3.restype = ci
+        L.psk_mttkrp_csf3.argtypes = [i64, i64, i64, i64, i64, i64, p, p, p, p, p, p, p, i64, p, i64, i32, p, i64, i32,
+                                      ci, p, sz, p]
+        L.psk_mttkrp_csf3.restype = ci
         L.psk_spmv_csr_atomics.argtypes = [i64, i64, i64, p, p, p, p, p, i32, ci, p, sz, p]
         L.psk_spmv_csr_atomics.restype = ci
         L.psk_spmv_csr_rowsplit.argtypes = [i64, i64, i64, p, p, p, p, p, ci, p]
@@ -191,6 +197,34 @@ def psk_spmm_bcsr(brows, bcols, nblocks, bs, pos, crd, vals, B, C, tile=0, phase
                              _ptr(ws), ws.numel(), _stream(stream))
     _check(st, "psk_spmm_bcsr")
     return C
+
+
+def psk_partition_csf3(pos_k, pos_l, nnz: int, tile: int, stream=None):
+    """(tile_slice, tile_fiber), each int32 with num_tiles+1 entries."""
+    nslices, nfibers = pos_k.numel() - 1, pos_l.numel() - 1
+    nt = max(psk_num_tiles(nnz, tile), 0)
+    ts = torch.empty(nt + 1, dtype=torch.int32, device=pos_k.device)
+    tf = torch.empty(nt + 1, dtype=torch.int32, device=pos_k.device)
+    st = lib().psk_partition_csf3(nslices, nfibers, int(nnz), _ptr(pos_k, torch.int32), _ptr(pos_l, torch.int32),
+                                  int(tile), _ptr(ts, torch.int32), _ptr(tf, torch.int32), _stream(stream))
+    _check(st, "psk_partition_csf3")
+    return ts, tf
+
+
+def psk_mttkrp_csf3(dims, crd_i, pos_k, crd_k, pos_l, crd_l, vals, C, D, A, tile=0, phases=PSK_PHASE_ALL, ws=None,
+                    stream=None):
+    """A (dims[0] x j) = MTTKRP of the three-level tensor with C (dims[1] x j) and D (dims[2] x j)."""
+    nslices, nfibers, nnz, j = pos_k.numel() - 1, pos_l.numel() - 1, crd_l.numel(), C.shape[1]
+    if ws is None:
+        ws = workspace(PSK_OP_MTTKRP_CSF3, nslices, nnz, k=j, tile=tile, device=pos_k.device)
+    st = lib().psk_mttkrp_csf3(int(dims[0]), int(dims[1]), int(dims[2]), nslices, nfibers, nnz,
+                               _ptr(crd_i, torch.int32), _ptr(pos_k, torch.int32), _ptr(crd_k, torch.int32),
+                               _ptr(pos_l, torch.int32), _ptr(crd_l, torch.int32), _ptr(vals, torch.float32),
+                               _ptr(C, torch.float32), int(C.stride(0)), _ptr(D, torch.float32), int(D.stride(0)),
+                               int(j), _ptr(A, torch.float32), int(A.stride(0)), int(tile), int(phases), _ptr(ws),
+                               ws.numel(), _stream(stream))
+    _check(st, "psk_mttkrp_csf3")
+    return A
 
 
 def psk_spmv_csr_atomics(rows, cols, nnz, pos, crd, vals, x, y, tile=0, phases=PSK_PHASE_ALL, ws=None, stream=None):

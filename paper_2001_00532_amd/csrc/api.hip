@@ -15,6 +15,7 @@ int32_t default_tile(int op)
         case PSK_OP_SPMM_CSR: return 512;
         case PSK_OP_SPMV_BCSR: return 512;
         case PSK_OP_SPMM_BCSR: return 64;
+        case PSK_OP_MTTKRP_CSF3: return 512;
         default: return -1;
     }
 }
@@ -26,6 +27,7 @@ bool tile_ok(int op, int32_t tile)
         case PSK_OP_SPMM_CSR: return spmm_csr_tile_ok(tile);
         case PSK_OP_SPMV_BCSR:
         case PSK_OP_SPMM_BCSR: return bcsr_tile_ok(tile);
+        case PSK_OP_MTTKRP_CSF3: return mttkrp_tile_ok(tile);
         default: return false;
     }
 }
@@ -37,6 +39,7 @@ int64_t carry_width(int op, int32_t k, int32_t bs)
         case PSK_OP_SPMM_CSR: return k;
         case PSK_OP_SPMV_BCSR: return bs;
         case PSK_OP_SPMM_BCSR: return (int64_t)bs * k;
+        case PSK_OP_MTTKRP_CSF3: return k;
         default: return 0;
     }
 }
@@ -98,7 +101,7 @@ size_t psk_workspace_bytes(int op, int64_t rows, int64_t nnz, int32_t k, int32_t
     // CSR SpMV picks 2048, or 1024 with column passes: size for the smaller one, which needs more
     if (tile == 0) tile = op == PSK_OP_SPMV_CSR ? 1024 : default_tile(op);
     if (tile <= 0 || nnz < 0 || nnz > kMaxI32) return 0;
-    if ((op == PSK_OP_SPMM_CSR || op == PSK_OP_SPMM_BCSR) && k <= 0) return 0;
+    if ((op == PSK_OP_SPMM_CSR || op == PSK_OP_SPMM_BCSR || op == PSK_OP_MTTKRP_CSF3) && k <= 0) return 0;
     if ((op == PSK_OP_SPMV_BCSR || op == PSK_OP_SPMM_BCSR) && bs <= 0) return 0;
     const int64_t width = carry_width(op, k, bs);
     if (width <= 0) return 0;
@@ -258,6 +261,54 @@ int psk_spmm_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, con
         }
     }
     if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, bs, k, ldc, tile, pos, ws, C, s);
+    return hip_status(e);
+}
+
+int psk_partition_csf3(int64_t nslices, int64_t nfibers, int64_t nnz, const int32_t *pos_k, const int32_t *pos_l,
+                       int32_t tile, int32_t *tile_slice, int32_t *tile_fiber, void *stream)
+{
+    if (nslices < 0 || nfibers < 0 || nnz < 0 || nnz > kMaxI32 || nslices > kMaxI32 - 1 || nfibers > kMaxI32 - 1)
+        return PSK_ERR_SIZE;
+    if (tile <= 0) return PSK_ERR_TILE;
+    if (!pos_k || !pos_l || !tile_slice || !tile_fiber) return PSK_ERR_NULL;
+    return hip_status(launch_partition_csf3((int32_t)nslices, (int32_t)nfibers, (int32_t)nnz, pos_k, pos_l, tile,
+                                            tile_slice, tile_fiber, static_cast<hipStream_t>(stream)));
+}
+
+int psk_mttkrp_csf3(int64_t dim_i, int64_t dim_k, int64_t dim_l, int64_t nslices, int64_t nfibers, int64_t nnz,
+                    const int32_t *crd_i, const int32_t *pos_k, const int32_t *crd_k, const int32_t *pos_l,
+                    const int32_t *crd_l, const float *vals, const float *C, int64_t ldc, const float *D,
+                    int64_t ldd, int32_t j, float *A, int64_t lda, int32_t tile, int phases, void *workspace,
+                    size_t workspace_bytes, void *stream)
+{
+    if (dim_i < 0 || dim_k < 0 || dim_l < 0 || nslices < 0 || nfibers < 0 || nslices > dim_i) return PSK_ERR_SIZE;
+    if (dim_i > kMaxI32 - 1 || dim_k > kMaxI32 || dim_l > kMaxI32 || nfibers > kMaxI32 - 1) return PSK_ERR_SIZE;
+    if (!crd_i && nslices != dim_i) return PSK_ERR_SIZE;          // dense first level: one slice per i
+    if (j <= 0 || ldc < j || ldd < j || lda < j) return PSK_ERR_SIZE;
+    if (nnz > 0 && nfibers == 0) return PSK_ERR_SIZE;
+    Workspace ws;
+    int st = check_common(PSK_OP_MTTKRP_CSF3, nslices, dim_l, nnz, pos_l, crd_l, vals, j, 1, &tile, phases, workspace,
+                          workspace_bytes, &ws);
+    if (st != PSK_OK) return st;
+    if (!pos_k || (nfibers > 0 && !crd_k) || (dim_i > 0 && !A) || (nnz > 0 && (!C || !D))) return PSK_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int32_t ntiles = (int32_t)psk_num_tiles(nnz, tile);
+    hipError_t e = hipSuccess;
+    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess)
+        e = launch_partition_csf3((int32_t)nslices, (int32_t)nfibers, (int32_t)nnz, pos_k, pos_l, tile, ws.tile_row,
+                                  ws.tile_aux, s);
+    if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
+        // a compressed first level leaves rows of A without a slice: clear them all first; so does nnz = 0
+        if (crd_i || ntiles == 0) {
+            if (lda == j) e = launch_fill_zero(A, dim_i * (int64_t)j, s);
+            else for (int64_t r = 0; r < dim_i && e == hipSuccess; ++r) e = launch_fill_zero(A + r * lda, j, s);
+        }
+        if (ntiles > 0 && e == hipSuccess)
+            e = launch_mttkrp_main((int32_t)nslices, (int32_t)nnz, crd_i, pos_k, crd_k, pos_l, crd_l, vals, C, ldc, D,
+                                   ldd, j, A, lda, tile, ws, ws.tile_aux, s);
+    }
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess)
+        e = launch_carry_fixup(ntiles, 1, j, lda, tile, pos_k, ws, A, s, pos_l, crd_i);
     return hip_status(e);
 }
 

@@ -1,0 +1,272 @@
+// MTTKRP on a three-level compressed tensor in position space (appendix "MTTKRP on a GPU"):
+//     A(i,j) = B(i,k,l) * C(k,j) * D(l,j)
+// Schedule: the k and l loops are fused, then i with them; the fused loop runs over the positions of
+// B's leaf level, split into tiles (workgroups) and wave chunks; j is split over the lanes; the loop
+// over a wave's positions is innermost.  Section 3: a position loop keeps track of every coordinate
+// above the cut the same way it tracks the row of a CSR matrix -- here two levels, fiber and slice.
+#include "psk_dev.h"
+#include "psk_internal.h"
+
+namespace psk {
+
+// tile_fiber[t] = largest q in [0, nfibers] with pos_l[q] <= min(t*tile, nnz); tile_slice[t] = largest s in
+// [0, nslices] with pos_k[s] <= tile_fiber[t]: two chained binary searches (Section 6.2), one lane per entry.
+__global__ __launch_bounds__(256) void k_partition_csf3(int nslices, int nfibers, int nnz,
+                                                        const int *__restrict__ pos_k,
+                                                        const int *__restrict__ pos_l, int tile, int ntiles,
+                                                        int *__restrict__ tile_slice,
+                                                        int *__restrict__ tile_fiber)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t > ntiles) return;
+    const long long first = (long long)t * tile;
+    const int target = first < nnz ? (int)first : nnz;
+    int lo = 0, hi = nfibers;
+    while (lo < hi) {
+        const int mid = lo + ((hi - lo + 1) >> 1);
+        if (pos_l[mid] <= target) lo = mid; else hi = mid - 1;
+    }
+    const int q = lo;
+    lo = 0; hi = nslices;
+    while (lo < hi) {
+        const int mid = lo + ((hi - lo + 1) >> 1);
+        if (pos_k[mid] <= q) lo = mid; else hi = mid - 1;
+    }
+    tile_fiber[t] = q;
+    tile_slice[t] = lo;
+}
+
+hipError_t launch_partition_csf3(int32_t nslices, int32_t nfibers, int32_t nnz, const int32_t *pos_k,
+                                 const int32_t *pos_l, int32_t tile, int32_t *tile_slice, int32_t *tile_fiber,
+                                 hipStream_t s)
+{
+    const int ntiles = nnz <= 0 ? 0 : (int)(((int64_t)nnz + tile - 1) / tile);
+    hipLaunchKernelGGL(k_partition_csf3, dim3((ntiles + 1 + 255) / 256), dim3(256), 0, s, nslices, nfibers, nnz, pos_k,
+                       pos_l, tile, ntiles, tile_slice, tile_fiber);
+    return hipGetLastError();
+}
+
+// One workgroup (4 waves) per tile of T leaf positions and per chunk of 64*VEC columns.
+//
+// Tile metadata in LDS: sflag[i] = s if leaf position i is the last leaf of slice s (slices play the role
+// the rows play in SpMM; a slice's leaves are pos_l[pos_k[s]] .. pos_l[pos_k[s+1]]), and sk[i] = the mode-k
+// coordinate of the fiber that owns leaf i (filled fiber by fiber from the tile's window of pos_l; fibers
+// with >= LONGF leaves in the tile are filled by a whole wave).  Slices without leaves that fall into the
+// tile's write range get zero rows.
+// A wave walks its leaves 64 at a time: l, k, flag and value are loaded one per lane and broadcast with
+// v_readlane, so that the rows C[k,:] and D[l,:] are wave-uniform, contiguous loads; U pairs of rows are
+// requested before the first multiply.  Consecutive leaves of a fiber re-read the same C row from L1.
+// Segments, records, carries: as in the SpMM kernel (the first and last open segments of each wave are
+// chained by wave 0; a chain whose slice began before the tile becomes the tile's carry record).
+template <int VEC>
+__global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const int *__restrict__ crd_i,
+                                                    const int *__restrict__ pos_k,
+                                                    const int *__restrict__ crd_k,
+                                                    const int *__restrict__ pos_l,
+                                                    const int *__restrict__ crd_l,
+                                                    const float *__restrict__ vals,
+                                                    const float *__restrict__ C, long long ldc,
+                                                    const float *__restrict__ D, long long ldd, int jdim,
+                                                    float *__restrict__ A, long long lda,
+                                                    const int *__restrict__ tile_slice,
+                                                    const int *__restrict__ tile_fiber,
+                                                    int *__restrict__ carry_row,
+                                                    float *__restrict__ carry_val, int ntiles, int T)
+{
+    constexpr int THREADS = 256, NW = THREADS / WAVE, KW = WAVE * VEC, U = 4, LONGF = 32;
+    extern __shared__ int smeta[];                // sflag[T], sk[T], long-fiber queue [3 * T / LONGF]
+    int *sflag = smeta, *sk = smeta + T, *slong = smeta + 2 * T;
+    __shared__ float srec[2 * NW][KW];
+    __shared__ int srec_row[2 * NW];              // -2 unused, -1 open segment, >= 0 slice that ended
+    __shared__ int nlong;
+
+    const int t = xcd_tile(blockIdx.x, ntiles);
+    if (t < 0) return;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+    const int t0 = t * T;
+    const int cnt = (nnz - t0 < T) ? nnz - t0 : T;
+    const int t1 = t0 + cnt;
+    const int col = blockIdx.y * KW + lane * VEC;
+    const bool active = col < jdim;
+
+    for (int i = tid; i < T; i += THREADS) { sflag[i] = -1; sk[i] = 0; }
+    if (tid < 2 * NW) srec_row[tid] = -2;
+    if (tid == 0) nlong = 0;
+
+    const int r0 = tile_slice[t], r1 = tile_slice[t + 1];
+    const int q0 = tile_fiber[t], q1 = tile_fiber[t + 1];
+    const int leaf_r0 = pos_l[pos_k[r0]], leaf_r1 = pos_l[pos_k[r1]];   // first leaf of slices r0, r1
+    const bool has_carry = (t > 0) && (leaf_r0 < t0);
+    const int rbeg = (t == 0) ? 0 : r0;
+    const bool straddle = leaf_r1 != t1;          // slice r1 continues into the next tile
+    const int rend = straddle ? r1 + 1 : r1;
+    const int qend = (pos_l[q1] != t1) ? q1 + 1 : q1;   // fibers with leaves in this tile: q0 .. qend-1
+    if (tid == 0 && blockIdx.y == 0 && !has_carry) carry_row[t] = -1;
+    __syncthreads();
+
+    // ---- slice ends of this tile, zero rows for slices without leaves
+    for (int rb = rbeg + wave * WAVE; rb < rend; rb += THREADS) {
+        const int r = rb + lane;
+        const bool valid = r < rend;
+        const int ps = valid ? pos_l[pos_k[r]] : 0, pe = valid ? pos_l[pos_k[r + 1]] : 1;
+        if (valid && pe > ps) {
+            const int e = pe - 1 - t0;
+            if (e >= 0 && e < cnt) sflag[e] = r;
+        }
+        unsigned long long empty = __ballot(valid && pe == ps);
+        while (empty) {
+            const int j = __ffsll((long long)empty) - 1;
+            empty &= empty - 1;
+            if (active) {
+                const float z[VEC] = {};
+                const long long row = crd_i ? crd_i[rb + j] : rb + j;
+                st_vec<VEC>(A + row * lda + col, z);
+            }
+        }
+    }
+    // ---- mode-k coordinate of every leaf of the tile
+    for (int q = q0 + tid; q < qend; q += THREADS) {
+        int lo = pos_l[q] - t0, hi = pos_l[q + 1] - t0;
+        lo = lo < 0 ? 0 : lo;
+        hi = hi > cnt ? cnt : hi;
+        const int kk = crd_k[q];
+        if (hi - lo < LONGF) {
+            for (int i = lo; i < hi; ++i) sk[i] = kk;
+        } else {
+            const int e = atomicAdd(&nlong, 1);
+            if (e < T / LONGF) { slong[3 * e] = kk; slong[3 * e + 1] = lo; slong[3 * e + 2] = hi; }
+        }
+    }
+    __syncthreads();
+    {
+        const int nl = nlong < T / LONGF ? nlong : T / LONGF;
+        for (int e = wave; e < nl; e += NW) {
+            const int kk = slong[3 * e], lo = slong[3 * e + 1], hi = slong[3 * e + 2];
+            for (int i = lo + lane; i < hi; i += WAVE) sk[i] = kk;
+        }
+    }
+    __syncthreads();
+
+    // ---- the wave's leaves
+    const int CH = T / NW;
+    const int wbeg = wave * CH < cnt ? wave * CH : cnt;
+    const int wend = wbeg + CH < cnt ? wbeg + CH : cnt;
+    float acc[VEC] = {};
+    bool seen = false;
+
+    auto flush = [&](int f) {
+        if (!seen) {
+            seen = true;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) srec[2 * wave][lane * VEC + v] = acc[v];
+            if (lane == 0) srec_row[2 * wave] = f;
+        } else if (active) {
+            const long long row = crd_i ? crd_i[f] : f;
+            st_vec<VEC>(A + row * lda + col, acc);
+        }
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] = 0.0f;
+    };
+
+    for (int base = wbeg; base < wend; base += WAVE) {
+        const int n = wend - base < WAVE ? wend - base : WAVE;
+        int l_l = 0, k_l = 0, f_l = -1;
+        float v_l = 0.0f;
+        if (lane < n) {
+            const int p = t0 + base + lane;
+            l_l = ld_stream(crd_l + p);
+            v_l = ld_stream(vals + p);
+            k_l = sk[base + lane];
+            f_l = sflag[base + lane];
+        }
+        for (int j0 = 0; j0 < n; j0 += U) {
+            float c[U][VEC], d[U][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int j = (j0 + u) & (WAVE - 1);       // lanes past n hold coordinate 0, value 0
+                const long long kk = rl(k_l, j), ll = rl(l_l, j);
+                if (active) {
+                    ld_vec<VEC>(c[u], C + kk * ldc + col);
+                    ld_vec<VEC>(d[u], D + ll * ldd + col);
+                } else {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) { c[u][v] = 0.0f; d[u][v] = 0.0f; }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int j = j0 + u;
+                if (j < n) {
+                    const float a = rl(v_l, j);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[v] = fmaf(a * c[u][v], d[u][v], acc[v]);
+                    const int f = rl(f_l, j);
+                    if (f >= 0) flush(f);
+                }
+            }
+        }
+    }
+    if (wbeg < wend) {
+        const int slot = seen ? 2 * wave + 1 : 2 * wave;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) srec[slot][lane * VEC + v] = acc[v];
+        if (lane == 0) srec_row[slot] = -1;
+    }
+    __syncthreads();
+
+    // ---- chain the records (wave 0)
+    if (wave != 0) return;
+    float run[VEC] = {};
+    auto finalize = [&](int r) {
+        if (has_carry && r == r0) {
+            if (active) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) carry_val[(long long)t * jdim + col + v] = run[v];
+            }
+            if (lane == 0 && blockIdx.y == 0) carry_row[t] = r;
+        } else if (active) {
+            const long long row = crd_i ? crd_i[r] : r;
+            st_vec<VEC>(A + row * lda + col, run);
+        }
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) run[v] = 0.0f;
+    };
+    for (int rec = 0; rec < 2 * NW; ++rec) {
+        const int code = srec_row[rec];
+        if (code == -2) continue;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) run[v] += srec[rec][lane * VEC + v];
+        if (code >= 0) finalize(code);
+    }
+    if (straddle) finalize(r1);
+}
+
+bool mttkrp_tile_ok(int32_t tile) { return tile == 256 || tile == 512 || tile == 1024 || tile == 2048; }
+
+hipError_t launch_mttkrp_main(int32_t nslices, int32_t nnz, const int32_t *crd_i, const int32_t *pos_k,
+                              const int32_t *crd_k, const int32_t *pos_l, const int32_t *crd_l, const float *vals,
+                              const float *C, int64_t ldc, const float *D, int64_t ldd, int32_t j, float *A,
+                              int64_t lda, int32_t tile, const Workspace &w, const int32_t *tile_fiber,
+                              hipStream_t s)
+{
+    const int ntiles = (int)(((int64_t)nnz + tile - 1) / tile);
+    if (ntiles == 0) return hipSuccess;
+    const uintptr_t al = reinterpret_cast<uintptr_t>(C) | reinterpret_cast<uintptr_t>(D) | reinterpret_cast<uintptr_t>(A);
+    int vec = 1;
+    if (j > 64 && j % 2 == 0 && ldc % 2 == 0 && ldd % 2 == 0 && lda % 2 == 0 && (al & 7) == 0) vec = 2;
+    if (j > 128 && j % 4 == 0 && ldc % 4 == 0 && ldd % 4 == 0 && lda % 4 == 0 && (al & 15) == 0) vec = 4;
+    const int kw = WAVE * vec;
+    const dim3 grid(xcd_grid(ntiles), (j + kw - 1) / kw);
+    const size_t lds = ((size_t)2 * tile + 3 * (size_t)(tile / 32)) * sizeof(int);
+#define PSK_GO(V)                                                                                               \
+    hipLaunchKernelGGL((k_mttkrp_pos<V>), grid, dim3(256), lds, s, nslices, nnz, crd_i, pos_k, crd_k, pos_l, crd_l, \
+                       vals, C, (long long)ldc, D, (long long)ldd, j, A, (long long)lda, w.tile_row, tile_fiber,    \
+                       w.carry_row, w.carry_val, ntiles, tile)
+    if (vec == 4) PSK_GO(4);
+    else if (vec == 2) PSK_GO(2);
+    else PSK_GO(1);
+#undef PSK_GO
+    return hipGetLastError();
+}
+
+}  // namespace psk

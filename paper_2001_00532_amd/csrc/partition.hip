@@ -148,9 +148,10 @@ hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s)
 // position, so the lane that sees the head of a run knows its length from pos[r+1] alone and no load
 // in the walk depends on another.  The run is added in tile order, in fp64, to the owner's partial
 // result.  out element (r, e) lives at out[(r*nsub + e / k) * ld + e % k].
-__device__ __forceinline__ int run_length(const int *__restrict__ pos, int r, int t, int tile, int shift, int ntiles)
+__device__ __forceinline__ int run_length(const int *__restrict__ pos, const int *__restrict__ pos2, int r, int t,
+                                          int tile, int shift, int ntiles)
 {
-    const int last = pos[r + 1] - 1;
+    const int last = (pos2 ? pos2[pos[r + 1]] : pos[r + 1]) - 1;
     int e = shift >= 0 ? last >> shift : last / tile;
     int len = e - t + 1;
     len = len < 1 ? 1 : len;
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(256) void k_carry_fixup1(int ntiles, long long ld, 
     if (t < ntiles) {
         r = carry_row[t];
         const int prev = t > 0 ? carry_row[t - 1] : -1;
-        if (r >= 0 && prev != r) len = run_length(pos, r, t, tile, shift, ntiles);
+        if (r >= 0 && prev != r) len = run_length(pos, nullptr, r, t, tile, shift, ntiles);
     }
     if (len > 0 && len <= 8) {
         float v[8];
@@ -197,6 +198,8 @@ __global__ __launch_bounds__(256) void k_carry_fixup1(int ntiles, long long ld, 
 // any width: a lane per (tile, element); the run is walked eight records at a time.
 __global__ __launch_bounds__(256) void k_carry_fixup(int ntiles, int width, int nsub, int k, long long ld, int tile,
                                                      int shift, const int *__restrict__ pos,
+                                                     const int *__restrict__ pos2,
+                                                     const int *__restrict__ rowmap,
                                                      const int *__restrict__ carry_row,
                                                      const float *__restrict__ carry_val,
                                                      float *__restrict__ out)
@@ -207,7 +210,7 @@ __global__ __launch_bounds__(256) void k_carry_fixup(int ntiles, int width, int 
     const int r = carry_row[t];
     if (r < 0) return;
     if (t > 0 && carry_row[t - 1] == r) return;
-    const int len = run_length(pos, r, t, tile, shift, ntiles);
+    const int len = run_length(pos, pos2, r, t, tile, shift, ntiles);
     double sum = 0.0;
     for (int u = 0; u < len; u += 8) {
         float v[8];
@@ -216,25 +219,27 @@ __global__ __launch_bounds__(256) void k_carry_fixup(int ntiles, int width, int 
 #pragma unroll
         for (int i = 0; i < 8; ++i) sum += (double)v[i];
     }
-    float *dst = out + ((long long)r * nsub + e / k) * ld + e % k;
+    const long long row = rowmap ? rowmap[r] : r;
+    float *dst = out + (row * nsub + e / k) * ld + e % k;
     *dst = (float)((double)*dst + sum);
 }
 
 hipError_t launch_carry_fixup(int32_t ntiles, int32_t nsub, int32_t k, int64_t ld, int32_t tile, const int32_t *pos,
-                              const Workspace &w, float *out, hipStream_t s)
+                              const Workspace &w, float *out, hipStream_t s, const int32_t *pos2,
+                              const int32_t *rowmap)
 {
     if (ntiles <= 1) return hipSuccess;   // tile 0 never has a carry
     int shift = -1;
     if ((tile & (tile - 1)) == 0) { shift = 0; while ((1 << shift) < tile) ++shift; }
     const int width = nsub * k;
-    if (width == 1) {
+    if (width == 1 && !pos2 && !rowmap) {
         hipLaunchKernelGGL(k_carry_fixup1, dim3((unsigned)((ntiles + 255) / 256)), dim3(256), 0, s, ntiles,
                            (long long)ld, tile, shift, pos, w.carry_row, w.carry_val, out);
         return hipGetLastError();
     }
     const int64_t n = (int64_t)ntiles * width;
     hipLaunchKernelGGL(k_carry_fixup, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, ntiles, width, nsub, k,
-                       (long long)ld, tile, shift, pos, w.carry_row, w.carry_val, out);
+                       (long long)ld, tile, shift, pos, pos2, rowmap, w.carry_row, w.carry_val, out);
     return hipGetLastError();
 }
 

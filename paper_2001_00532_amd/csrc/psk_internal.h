@@ -6,12 +6,13 @@
 
 namespace psk {
 
-// Workspace carving: [tile_row: ntiles+1 int32][carry_row: ntiles int32][carry_val: ntiles*width float],
-// each part starting on a 256-byte boundary.
+// Workspace carving: [tile_row: ntiles+1 int32][carry_row: ntiles int32][carry_val: ntiles*width float]
+// [tile_aux: ntiles+1 int32 (second table of a two-level cut)], each part starting on a 256-byte boundary.
 struct Workspace {
     int32_t *tile_row;
     int32_t *carry_row;
     float   *carry_val;
+    int32_t *tile_aux;
     size_t   bytes;
 };
 inline size_t align256(size_t n) { return (n + 255) & ~size_t(255); }
@@ -24,7 +25,8 @@ inline Workspace carve(void *base, int64_t ntiles, int64_t width)
     w.tile_row = reinterpret_cast<int32_t *>(p);
     w.carry_row = reinterpret_cast<int32_t *>(p + a);
     w.carry_val = reinterpret_cast<float *>(p + a + b);
-    w.bytes = a + b + c;
+    w.tile_aux = reinterpret_cast<int32_t *>(p + a + b + c);
+    w.bytes = a + b + c + a;
     return w;
 }
 
@@ -36,8 +38,11 @@ hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s);
 hipError_t launch_probe_locality(int32_t nnz, const int32_t *crd, int32_t *result, hipStream_t s);
 // Adds the per-tile carry records to the output: element e of a record of `nsub*k` floats goes to
 // out[(row*nsub + e / k) * ld + e % k].
+// `pos2` (optional): two-level hierarchy, a row's last position is pos2[pos[r+1]] - 1.  `rowmap` (optional):
+// row r of the hierarchy is stored at output row rowmap[r].
 hipError_t launch_carry_fixup(int32_t ntiles, int32_t nsub, int32_t k, int64_t ld, int32_t tile, const int32_t *pos,
-                              const Workspace &w, float *out, hipStream_t s);
+                              const Workspace &w, float *out, hipStream_t s, const int32_t *pos2 = nullptr,
+                              const int32_t *rowmap = nullptr);
 
 // CSR SpMV
 bool spmv_csr_tile_ok(int32_t tile);
@@ -64,5 +69,16 @@ hipError_t launch_spmv_bcsr4_main(int32_t brows, int32_t nblocks, const int32_t 
 hipError_t launch_spmm_bcsr4_main(int32_t brows, int32_t nblocks, const int32_t *pos, const int32_t *crd,
                                   const float *vals, const float *B, int32_t k, int64_t ldb, float *C,
                                   int64_t ldc, int32_t tile, const Workspace &w, hipStream_t s);
+
+// MTTKRP on a three-level hierarchy
+bool mttkrp_tile_ok(int32_t tile);
+hipError_t launch_partition_csf3(int32_t nslices, int32_t nfibers, int32_t nnz, const int32_t *pos_k,
+                                 const int32_t *pos_l, int32_t tile, int32_t *tile_slice, int32_t *tile_fiber,
+                                 hipStream_t s);
+hipError_t launch_mttkrp_main(int32_t nslices, int32_t nnz, const int32_t *crd_i, const int32_t *pos_k,
+                              const int32_t *crd_k, const int32_t *pos_l, const int32_t *crd_l, const float *vals,
+                              const float *C, int64_t ldc, const float *D, int64_t ldd, int32_t j, float *A,
+                              int64_t lda, int32_t tile, const Workspace &w, const int32_t *tile_fiber,
+                              hipStream_t s);
 
 }  // namespace psk

@@ -9,38 +9,6 @@
 
 namespace psk {
 
-template <int VEC> struct VecT;
-template <> struct VecT<1> { typedef float type; };
-template <> struct VecT<2> { typedef v2f type; };
-template <> struct VecT<4> { typedef v4f type; };
-
-template <int VEC>
-__device__ __forceinline__ void ld_vec(float (&d)[VEC], const float *p)
-{
-    typedef typename VecT<VEC>::type V;
-    V v = *reinterpret_cast<const V *>(p);
-    if constexpr (VEC == 1) d[0] = v;
-    else {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) d[i] = v[i];
-    }
-}
-template <int VEC>
-__device__ __forceinline__ void st_vec(float *p, const float (&s)[VEC])
-{
-    typedef typename VecT<VEC>::type V;
-    V v;
-    if constexpr (VEC == 1) v = s[0];
-    else {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) v[i] = s[i];
-    }
-    __builtin_nontemporal_store(v, reinterpret_cast<V *>(p));
-}
-
-__device__ __forceinline__ int   rl(int v, int lane)   { return __builtin_amdgcn_readlane(v, lane); }
-__device__ __forceinline__ float rl(float v, int lane) { return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane)); }
-
 // One workgroup (4 waves) per tile of T positions (T/4 consecutive positions per wave) and per
 // column chunk.
 //

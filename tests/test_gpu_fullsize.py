@@ -113,3 +113,23 @@ def test_analyze_full_size():
     assert psk.psk_analyze_csr(A.rows, A.cols, A.nnz, dev(A.pos), dev(A.crd)) == 2
     A = wl.config(3)["A"]
     assert psk.psk_analyze_csr(A.rows, A.cols, A.nnz, dev(A.pos), dev(A.crd)) == 1
+
+
+def test_mttkrp_full_size():
+    T = wl.csf3_powerlaw(500_000, 100_000, 100_000, 8, 1.8, 4096, wl.BASE_SEED + 9)
+    I, K, L = T.dims
+    say("mttkrp slices", T.nslices, "fibers", T.nfibers, "nnz", T.nnz)
+    C = wl.dense_uniform(K * 64, 1, wl.S_B).reshape(K, 64)
+    D = wl.dense_uniform(L * 64, 2, wl.S_B).reshape(L, 64)
+    pos_k, pos_l = dev(T.pos_k), dev(T.pos_l)
+    tile = psk.psk_default_tile(psk.PSK_OP_MTTKRP_CSF3)
+    ts, tf = psk.psk_partition_csf3(pos_k, pos_l, T.nnz, tile)
+    ws, wf = oracle.partition_csf3(T.pos_k, T.pos_l, tile)
+    assert (ts.cpu().numpy() == ws).all() and (tf.cpu().numpy() == wf).all()
+    A = torch.full((I, 64), float("nan"), device="cuda")
+    psk.psk_mttkrp_csf3(T.dims, None, pos_k, dev(T.crd_k), pos_l, dev(T.crd_l), dev(T.vals), dev(C), dev(D), A)
+    torch.cuda.synchronize()
+    assert not torch.isnan(A).any()
+    sel = sample_rows(T.nslices, 20000, 9)
+    ref, mag = oracle.mttkrp_csf3(T.pos_k, T.crd_k, T.pos_l, T.crd_l, T.vals, C, D, sel=sel, threads=16)
+    check(A[torch.from_numpy(sel).cuda()].cpu().numpy(), ref, mag, "mttkrp sampled slices")

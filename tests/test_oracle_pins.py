@@ -284,3 +284,77 @@ def test_tolerance_helper():
     assert not ok
     ok, _ = oracle.within_tolerance([0.0], [0.0], [0.0])
     assert ok
+
+
+# ---------------------------------------------------------------- MTTKRP on a three-level hierarchy
+def dense_of_csf3(T):
+    I, K, L = T.dims
+    B = np.zeros((I, K, L), dtype=np.float64)
+    for s in range(T.nslices):
+        i = T.crd_i[s] if T.crd_i is not None else s
+        for q in range(T.pos_k[s], T.pos_k[s + 1]):
+            for p in range(T.pos_l[q], T.pos_l[q + 1]):
+                B[i, T.crd_k[q], T.crd_l[p]] += float(T.vals[p])
+    return B
+
+
+def small_csf3(seed, compressed_i=False):
+    rng = np.random.default_rng(seed)
+    ns = 9
+    fps = rng.integers(0, 5, size=ns)                       # fibers per slice, some slices empty
+    lpf = rng.integers(0, 6, size=int(fps.sum()))           # leaves per fiber, some fibers empty
+    dims = (14 if compressed_i else ns, 11, 13)
+    return wl.csf3_from_lengths(fps, lpf, dims, seed, compressed_i=compressed_i)
+
+
+@pytest.mark.parametrize("compressed_i", [False, True])
+def test_mttkrp_vs_einsum(compressed_i):
+    T = small_csf3(5, compressed_i)
+    I, K, L = T.dims
+    C = wl.dense_uniform(K * 6, 1, wl.S_B).reshape(K, 6)
+    D = wl.dense_uniform(L * 6, 2, wl.S_B).reshape(L, 6)
+    A, mag = oracle.mttkrp_csf3(T.pos_k, T.crd_k, T.pos_l, T.crd_l, T.vals, C, D)
+    B = dense_of_csf3(T)
+    full = np.einsum("ikl,kj,lj->ij", B, C.astype(np.float64), D.astype(np.float64))
+    fullm = np.einsum("ikl,kj,lj->ij", np.abs(B), np.abs(C.astype(np.float64)), np.abs(D.astype(np.float64)))
+    rows = T.crd_i if T.crd_i is not None else np.arange(T.nslices)
+    np.testing.assert_allclose(A, full[rows], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(mag, fullm[rows], rtol=0, atol=1e-13)
+    # rows of the full result that no slice maps to are zero
+    others = np.setdiff1d(np.arange(I), rows)
+    assert (full[others] == 0).all()
+
+
+def test_mttkrp_hand_worked_and_reductions():
+    # one slice, two fibers: k=1 with leaves l=0 (2.0), l=2 (-1.0); k=0 with leaf l=1 (4.0)
+    pos_k, crd_k = [0, 2], [1, 0]
+    pos_l, crd_l, vals = [0, 2, 3], [0, 2, 1], [2.0, -1.0, 4.0]
+    C = np.array([[1.0, 10.0], [2.0, 20.0]], dtype=np.float32)           # K = 2
+    D = np.array([[1.0, 1.0], [0.5, 2.0], [3.0, -1.0]], dtype=np.float32)  # L = 3
+    A, mag = oracle.mttkrp_csf3(pos_k, crd_k, pos_l, crd_l, vals, C, D)
+    # j=0: 2*2*1 + (-1)*2*3 + 4*1*0.5 = 4 - 6 + 2 = 0 ; j=1: 2*20*1 + (-1)*20*(-1) + 4*10*2 = 40 + 20 + 80 = 140
+    assert A.tolist() == [[0.0, 140.0]] and mag.tolist() == [[12.0, 140.0]]
+    # with one leaf per fiber and D = 1 the operation is an SpMM with C
+    T = wl.csf3_from_lengths([3, 0, 2, 4], [1] * 9, (4, 7, 5), seed=3)
+    Cm = wl.dense_uniform(7 * 4, 3, wl.S_B).reshape(7, 4)
+    A, _ = oracle.mttkrp_csf3(T.pos_k, T.crd_k, T.pos_l, T.crd_l, T.vals, Cm, np.ones((5, 4), np.float32))
+    S, _ = oracle.spmm_csr(T.pos_k, T.crd_k, T.vals, Cm)
+    assert (A == S).all()
+
+
+def test_partition_csf3_vs_bruteforce():
+    for seed in range(6):
+        T = small_csf3(seed)
+        nnz = T.nnz
+        for tile in (1, 2, 3, 5, 64):
+            ts, tf = oracle.partition_csf3(T.pos_k, T.pos_l, tile)
+            nt = 0 if nnz == 0 else -(-nnz // tile)
+            for t in range(nt + 1):
+                first = min(t * tile, nnz)
+                q = max(q for q in range(T.nfibers + 1) if T.pos_l[q] <= first)
+                s = max(s for s in range(T.nslices + 1) if T.pos_k[s] <= q)
+                assert (tf[t], ts[t]) == (q, s)
+            assert ts[-1] == T.nslices and tf[-1] == T.nfibers
+            # composition: the slice table equals the CSR cut of the composed pos array
+            composed = T.pos_l[T.pos_k]
+            assert (ts == oracle.partition(composed, tile)).all()

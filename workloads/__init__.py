@@ -125,6 +125,56 @@ def csr_powerlaw(rows: int, cols: int, alpha: float, kmin: int, kmax: int, seed:
     return csr_from_lengths(zipf_lengths(rows, alpha, kmin, min(kmax, cols), seed), cols, seed)
 
 
+@dataclass
+class CSF3:
+    """Order-3 tensor B(i,k,l) as a three-level coordinate hierarchy: slices (mode i, dense when crd_i is
+    None), fibers (mode k), leaves (mode l)."""
+    dims: tuple            # (I, K, L)
+    crd_i: object          # int32 [nslices] or None
+    pos_k: np.ndarray      # int32 [nslices+1]
+    crd_k: np.ndarray      # int32 [nfibers]
+    pos_l: np.ndarray      # int32 [nfibers+1]
+    crd_l: np.ndarray      # int32 [nnz]
+    vals: np.ndarray       # float32 [nnz]
+
+    @property
+    def nslices(self) -> int:
+        return int(self.pos_k.size - 1)
+
+    @property
+    def nfibers(self) -> int:
+        return int(self.pos_l.size - 1)
+
+    @property
+    def nnz(self) -> int:
+        return int(self.pos_l[-1])
+
+
+def csf3_from_lengths(fibers_per_slice, leaves_per_fiber, dims, seed: int, compressed_i: bool = False) -> CSF3:
+    """fibers_per_slice[s] fibers in slice s (distinct sorted k), leaves_per_fiber[q] leaves in fiber q
+    (distinct sorted l).  With compressed_i the slices get distinct sorted coordinates out of dims[0]."""
+    I, K, L = dims
+    lk = csr_from_lengths(fibers_per_slice, K, seed)
+    if lk.nnz != len(leaves_per_fiber):
+        raise ValueError("leaves_per_fiber must have one entry per fiber")
+    ll = csr_from_lengths(leaves_per_fiber, L, seed + 7919)
+    crd_i = None
+    if compressed_i:
+        crd_i = csr_from_lengths([lk.rows], I, seed + 104729).crd
+    elif lk.rows != I:
+        raise ValueError("dense first level needs one entry of fibers_per_slice per i")
+    return CSF3((I, K, L), crd_i, lk.pos, lk.crd, ll.pos, ll.crd, ll.vals)
+
+
+def csf3_powerlaw(I: int, K: int, L: int, mean_fibers: float, alpha: float, max_leaves: int, seed: int) -> CSF3:
+    """Synthetic stand-in for a FROSTT-like tensor: about mean_fibers fibers per slice (uniform in
+    [0, 2*mean_fibers]), leaves per fiber from the truncated Zipf law k^-alpha on [1, max_leaves]."""
+    fps = (dense_uniform(I, seed, S_LEN, 0.0, 1.0) * (2 * mean_fibers + 1)).astype(np.int64)
+    fps = np.minimum(fps, K)
+    lpf = zipf_lengths(int(fps.sum()), alpha, 1, min(max_leaves, L), seed + 1)
+    return csf3_from_lengths(fps, lpf, (I, K, L), seed)
+
+
 def exponential_lengths(rows: int, total: int, base: float, cols: int, seed: int) -> np.ndarray:
     """Row lengths proportional to base**rank, scaled to about `total` stored entries, capped at
     `cols`, then shuffled (the skew experiment of Section 8.4: nnz fixed, skew set by the base of an
