@@ -117,7 +117,7 @@ def bench_copy(args, torch):
 
 def bench_mttkrp(args, torch, psk, wl):
     """MTTKRP on the synthetic three-level tensor; same record layout as the matrix workloads."""
-    J = 64
+    J = args.rank
     t_gen = time.time()
     T = wl.csf3_powerlaw(500_000, 100_000, 100_000, 8, 1.8, 4096, wl.BASE_SEED + 9)
     I, K, L = T.dims
@@ -128,7 +128,7 @@ def bench_mttkrp(args, torch, psk, wl):
     tile = args.tile or psk.psk_default_tile(psk.PSK_OP_MTTKRP_CSF3)
     comp = 8 * nnz + 8 * nfib + 4 * (I + 1) + 4 * J * (K + L) + 4 * J * I
     noreuse = 8 * nnz + 4 * J * nnz + 4 * J * nfib + 8 * nfib + 4 * (I + 1) + 4 * J * I
-    fl = 3 * J * nnz
+    fl = 2 * J * nnz + 2 * J * nfib      # sum_l b*D(l,:) per fiber, then one multiply-add with C(k,:) per fiber
     dev = torch.device("cuda:0")
     copies = args.copies or 2
     sets = []
@@ -219,6 +219,7 @@ def main():
                     help="column passes of the CSR SpMV (0 = ask psk_analyze_csr)")
     ap.add_argument("--skew-base", type=float, default=1.00256, help="base of the expskew workload")
     ap.add_argument("--copies", type=int, default=0, help="operand copies rotated between steps (0 = auto)")
+    ap.add_argument("--rank", type=int, default=64, help="mttkrp: number of columns j of the factor matrices")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--baselines", action="store_true", help="also time the row-split kernels")
     args = ap.parse_args()

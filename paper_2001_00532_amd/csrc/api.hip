@@ -15,7 +15,7 @@ int32_t default_tile(int op)
         case PSK_OP_SPMM_CSR: return 512;
         case PSK_OP_SPMV_BCSR: return 512;
         case PSK_OP_SPMM_BCSR: return 64;
-        case PSK_OP_MTTKRP_CSF3: return 512;
+        case PSK_OP_MTTKRP_CSF3: return 2048;
         default: return -1;
     }
 }

@@ -50,12 +50,16 @@ hipError_t launch_partition_csf3(int32_t nslices, int32_t nfibers, int32_t nnz, 
 //
 // Tile metadata in LDS: sflag[i] = s if leaf position i is the last leaf of slice s (slices play the role
 // the rows play in SpMM; a slice's leaves are pos_l[pos_k[s]] .. pos_l[pos_k[s+1]]), and sk[i] = the mode-k
-// coordinate of the fiber that owns leaf i (filled fiber by fiber from the tile's window of pos_l; fibers
-// with >= LONGF leaves in the tile are filled by a whole wave).  Slices without leaves that fall into the
+// coordinate k of the fiber that owns leaf i, stored as ~k on the fiber's last leaf in the tile (filled fiber
+// by fiber from the tile's window of pos_l; fibers with >= LONGF leaves in the tile are filled by a whole
+// wave).  Slices without leaves that fall into the
 // tile's write range get zero rows.
 // A wave walks its leaves 64 at a time: l, k, flag and value are loaded one per lane and broadcast with
-// v_readlane, so that the rows C[k,:] and D[l,:] are wave-uniform, contiguous loads; U pairs of rows are
-// requested before the first multiply.  Consecutive leaves of a fiber re-read the same C row from L1.
+// v_readlane, so that the rows D[l,:] and C[k,:] are wave-uniform, contiguous loads; U rows of D are
+// requested before the first multiply.  Within a fiber the product is regrouped by distributivity,
+// A(i,:) += C(k,:) * sum_l B(i,k,l) D(l,:), so the C row is requested once, where the fiber's partial sum
+// closes (its last leaf in the tile, or the wave's last leaf), not once per leaf: a cache hit between every
+// two misses of the D gather costs bandwidth, because the vector memory pipeline returns in order.
 // Segments, records, carries: as in the SpMM kernel (the first and last open segments of each wave are
 // chained by wave 0; a chain whose slice began before the tile becomes the tile's carry record).
 template <int VEC>
@@ -73,7 +77,7 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
                                                     int *__restrict__ carry_row,
                                                     float *__restrict__ carry_val, int ntiles, int T)
 {
-    constexpr int THREADS = 256, NW = THREADS / WAVE, KW = WAVE * VEC, U = 4, LONGF = 32;
+    constexpr int THREADS = 256, NW = THREADS / WAVE, KW = WAVE * VEC, U = (VEC == 4 ? 4 : 8), LONGF = 32;
     extern __shared__ int smeta[];                // sflag[T], sk[T], long-fiber queue [3 * T / LONGF]
     int *sflag = smeta, *sk = smeta + T, *slong = smeta + 2 * T;
     __shared__ float srec[2 * NW][KW];
@@ -82,12 +86,14 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
 
     const int t = xcd_tile(blockIdx.x, ntiles);
     if (t < 0) return;
-    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);   // tells the compiler it is uniform
     const int t0 = t * T;
     const int cnt = (nnz - t0 < T) ? nnz - t0 : T;
     const int t1 = t0 + cnt;
     const int col = blockIdx.y * KW + lane * VEC;
     const bool active = col < jdim;
+    const int lcol = active ? col : 0;            // lanes past the last column load column 0 and store nothing
 
     for (int i = tid; i < T; i += THREADS) { sflag[i] = -1; sk[i] = 0; }
     if (tid < 2 * NW) srec_row[tid] = -2;
@@ -131,7 +137,7 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
         hi = hi > cnt ? cnt : hi;
         const int kk = crd_k[q];
         if (hi - lo < LONGF) {
-            for (int i = lo; i < hi; ++i) sk[i] = kk;
+            for (int i = lo; i < hi; ++i) sk[i] = (i == hi - 1) ? ~kk : kk;
         } else {
             const int e = atomicAdd(&nlong, 1);
             if (e < T / LONGF) { slong[3 * e] = kk; slong[3 * e + 1] = lo; slong[3 * e + 2] = hi; }
@@ -142,7 +148,7 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
         const int nl = nlong < T / LONGF ? nlong : T / LONGF;
         for (int e = wave; e < nl; e += NW) {
             const int kk = slong[3 * e], lo = slong[3 * e + 1], hi = slong[3 * e + 2];
-            for (int i = lo + lane; i < hi; i += WAVE) sk[i] = kk;
+            for (int i = lo + lane; i < hi; i += WAVE) sk[i] = (i == hi - 1) ? ~kk : kk;
         }
     }
     __syncthreads();
@@ -152,6 +158,7 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
     const int wbeg = wave * CH < cnt ? wave * CH : cnt;
     const int wend = wbeg + CH < cnt ? wbeg + CH : cnt;
     float acc[VEC] = {};
+    float facc[VEC] = {};                         // sum of b * D(l, :) over the leaves of the open fiber
     bool seen = false;
 
     auto flush = [&](int f) {
@@ -168,30 +175,41 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
         for (int v = 0; v < VEC; ++v) acc[v] = 0.0f;
     };
 
+    // crd_l and vals of 64 leaves, one per lane; requested one round ahead of their use
+    int l_n = 0;
+    float v_n = 0.0f;
+    auto fetch = [&](int base) {
+        l_n = 0;
+        v_n = 0.0f;
+        if (base + lane < wend) {
+            l_n = ld_stream(crd_l + t0 + base + lane);
+            v_n = ld_stream(vals + t0 + base + lane);
+        }
+    };
+    fetch(wbeg);
     for (int base = wbeg; base < wend; base += WAVE) {
         const int n = wend - base < WAVE ? wend - base : WAVE;
-        int l_l = 0, k_l = 0, f_l = -1;
-        float v_l = 0.0f;
-        if (lane < n) {
-            const int p = t0 + base + lane;
-            l_l = ld_stream(crd_l + p);
-            v_l = ld_stream(vals + p);
-            k_l = sk[base + lane];
-            f_l = sflag[base + lane];
-        }
+        const int l_l = l_n;
+        const float v_l = v_n;
+        int k_l = lane < n ? sk[base + lane] : 0;
+        const int f_l = lane < n ? sflag[base + lane] : -1;
+        fetch(base + WAVE);
+        if (base + lane == wend - 1 && k_l >= 0) k_l = ~k_l;   // the wave's last leaf closes its fiber's partial sum
         for (int j0 = 0; j0 < n; j0 += U) {
             float c[U][VEC], d[U][VEC];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int j = (j0 + u) & (WAVE - 1);       // lanes past n hold coordinate 0, value 0
-                const long long kk = rl(k_l, j), ll = rl(l_l, j);
-                if (active) {
-                    ld_vec<VEC>(c[u], C + kk * ldc + col);
-                    ld_vec<VEC>(d[u], D + ll * ldd + col);
+                const int j = (j0 + u) & (WAVE - 1);       // lanes past n hold coordinate 0, value 0, no flag
+                const int ke = rl(k_l, j);
+                const long long ll = rl(l_l, j);
+                // The C row is needed once per fiber, where its partial sum closes (uniform over the wave).
+                if (ke < 0) {
+                    ld_vec<VEC>(c[u], C + (long long)(~ke) * ldc + lcol);
                 } else {
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) { c[u][v] = 0.0f; d[u][v] = 0.0f; }
+                    for (int v = 0; v < VEC; ++v) c[u][v] = 0.0f;
                 }
+                ld_vec<VEC>(d[u], D + ll * ldd + lcol);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -199,9 +217,13 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
                 if (j < n) {
                     const float a = rl(v_l, j);
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) acc[v] = fmaf(a * c[u][v], d[u][v], acc[v]);
-                    const int f = rl(f_l, j);
-                    if (f >= 0) flush(f);
+                    for (int v = 0; v < VEC; ++v) facc[v] = fmaf(a, d[u][v], facc[v]);
+                    if (rl(k_l, j) < 0) {
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) { acc[v] = fmaf(c[u][v], facc[v], acc[v]); facc[v] = 0.0f; }
+                        const int f = rl(f_l, j);
+                        if (f >= 0) flush(f);
+                    }
                 }
             }
         }

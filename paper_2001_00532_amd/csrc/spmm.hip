@@ -41,12 +41,14 @@ __global__ __launch_bounds__(256) void k_spmm_pos(int rows, int nnz, const int *
 
     const int t = xcd_tile(blockIdx.x, ntiles);
     if (t < 0) return;
-    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);   // tells the compiler it is uniform
     const int t0 = t * T;
     const int cnt = (nnz - t0 < T) ? nnz - t0 : T;
     const int t1 = t0 + cnt;
     const int col = blockIdx.y * KW + lane * VEC;
     const bool active = col < k;
+    const int lcol = active ? col : 0;            // lanes past the last column load column 0 and store nothing
 
     for (int i = tid; i < T; i += THREADS) sflag[i] = -1;
     if (tid < 2 * NW) srec_row[tid] = -2;
@@ -106,25 +108,37 @@ __global__ __launch_bounds__(256) void k_spmm_pos(int rows, int nnz, const int *
             for (int v = 0; v < VEC; ++v) acc[ii][v] = 0.0f;
     };
 
-    for (int base = wbeg; base < wend; base += WAVE) {
-        const int n = wend - base < WAVE ? wend - base : WAVE;
-        int c_l = 0, f_l = -1;
-        float v_l[BS * BS];
+    // crd and vals of 64 positions, one per lane; requested one round ahead of their use
+    int c_n = 0;
+    float v_n[BS * BS];
+    auto fetch = [&](int base) {
+        c_n = 0;
 #pragma unroll
-        for (int e = 0; e < BS * BS; ++e) v_l[e] = 0.0f;
-        if (lane < n) {
+        for (int e = 0; e < BS * BS; ++e) v_n[e] = 0.0f;
+        if (base + lane < wend) {
             const int p = t0 + base + lane;
-            c_l = ld_stream(crd + p);
-            f_l = sflag[base + lane];
-            if constexpr (BS == 1) v_l[0] = ld_stream(vals + p);
+            c_n = ld_stream(crd + p);
+            if constexpr (BS == 1) v_n[0] = ld_stream(vals + p);
             else {
 #pragma unroll
                 for (int q = 0; q < BS * BS / 4; ++q) {
                     const v4f v = *reinterpret_cast<const v4f *>(vals + (long long)p * (BS * BS) + q * 4);
-                    v_l[4 * q + 0] = v.x; v_l[4 * q + 1] = v.y; v_l[4 * q + 2] = v.z; v_l[4 * q + 3] = v.w;
+                    v_n[4 * q + 0] = v.x; v_n[4 * q + 1] = v.y; v_n[4 * q + 2] = v.z; v_n[4 * q + 3] = v.w;
                 }
             }
         }
+    };
+    constexpr bool AHEAD = BS == 1;               // blocks: 16 more registers per lane would cost occupancy
+    if (AHEAD) fetch(wbeg);
+    for (int base = wbeg; base < wend; base += WAVE) {
+        const int n = wend - base < WAVE ? wend - base : WAVE;
+        if (!AHEAD) fetch(base);
+        const int c_l = c_n;
+        const int f_l = lane < n ? sflag[base + lane] : -1;
+        float v_l[BS * BS];
+#pragma unroll
+        for (int e = 0; e < BS * BS; ++e) v_l[e] = v_n[e];
+        if (AHEAD) fetch(base + WAVE);
         for (int j0 = 0; j0 < n; j0 += U) {
             float b[U][BS][VEC];
 #pragma unroll
@@ -133,11 +147,7 @@ __global__ __launch_bounds__(256) void k_spmm_pos(int rows, int nnz, const int *
                 const long long c = rl(c_l, j);
 #pragma unroll
                 for (int ji = 0; ji < BS; ++ji) {
-                    if (active) ld_vec<VEC>(b[u][ji], B + (c * BS + ji) * ldb + col);
-                    else {
-#pragma unroll
-                        for (int v = 0; v < VEC; ++v) b[u][ji][v] = 0.0f;
-                    }
+                    ld_vec<VEC>(b[u][ji], B + (c * BS + ji) * ldb + lcol);
                 }
             }
 #pragma unroll
