@@ -39,7 +39,8 @@ __global__ __launch_bounds__(256) void k_spmv_bcsr4(int brows, int nblocks, cons
 
     const int t = xcd_tile(blockIdx.x, ntiles);
     if (t < 0) return;
-    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);   // tells the compiler it is uniform
     const int ii = tid & 3;
     const int t0 = t * TB;
     const int cnt = (nblocks - t0 < TB) ? nblocks - t0 : TB;

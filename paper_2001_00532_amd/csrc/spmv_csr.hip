@@ -84,7 +84,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
 
     const int t = xcd_tile(blockIdx.x, ntiles);
     if (t < 0) return;
-    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);   // tells the compiler it is uniform
     const int t0 = t * T;
     const int cnt = (nnz - t0 < T) ? nnz - t0 : T;
     const int t1 = t0 + cnt;
