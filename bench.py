@@ -43,13 +43,14 @@ HBM_PEAK_GBS = 8000.0
 # scaled by the copy-kernel calibration; the summaries are under profiles/.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
     # (workload, tile, col_passes): bytes per launch of the tile kernel
-    ("powerlaw", 1024, 2): 699619113,      # profiles/k_spmv_pos_powerlaw_2passes.txt
-    ("powerlaw", 2048, 1): 3559120490,     # profiles/k_spmv_pos_powerlaw_1pass.txt
-    ("uniform28", 1024, 2): 678257792,     # profiles/k_spmv_pos_uniform28.txt
-    ("stencil", 2048, 1): 929642938,       # profiles/k_spmv_pos_stencil.txt
-    ("spmm", 512, 1): 8774441013,          # profiles/k_spmm_pos_csr_spmm_k128.txt
-    ("bcsr_spmv", 512, 1): 191984843,      # profiles/k_spmv_bcsr4_bcsr_spmv.txt
-    ("bcsr_spmm", 64, 1): 2411752469,      # profiles/k_spmm_pos_bcsr_spmm_n64.txt
+    ("powerlaw", 1024, 2): 697122557,      # profiles/k_spmv_pos_powerlaw_2passes.txt
+    ("powerlaw", 2048, 1): 3559074828,     # profiles/k_spmv_pos_powerlaw_1pass.txt
+    ("uniform28", 1024, 2): 683671911,     # profiles/k_spmv_pos_uniform28.txt
+    ("stencil", 2048, 1): 929631325,       # profiles/k_spmv_pos_stencil.txt
+    ("spmm", 512, 1): 8775522994,          # profiles/k_spmm_pos_csr_spmm_k128.txt
+    ("bcsr_spmv", 512, 1): 191661400,      # profiles/k_spmv_bcsr4_bcsr_spmv.txt
+    ("bcsr_spmm", 64, 1): 2411765634,      # profiles/k_spmm_pos_bcsr_spmm_n64.txt
+    ("mttkrp", 2048, 1): 11818248693,      # profiles/k_mttkrp_pos_mttkrp_j64.txt (L2 <-> fabric, j = 64)
 }
 
 WORKLOADS = {
@@ -168,7 +169,11 @@ def bench_mttkrp(args, torch, psk, wl):
     main_ms = time_phase(psk.PSK_PHASE_MAIN)
     all_ms = time_phase(psk.PSK_PHASE_ALL)
     main_avg = sum(main_ms) / len(main_ms)
-    achieved = noreuse / (main_avg * 1e-3) / 1e9
+    # C and D (4*J*(K+L) bytes) stay in the 256 MB memory-side cache, so HBM sees each operand once:
+    # the roofline is priced on those compulsory bytes.  What the kernel is bound by is the rate at which
+    # L2 misses on D rows are served (no-reuse bytes / time, reported beside it).
+    achieved = comp / (main_avg * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get(("mttkrp", tile, 1)) if J == 64 else None
     rec = {
         "metric": "SpMV/SpMM GFLOP/s and achieved HBM GB/s (% of MI355X peak), 1 GPU",
         "value": round(fl / (wall / args.steps) / 1e9, 3), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -181,10 +186,12 @@ def bench_mttkrp(args, torch, psk, wl):
         "phases_us_median": {"main": round(statistics.median(main_ms) * 1e3, 2),
                              "all": round(statistics.median(all_ms) * 1e3, 2)},
         "roofline": {"bound": "hbm", "kernel": "k_mttkrp_pos", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(("mttkrp", tile, 1)), "algorithmic_bytes": noreuse,
-                     "compulsory_bytes": comp, "avg_launch_us": round(main_avg * 1e3, 2), "launches_per_step": 1,
-                     "byte_model": "one D row per nonzero and one C row per fiber (no reuse)"},
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "algorithmic_bytes": comp, "no_reuse_bytes": noreuse,
+                     "no_reuse_GBs": round(noreuse / (main_avg * 1e-3) / 1e9, 2),
+                     "avg_launch_us": round(main_avg * 1e3, 2), "launches_per_step": 1,
+                     "byte_model": "every operand once (factor matrices are cache resident); no_reuse_* counts one "
+                                   "D row per nonzero and one C row per fiber, the requests the L2 actually serves"},
     }
     if not args.no_cpu:
         import oracle
