@@ -426,6 +426,20 @@ def main():
             if i >= 4:
                 ts.append(e0.elapsed_time(e1))
         base["position_space_atomics_us_median"] = round(statistics.median(ts) * 1e3, 2)
+        for name, phases in (("position_space_no_temporary_us_median", psk.PSK_PHASE_ALL),
+                             ("position_space_no_temporary_main_us_median", psk.PSK_PHASE_MAIN)):
+            ts = []
+            for i in range(12):     # ablation: rolled load loop, no register temporary (Section 8.3)
+                s = sets[i % copies]
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                psk.psk_spmv_csr_notemp(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"],
+                                        tile=args.tile, phases=phases, ws=s["ws"], stream=stream)
+                e1.record(stream)
+                e1.synchronize()
+                if i >= 4:
+                    ts.append(e0.elapsed_time(e1))
+            base[name] = round(statistics.median(ts) * 1e3, 2)
         rec["rowsplit_baselines"] = base
 
     # ---- the CPU oracle on this machine's host cores (a baseline, not a target)

@@ -236,6 +236,17 @@ int psk_spmv_csr_atomics(int64_t rows, int64_t cols, int64_t nnz, const int32_t 
                          const float *vals, const float *x, float *y, int32_t tile, int phases,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Ablation of Section 8.3 (the optimised schedule "without the temporary or loop unrolling"): same cut,
+ * same row logic, carries and fix-up as psk_spmv_csr, but each thread walks its positions in a rolled
+ * loop (load, gather, multiply, store to on-chip memory, one position after the other) instead of
+ * issuing all its loads first and keeping the products in registers.  Same arguments, workspace and
+ * result (within the fp32 tolerance) as psk_spmv_csr with col_passes = 1.
+ */
+int psk_spmv_csr_notemp(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                        const float *vals, const float *x, float *y, int32_t tile, int phases,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
 /* Row-split SpMM baseline: one wave per row, lanes over the columns of B. */
 int psk_spmm_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos,
                           const int32_t *crd, const float *vals, const float *B, int32_t k,

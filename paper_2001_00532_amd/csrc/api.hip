@@ -185,6 +185,28 @@ int psk_spmv_csr_atomics(int64_t rows, int64_t cols, int64_t nnz, const int32_t 
     return hip_status(e);
 }
 
+int psk_spmv_csr_notemp(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                        const float *vals, const float *x, float *y, int32_t tile, int phases, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    Workspace ws;
+    int st = check_common(PSK_OP_SPMV_CSR, rows, cols, nnz, pos, crd, vals, 1, 1, &tile, phases, workspace,
+                          workspace_bytes, &ws);
+    if (st != PSK_OK) return st;
+    if ((rows > 0 && !y) || (nnz > 0 && !x)) return PSK_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int32_t ntiles = (int32_t)psk_num_tiles(nnz, tile);
+    hipError_t e = hipSuccess;
+    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, 0, ws.tile_row, s);
+    if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
+        if (ntiles == 0) e = launch_fill_zero(y, rows, s);
+        else e = launch_spmv_csr_main((int32_t)rows, (int32_t)cols, (int32_t)nnz, pos, crd, vals, x, y, tile, -2, ws, s);
+    }
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess && ntiles > 0)
+        e = launch_carry_fixup(ntiles, 1, 1, 1, tile, pos, ws, y, s);
+    return hip_status(e);
+}
+
 int psk_spmm_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
                  const float *vals, const float *B, int32_t k, int64_t ldb, float *C, int64_t ldc,
                  int32_t tile, int phases, void *workspace, size_t workspace_bytes, void *stream)

@@ -60,6 +60,9 @@ __device__ __forceinline__ void run_select(const RunPlan &p, v4f_u wA, v4f_u wB,
 
 // VARIANT 0: one pass, carries.  1: a column pass (window [clo, chi), accum adds to earlier passes).
 // 2: one pass with the schedule's atomics instead of carries (baseline).
+// 3: one pass without the per-thread temporary and without the unrolled load loop (the ablation of
+//    Section 8.3): each thread walks its positions in a rolled loop, one load -> gather -> multiply -> LDS
+//    store after the other.
 template <int THREADS, int NPT, int MODE, int VARIANT>
 __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nnz, const int *__restrict__ pos,
                                                       const int *__restrict__ crd,
@@ -75,7 +78,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
     constexpr int LONG = 32;
     constexpr int MAXLONG = T / LONG;
     constexpr bool VEC = MODE != 0;
-    constexpr bool WIN = VARIANT == 1, ATOM = VARIANT == 2;
+    constexpr bool WIN = VARIANT == 1, ATOM = VARIANT == 2, NOTEMP = VARIANT == 3;
     static_assert(NPT % 4 == 0, "NPT must be a multiple of 4");
     __shared__ float sprod[skewed_size<1>(T)];
     __shared__ int slong[MAXLONG * 3];
@@ -101,7 +104,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
     v4f vv[VEC ? NPT / 4 : 1];
     int cs[MODE == 1 ? 1 : NPT];
     float vs[MODE == 1 ? 1 : NPT];
-    const bool full = (cnt == T);
+    const bool full = (cnt == T) && !NOTEMP;
     if (full) {
         if (VEC) {
 #pragma unroll
@@ -128,7 +131,14 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
         my_hi = pos[rbeg + tid + 1];
     }
 
-    if (full) {
+    if (NOTEMP) {
+        if (tid == 0) nlong = 0;
+#pragma unroll 1
+        for (int g = 0; g < NPT; ++g) {
+            const int i = g * THREADS + tid;
+            sprod[skew<1>(i)] = i < cnt ? vals[t0 + i] * x[crd[t0 + i]] : 0.0f;
+        }
+    } else if (full) {
         if (MODE == 1) {
             float xg[NPT / 4][4];
             RunPlan plan[NPT / 4];
@@ -210,7 +220,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
     };
 
     // ---- 3a. the tile lies inside a single row
-    if (rend - rbeg == 1) {
+    if (!NOTEMP && rend - rbeg == 1) {
         float s = 0.0f;
 #pragma unroll
         for (int g = 0; g < NPT; ++g) s += prod[g];
@@ -227,10 +237,10 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
     }
 
     // ---- 3b. several rows: products to LDS in position order
-    if (tid == 0) nlong = 0;
+    if (!NOTEMP) {
+        if (tid == 0) nlong = 0;
 #pragma unroll
-    for (int g = 0; g < NPT; ++g) {
-        sprod[skew<1>(tile_index<MODE, THREADS>(g, tid))] = prod[g];
+        for (int g = 0; g < NPT; ++g) sprod[skew<1>(tile_index<MODE, THREADS>(g, tid))] = prod[g];
     }
     __syncthreads();
     for (int r = rbeg + tid; r < rend; r += THREADS) {
@@ -279,8 +289,9 @@ static void launch_pos(int mode, int grid, hipStream_t s, int rows, int cols, in
 #define PSK_GO(M, W)                                                                                             \
     hipLaunchKernelGGL((k_spmv_pos<THREADS, NPT, M, W>), dim3(grid), dim3(THREADS), 0, s, rows, cols, nnz, pos,  \
                        crd, vals, x, y, w.tile_row, w.carry_row, w.carry_val, ntiles, clo, chi, accum)
-    const int variant = accum == 2 ? 2 : ((clo > 0 || chi < cols) ? 1 : 0);
-    if (mode == 1) { if (variant == 2) PSK_GO(1, 2); else if (variant == 1) PSK_GO(1, 1); else PSK_GO(1, 0); }
+    const int variant = accum >= 2 ? accum : ((clo > 0 || chi < cols) ? 1 : 0);
+    if (variant == 3) PSK_GO(0, 3);
+    else if (mode == 1) { if (variant == 2) PSK_GO(1, 2); else if (variant == 1) PSK_GO(1, 1); else PSK_GO(1, 0); }
     else { if (variant == 2) PSK_GO(0, 2); else if (variant == 1) PSK_GO(0, 1); else PSK_GO(0, 0); }
 #undef PSK_GO
 }
@@ -292,11 +303,13 @@ hipError_t launch_spmv_csr_main(int32_t rows, int32_t cols, int32_t nnz, const i
     const int ntiles = (int)(((int64_t)nnz + tile - 1) / tile);
     if (ntiles == 0) return hipSuccess;
     const int grid = xcd_grid(ntiles);
-    const bool atomics = col_passes < 0;          // baseline: one pass, atomic adds for rows that span tiles
+    // baselines: -1 = one pass with atomic adds for rows that span tiles, -2 = one pass without the
+    // register temporary and the unrolled load loop
+    const int baseline = col_passes == -1 ? 2 : (col_passes == -2 ? 3 : 0);
     if (col_passes < 1) col_passes = 1;
     for (int p = 0; p < col_passes; ++p) {
     const int clo = (int)((int64_t)cols * p / col_passes), chi = (int)((int64_t)cols * (p + 1) / col_passes);
-    const int accum = atomics ? 2 : (p > 0);
+    const int accum = baseline ? baseline : (p > 0);
     const bool aligned = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
     const int vec = aligned ? 1 : 0;
     switch (tile) {

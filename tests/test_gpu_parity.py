@@ -335,6 +335,24 @@ def test_spmv_atomics_baseline():
             check(y.cpu().numpy(), ref, mag, "atomics %s tile %d" % (name, tile))
 
 
+def test_spmv_without_temporary_ablation():
+    """The ablation kernel (rolled load loop, no register temporary) computes the same product."""
+    rng = np.random.default_rng(9)
+    cases = [("powerlaw", wl.config(2, 0.02)["A"]), ("stencil", wl.config(3, 0.01)["A"])]
+    for kind in ("mixed", "one_row_has_all", "all_empty", "single_long_rows", "empty_head_tail"):
+        cases.append((kind, wl.csr_from_lengths(adversarial_lengths(rng, 3001, 5003, kind), 5003, seed=72)))
+    for name, A in cases:
+        x = wl.dense_uniform(A.cols, 72, wl.S_X)
+        ref, mag = oracle.spmv_csr(A.pos, A.crd, A.vals, x, threads=8)
+        D, xd = DevCSR(A), dev(x)
+        for tile in (0, 256, 512, 1024, 4096):
+            say("no temporary", name, "tile", tile)
+            y = torch.full((A.rows,), float("nan"), device="cuda")
+            psk.psk_spmv_csr_notemp(A.rows, A.cols, A.nnz, D.pos, D.crd, D.vals, xd, y, tile=tile)
+            torch.cuda.synchronize()
+            check(y.cpu().numpy(), ref, mag, "no temporary %s tile %d" % (name, tile))
+
+
 # ------------------------------------------------------------------ randomised shapes
 def test_random_shapes_all_operations():
     """Sixty seeded random problems: sizes, row-length mixes, tiles, dense widths and pass counts drawn
