@@ -44,6 +44,8 @@ def _lib():
         lib.oracle_threads.restype = ci
         lib.oracle_spmv_csr.argtypes = [i64, p, p, p, p, p, p, p, i64, ci]
         lib.oracle_spmv_csr.restype = None
+        lib.oracle_spmv_csr_f64.argtypes = [i64, p, p, p, p, p, p, p, i64, ci]
+        lib.oracle_spmv_csr_f64.restype = None
         lib.oracle_spmm_csr.argtypes = [i64, i64, p, p, p, p, i64, p, p, p, i64, ci]
         lib.oracle_spmm_csr.restype = None
         lib.oracle_spmv_bcsr.argtypes = [i64, i32, p, p, p, p, p, p, p, i64, ci]
@@ -93,6 +95,21 @@ def spmv_csr(pos, crd, vals, x, sel=None, threads: int = 1):
     mag = np.empty(n, dtype=np.float64)
     _lib().oracle_spmv_csr(rows, pos.ctypes.data, crd.ctypes.data, vals.ctypes.data, x.ctypes.data,
                            y.ctypes.data, mag.ctypes.data, sp, ns, int(threads))
+    return y, mag
+
+
+def spmv_csr_f64(pos, crd, vals, x, sel=None, threads: int = 1):
+    """fp64 operands; sums in extended precision, rounded once.  Returns (y, mag) as float64."""
+    pos, crd = _i32(pos), _i32(crd)
+    vals = np.ascontiguousarray(vals, dtype=np.float64)
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    rows = pos.size - 1
+    keep, sp, ns = _sel(sel)
+    n = ns if keep is not None else rows
+    y = np.empty(n, dtype=np.float64)
+    mag = np.empty(n, dtype=np.float64)
+    _lib().oracle_spmv_csr_f64(rows, pos.ctypes.data, crd.ctypes.data, vals.ctypes.data, x.ctypes.data,
+                               y.ctypes.data, mag.ctypes.data, sp, ns, int(threads))
     return y, mag
 
 

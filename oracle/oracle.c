@@ -79,6 +79,29 @@ void oracle_spmv_csr(int64_t rows, const int32_t *pos, const int32_t *crd, const
     }
 }
 
+/* The same product for fp64 operands (the paper's own temporaries are Float64: appendix "SPMV on a
+ * GPU").  Products and sums are formed in long double (x87 extended, 64-bit significand) and rounded
+ * to double once, so that the reference carries ~2^-11 of the rounding error an fp64 kernel may have. */
+void oracle_spmv_csr_f64(int64_t rows, const int32_t *pos, const int32_t *crd, const double *vals,
+                         const double *x, double *y, double *mag, const int64_t *sel, int64_t nsel,
+                         int threads)
+{
+    int64_t n = sel ? nsel : rows;
+    threads = clamp_threads(threads);
+#pragma omp parallel for schedule(dynamic, 1024) num_threads(threads)
+    for (int64_t s = 0; s < n; ++s) {
+        int64_t i = sel ? sel[s] : s;
+        long double acc = 0.0L, m = 0.0L;
+        for (int64_t p = pos[i]; p < pos[i + 1]; ++p) {
+            long double t = (long double)vals[p] * (long double)x[crd[p]];
+            acc += t;
+            m += fabsl(t);
+        }
+        y[s] = (double)acc;
+        if (mag) mag[s] = (double)m;
+    }
+}
+
 /* C(i,k) = A(i,j) * B(j,k), CSR A, row-major B (ldb) and C (k doubles per row, packed). */
 void oracle_spmm_csr(int64_t rows, int64_t k, const int32_t *pos, const int32_t *crd,
                      const float *vals, const float *B, int64_t ldb, double *C, double *mag,

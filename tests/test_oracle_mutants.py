@@ -40,6 +40,9 @@ MUTANTS = [
      "    int64_t i = 0;\n    for (int64_t t = 0; t <= ntiles; ++t) {\n        i = t;\n        int64_t first = t * tile;"),
     ("partition_stops_at_empty_rows", "while (i < rows && (int64_t)pos[i + 1] <= first) ++i;", "if (i < rows && (int64_t)pos[i + 1] <= first) ++i;"),
     ("num_tiles_floor", "(nnz + tile - 1) / tile", "nnz / tile"),
+    ("f64_sums_in_double", "long double acc = 0.0L, m = 0.0L;", "double acc = 0.0, m = 0.0;"),
+    ("f64_x_indexed_by_position", "(long double)vals[p] * (long double)x[crd[p]];", "(long double)vals[p] * (long double)x[p % 3];"),
+    ("f64_operands_read_as_float", "(long double)vals[p] * (long double)x[crd[p]];", "(long double)(float)vals[p] * (long double)x[crd[p]];"),
 ]
 
 
@@ -103,6 +106,19 @@ def pins_pass(lib) -> bool:
                                np.ones(3, np.float32))
         if y[0] != 2.0 ** -30:
             return False
+        # fp64 operands: cancellation that needs more than a double sum, exact rationals on a small case
+        y, _ = oracle.spmv_csr_f64(pos, np.array([0, 1, 2], np.int32), np.array([2.0 ** 60, 1.0, -(2.0 ** 60)]), np.ones(3))
+        if y[0] != 1.0:
+            return False
+        from fractions import Fraction
+        v64 = wl.dense_uniform_f64(A.nnz, 9, wl.S_VALS)
+        x64 = wl.dense_uniform_f64(47, 9, wl.S_X)
+        y64, _ = oracle.spmv_csr_f64(A.pos, A.crd, v64, x64)
+        for i in range(A.rows):
+            ex = sum((Fraction(float(v64[q])) * Fraction(float(x64[A.crd[q]])) for q in range(A.pos[i], A.pos[i + 1])),
+                     Fraction(0))
+            if abs(Fraction(float(y64[i])) - ex) > Fraction(1, 2 ** 50):
+                return False
         # partition: closed form, last-tile clamp, empty rows
         p = (np.arange(51) * 7).astype(np.int32)
         if oracle.partition(p, 13).tolist() != [min(t * 13, 350) // 7 for t in range(27)] + [50]:

@@ -358,3 +358,54 @@ def test_partition_csf3_vs_bruteforce():
             # composition: the slice table equals the CSR cut of the composed pos array
             composed = T.pos_l[T.pos_k]
             assert (ts == oracle.partition(composed, tile)).all()
+
+
+# ------------------------------------------------------------------ fp64 SpMV oracle (extended-precision sums)
+def test_f64_oracle_against_exact_rational_arithmetic():
+    """Brute force in exact rationals on small random matrices: the oracle's result must be the exact
+    sum to within 2^-60 of sum |a x| (extended precision, one final rounding to double)."""
+    from fractions import Fraction
+
+    rng = np.random.default_rng(64)
+    for rows, cols in ((7, 5), (40, 33)):
+        lengths = rng.integers(0, cols + 1, size=rows)
+        A = wl.csr_from_lengths(lengths, cols, seed=64)
+        vals = wl.dense_uniform_f64(A.nnz, 64, wl.S_VALS)
+        x = wl.dense_uniform_f64(cols, 65, wl.S_X)
+        y, mag = oracle.spmv_csr_f64(A.pos, A.crd, vals, x)
+        for i in range(rows):
+            exact, m = Fraction(0), Fraction(0)
+            for p in range(A.pos[i], A.pos[i + 1]):
+                t = Fraction(float(vals[p])) * Fraction(float(x[A.crd[p]]))
+                exact += t
+                m += abs(t)
+            assert abs(Fraction(float(y[i])) - exact) <= m * Fraction(1, 2 ** 52) + Fraction(1, 10 ** 300)
+            # the reference must be far better than a double-precision sum needs to be
+            assert abs(Fraction(float(y[i])) - exact) <= abs(exact) * Fraction(1, 2 ** 52) + m * Fraction(1, 2 ** 58)
+            assert abs(Fraction(float(mag[i])) - m) <= m * Fraction(1, 2 ** 50)
+
+
+def test_f64_oracle_survives_cancellation_that_defeats_a_double_sum():
+    """[2^60, 1, -2^60] . [1, 1, 1] = 1 exactly; a running sum in double returns 0."""
+    pos = np.array([0, 3], dtype=np.int32)
+    crd = np.array([0, 1, 2], dtype=np.int32)
+    vals = np.array([2.0 ** 60, 1.0, -(2.0 ** 60)])
+    y, mag = oracle.spmv_csr_f64(pos, crd, vals, np.ones(3))
+    assert y[0] == 1.0
+    assert mag[0] == 2.0 ** 61          # 2^61 + 1 rounded to double
+
+
+def test_f64_oracle_reduces_to_the_fp32_operand_oracle():
+    """On operands that are exactly representable in fp32 both oracles compute the same row sums."""
+    A = wl.csr_from_lengths(np.random.default_rng(3).integers(0, 60, size=500), 300, seed=3)
+    x = wl.dense_uniform(300, 3, wl.S_X)
+    y32, m32 = oracle.spmv_csr(A.pos, A.crd, A.vals, x)
+    y64, m64 = oracle.spmv_csr_f64(A.pos, A.crd, A.vals.astype(np.float64), x.astype(np.float64))
+    assert np.all(np.abs(y32 - y64) <= 1e-14 * m64 + 1e-300)
+    assert np.allclose(m32, m64, rtol=1e-14, atol=0)
+
+
+def test_f64_generator_uses_more_than_fp32_precision():
+    v = wl.dense_uniform_f64(1000, 1, wl.S_VALS)
+    assert v.dtype == np.float64 and np.any(v != v.astype(np.float32).astype(np.float64))
+    assert v.min() >= -1.0 and v.max() < 1.0 + 2.0 ** -23

@@ -89,6 +89,13 @@ def dense_uniform(n: int, seed: int, stream: int, lo: float = -1.0, hi: float = 
     return out
 
 
+def dense_uniform_f64(n: int, seed: int, stream: int, lo: float = -1.0, hi: float = 1.0) -> np.ndarray:
+    """fp64 values with 48 random significand bits: two 24-bit draws, the second scaled by 2^-24."""
+    a = dense_uniform(n, seed, stream, lo, hi).astype(np.float64)
+    b = dense_uniform(n, seed ^ 0x5DEECE66D, stream, 0.0, 1.0).astype(np.float64)
+    return a + b * (hi - lo) * 2.0 ** -24
+
+
 def csr_from_lengths(lengths, cols: int, seed: int, lo: float = -1.0, hi: float = 1.0, bs: int = 1) -> CSR:
     """CSR/BCSR with the given number of stored entries per row; columns are
     distinct, uniform over [0, cols) and sorted within each row."""
