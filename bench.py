@@ -226,6 +226,7 @@ def main():
                     help="column passes of the CSR SpMV (0 = ask psk_analyze_csr)")
     ap.add_argument("--skew-base", type=float, default=1.00256, help="base of the expskew workload")
     ap.add_argument("--copies", type=int, default=0, help="operand copies rotated between steps (0 = auto)")
+    ap.add_argument("--f64", action="store_true", help="CSR SpMV workloads: fp64 values, vector and result")
     ap.add_argument("--rank", type=int, default=64, help="mttkrp: number of columns j of the factor matrices")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--baselines", action="store_true", help="also time the row-split kernels")
@@ -265,14 +266,26 @@ def main():
     A = cfg["A"]
     k = cfg.get("k", 1) if kind.endswith("spmm") else 1
     dense_h = cfg["B"] if kind.endswith("spmm") else cfg["x"]
+    f64 = args.f64
+    if f64 and kind != "csr_spmv":
+        sys.stderr.write("bench.py: --f64 applies to the CSR SpMV workloads\n")
+        sys.exit(2)
+    vals_h = A.vals
+    if f64:
+        vals_h = wl.dense_uniform_f64(A.nnz, wl.BASE_SEED + cfg_no, wl.S_VALS)
+        dense_h = wl.dense_uniform_f64(A.cols, wl.BASE_SEED + cfg_no, wl.S_X)
     t_gen = time.time() - t_gen
     out_rows = A.rows * A.bs
     L = np.diff(A.pos)
     comp_bytes, noreuse_bytes = algorithmic_bytes(kind, A, k)
+    if f64:
+        comp_bytes = noreuse_bytes = 12 * A.nnz + 4 * (A.rows + 1) + 8 * A.cols + 8 * A.rows
     fl = flops(kind, A, k)
 
     op = {"csr_spmv": psk.PSK_OP_SPMV_CSR, "csr_spmm": psk.PSK_OP_SPMM_CSR, "bcsr_spmv": psk.PSK_OP_SPMV_BCSR,
           "bcsr_spmm": psk.PSK_OP_SPMM_BCSR}[kind]
+    if f64:
+        op = psk.PSK_OP_SPMV_CSR_F64
     tile = args.tile or psk.psk_default_tile(op)
     tile_given = bool(args.tile)
 
@@ -282,14 +295,15 @@ def main():
     sets = []
     for _ in range(copies):
         s = {"pos": torch.from_numpy(A.pos).to(dev), "crd": torch.from_numpy(A.crd).to(dev),
-             "vals": torch.from_numpy(A.vals).to(dev), "dense": torch.from_numpy(dense_h).to(dev)}
-        s["out"] = torch.empty((out_rows, k) if kind.endswith("spmm") else (out_rows,), device=dev)
+             "vals": torch.from_numpy(vals_h).to(dev), "dense": torch.from_numpy(dense_h).to(dev)}
+        s["out"] = torch.empty((out_rows, k) if kind.endswith("spmm") else (out_rows,), device=dev,
+                               dtype=torch.float64 if f64 else torch.float32)
         sets.append(s)
     stream = torch.cuda.current_stream()
 
     # plan step, outside the timed region like the workspace allocation: depends only on A
     col_passes = 1
-    if kind == "csr_spmv":
+    if kind == "csr_spmv" and not f64:
         col_passes = args.col_passes or psk.psk_analyze_csr(A.rows, A.cols, A.nnz, sets[0]["pos"], sets[0]["crd"],
                                                             stream=stream)
         if col_passes > 1 and not tile_given:
@@ -298,7 +312,10 @@ def main():
         s["ws"] = psk.workspace(op, A.rows, A.nnz, k=k, bs=A.bs, tile=tile, device=dev)
 
     def step(s, phases=psk.PSK_PHASE_ALL):
-        if kind == "csr_spmv":
+        if f64:
+            psk.psk_spmv_csr_f64(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"], tile=tile,
+                                 phases=phases, ws=s["ws"], stream=stream)
+        elif kind == "csr_spmv":
             psk.psk_spmv_csr(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"], tile=tile,
                              col_passes=col_passes, phases=phases, ws=s["ws"], stream=stream)
         elif kind == "csr_spmm":
@@ -346,7 +363,7 @@ def main():
     main_avg = sum(main_ms) / len(main_ms)
     kernel_bytes = noreuse_bytes if kind.endswith("spmm") else comp_bytes
     achieved = kernel_bytes / (main_avg * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, tile, col_passes))
+    traffic = None if f64 else MEASURED_TRAFFIC_BYTES.get((args.workload, tile, col_passes))
     if traffic is not None:
         traffic *= col_passes           # like `achieved`: all launches of the tile kernel in one product
 
@@ -361,7 +378,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f64" if f64 else "f32",
         "data": "synthetic",
         "config": {
             "workload": "%s: %s, %d x %d%s, nnz %d (max row %d, mean %.2f), tile %d, col_passes %d, k %d, %d operand copies rotated"
@@ -384,7 +401,7 @@ def main():
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": {"csr_spmv": "k_spmv_pos", "csr_spmm": "k_spmm_pos<1,*>", "bcsr_spmv": "k_spmv_bcsr4",
+            "kernel": "k_spmv_pos_f64" if f64 else {"csr_spmv": "k_spmv_pos", "csr_spmm": "k_spmm_pos<1,*>", "bcsr_spmv": "k_spmv_bcsr4",
                        "bcsr_spmm": "k_spmm_pos<4,*>"}[kind],
             "achieved": round(achieved, 2),
             "peak": HBM_PEAK_GBS,
@@ -399,7 +416,7 @@ def main():
         },
     }
 
-    if args.baselines and kind == "csr_spmv":
+    if args.baselines and kind == "csr_spmv" and not f64:
         base = {}
         for name, variant in (("thread_per_row", 0), ("wave_per_row", 1)):
             ts = []
@@ -458,7 +475,9 @@ def main():
         frac = 1.0 if sel is None else len(sel) / A.rows
 
         def run_oracle():
-            if kind == "csr_spmv":
+            if f64:
+                oracle.spmv_csr_f64(A.pos, A.crd, vals_h, dense_h, threads=cores)
+            elif kind == "csr_spmv":
                 oracle.spmv_csr(A.pos, A.crd, A.vals, dense_h, threads=cores)
             elif kind == "csr_spmm":
                 oracle.spmm_csr(A.pos, A.crd, A.vals, dense_h, sel=sel, threads=cores)

@@ -72,7 +72,8 @@ typedef enum {
     PSK_OP_SPMM_CSR = 1,
     PSK_OP_SPMV_BCSR = 2,
     PSK_OP_SPMM_BCSR = 3,
-    PSK_OP_MTTKRP_CSF3 = 4
+    PSK_OP_MTTKRP_CSF3 = 4,
+    PSK_OP_SPMV_CSR_F64 = 5
 } psk_op;
 
 enum { PSK_PHASE_PARTITION = 1, PSK_PHASE_MAIN = 2, PSK_PHASE_FIXUP = 4, PSK_PHASE_ALL = 7 };
@@ -222,6 +223,19 @@ int psk_partition_csf3(int64_t nslices, int64_t nfibers, int64_t nnz, const int3
 int psk_spmv_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos,
                           const int32_t *crd, const float *vals, const float *x, float *y,
                           int variant, void *stream);
+
+/*
+ * y = A x with fp64 values, vector and result (the value type of the paper's own schedules: the
+ * per-thread temporary of appendix "SPMV on a GPU" is Float64).  Same cut, tile kernel structure,
+ * carry records (doubles) and fix-up as psk_spmv_csr; one pass; products and sums in fp64.
+ * vals [nnz], x [cols], y [rows] doubles, 8-byte aligned (PSK_ERR_ALIGNMENT otherwise); crd and vals
+ * 16-byte aligned selects the 16-byte load path.  tile in {0, 256, 512, 1024, 2048}, 0 = 1024.
+ * Workspace from psk_workspace_bytes(PSK_OP_SPMV_CSR_F64, rows, nnz, 1, 1, tile).
+ * Deterministic; |y - exact| <= 1e-14 * sum_j |a_ij x_j| per row.
+ */
+int psk_spmv_csr_f64(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                     const double *vals, const double *x, double *y, int32_t tile, int phases,
+                     void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Baseline with the schedule's own race strategy (appendix "SPMV on a GPU": the thread level is

@@ -16,6 +16,7 @@ int32_t default_tile(int op)
         case PSK_OP_SPMV_BCSR: return 512;
         case PSK_OP_SPMM_BCSR: return 64;
         case PSK_OP_MTTKRP_CSF3: return 2048;
+        case PSK_OP_SPMV_CSR_F64: return 1024;
         default: return -1;
     }
 }
@@ -28,6 +29,7 @@ bool tile_ok(int op, int32_t tile)
         case PSK_OP_SPMV_BCSR:
         case PSK_OP_SPMM_BCSR: return bcsr_tile_ok(tile);
         case PSK_OP_MTTKRP_CSF3: return mttkrp_tile_ok(tile);
+        case PSK_OP_SPMV_CSR_F64: return spmv_csr_f64_tile_ok(tile);
         default: return false;
     }
 }
@@ -40,6 +42,7 @@ int64_t carry_width(int op, int32_t k, int32_t bs)
         case PSK_OP_SPMV_BCSR: return bs;
         case PSK_OP_SPMM_BCSR: return (int64_t)bs * k;
         case PSK_OP_MTTKRP_CSF3: return k;
+        case PSK_OP_SPMV_CSR_F64: return 2;   // one double per tile
         default: return 0;
     }
 }
@@ -161,6 +164,29 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
         else e = launch_spmv_csr_main((int32_t)rows, (int32_t)cols, (int32_t)nnz, pos, crd, vals, x, y, tile, col_passes, ws, s);
     }
     if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, 1, 1, tile, pos, ws, y, s);
+    return hip_status(e);
+}
+
+int psk_spmv_csr_f64(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                     const double *vals, const double *x, double *y, int32_t tile, int phases, void *workspace,
+                     size_t workspace_bytes, void *stream)
+{
+    Workspace ws;
+    int st = check_common(PSK_OP_SPMV_CSR_F64, rows, cols, nnz, pos, crd, vals, 1, 1, &tile, phases, workspace,
+                          workspace_bytes, &ws);
+    if (st != PSK_OK) return st;
+    if ((rows > 0 && !y) || (nnz > 0 && !x)) return PSK_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(vals) | reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) & 7)
+        return PSK_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int32_t ntiles = (int32_t)psk_num_tiles(nnz, tile);
+    hipError_t e = hipSuccess;
+    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, 0, ws.tile_row, s);
+    if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
+        if (ntiles == 0) e = launch_fill_zero(reinterpret_cast<float *>(y), 2 * rows, s);
+        else e = launch_spmv_csr_f64_main((int32_t)rows, (int32_t)nnz, pos, crd, vals, x, y, tile, ws, s);
+    }
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup_f64(ntiles, tile, pos, ws, y, s);
     return hip_status(e);
 }
 

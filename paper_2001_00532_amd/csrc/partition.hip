@@ -159,11 +159,13 @@ __device__ __forceinline__ int run_length(const int *__restrict__ pos, const int
 }
 
 // width = 1 (SpMV): a lane per tile; runs of more than 8 records are summed by the whole wave.
+// V = float: fp32 records and output, summed in fp64.  V = double: all fp64.
+template <typename V>
 __global__ __launch_bounds__(256) void k_carry_fixup1(int ntiles, long long ld, int tile, int shift,
                                                       const int *__restrict__ pos,
                                                       const int *__restrict__ carry_row,
-                                                      const float *__restrict__ carry_val,
-                                                      float *__restrict__ out)
+                                                      const V *__restrict__ carry_val,
+                                                      V *__restrict__ out)
 {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = threadIdx.x & (WAVE - 1);
@@ -174,13 +176,13 @@ __global__ __launch_bounds__(256) void k_carry_fixup1(int ntiles, long long ld, 
         if (r >= 0 && prev != r) len = run_length(pos, nullptr, r, t, tile, shift, ntiles);
     }
     if (len > 0 && len <= 8) {
-        float v[8];
+        V v[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = i < len ? carry_val[t + i] : 0.0f;
+        for (int i = 0; i < 8; ++i) v[i] = i < len ? carry_val[t + i] : V(0);
         double sum = 0.0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) sum += (double)v[i];
-        out[r * ld] = (float)((double)out[r * ld] + sum);
+        out[r * ld] = (V)((double)out[r * ld] + sum);
     }
     unsigned long long big = __ballot(len > 8);
     while (big) {
@@ -191,7 +193,7 @@ __global__ __launch_bounds__(256) void k_carry_fixup1(int ntiles, long long ld, 
         for (int u = lane; u < n; u += WAVE) acc += (double)carry_val[t0 + u];
 #pragma unroll
         for (int m = 1; m < WAVE; m <<= 1) acc += __shfl_xor(acc, m, WAVE);
-        if (lane == src) out[row * ld] = (float)((double)out[row * ld] + acc);
+        if (lane == src) out[row * ld] = (V)((double)out[row * ld] + acc);
     }
 }
 
@@ -233,13 +235,24 @@ hipError_t launch_carry_fixup(int32_t ntiles, int32_t nsub, int32_t k, int64_t l
     if ((tile & (tile - 1)) == 0) { shift = 0; while ((1 << shift) < tile) ++shift; }
     const int width = nsub * k;
     if (width == 1 && !pos2 && !rowmap) {
-        hipLaunchKernelGGL(k_carry_fixup1, dim3((unsigned)((ntiles + 255) / 256)), dim3(256), 0, s, ntiles,
+        hipLaunchKernelGGL(k_carry_fixup1<float>, dim3((unsigned)((ntiles + 255) / 256)), dim3(256), 0, s, ntiles,
                            (long long)ld, tile, shift, pos, w.carry_row, w.carry_val, out);
         return hipGetLastError();
     }
     const int64_t n = (int64_t)ntiles * width;
     hipLaunchKernelGGL(k_carry_fixup, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, ntiles, width, nsub, k,
                        (long long)ld, tile, shift, pos, pos2, rowmap, w.carry_row, w.carry_val, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_carry_fixup_f64(int32_t ntiles, int32_t tile, const int32_t *pos, const Workspace &w, double *out,
+                                  hipStream_t s)
+{
+    if (ntiles <= 1) return hipSuccess;
+    int shift = -1;
+    if ((tile & (tile - 1)) == 0) { shift = 0; while ((1 << shift) < tile) ++shift; }
+    hipLaunchKernelGGL(k_carry_fixup1<double>, dim3((unsigned)((ntiles + 255) / 256)), dim3(256), 0, s, ntiles, 1ll,
+                       tile, shift, pos, w.carry_row, reinterpret_cast<const double *>(w.carry_val), out);
     return hipGetLastError();
 }
 

@@ -1,0 +1,194 @@
+// CSR SpMV with fp64 values, vector and result: the value type of the paper's own schedules (the
+// per-thread temporary of appendix "SPMV on a GPU" is declared Float64).  Same position cut, row
+// logic and carry records as the fp32 kernel; one pass, 8-byte gathers.
+#include "psk_dev.h"
+#include "psk_internal.h"
+
+namespace psk {
+
+typedef double v2d __attribute__((ext_vector_type(2)));
+
+// Sum over the 64 lanes of a wave, same bits in every lane (xor butterfly through the LDS crossbar).
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) v += __shfl_xor(v, m, WAVE);
+    return v;
+}
+
+// One workgroup per tile of T = THREADS*NPT positions.  VEC: crd is read with 16-byte loads and vals
+// with two 16-byte loads per four positions (both arrays 16-byte aligned), a lane keeps four
+// consecutive positions; otherwise 4- and 8-byte loads at lane-consecutive positions.
+template <int THREADS, int NPT, bool VEC>
+__global__ __launch_bounds__(THREADS) void k_spmv_pos_f64(int rows, int nnz, const int *__restrict__ pos,
+                                                          const int *__restrict__ crd,
+                                                          const double *__restrict__ vals,
+                                                          const double *__restrict__ x, double *__restrict__ y,
+                                                          const int *__restrict__ tile_row,
+                                                          int *__restrict__ carry_row,
+                                                          double *__restrict__ carry_val, int ntiles)
+{
+    constexpr int T = THREADS * NPT;
+    constexpr int NW = THREADS / WAVE;
+    constexpr int LONG = 32;
+    constexpr int MAXLONG = T / LONG;
+    static_assert(NPT % 4 == 0, "NPT must be a multiple of 4");
+    __shared__ double sprod[skewed_size<1>(T)];
+    __shared__ int slong[MAXLONG * 3];
+    __shared__ int nlong;
+    __shared__ double swave[NW];
+
+    const int t = xcd_tile(blockIdx.x, ntiles);
+    if (t < 0) return;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
+    const int t0 = t * T;
+    const int cnt = (nnz - t0 < T) ? nnz - t0 : T;
+    const int t1 = t0 + cnt;
+    auto index = [&](int g) { return VEC ? ((g / 4) * THREADS + tid) * 4 + (g & 3) : g * THREADS + tid; };
+
+    // the dependent chain tile_row -> pos is started first and runs underneath the streams
+    const int r0 = tile_row[t], r1 = tile_row[t + 1];
+
+    double prod[NPT];
+    const bool full = cnt == T;
+    if (full) {
+        int c[NPT];
+        double v[NPT];
+        if (VEC) {
+#pragma unroll
+            for (int g = 0; g < NPT / 4; ++g) {
+                const int off = t0 + (g * THREADS + tid) * 4;
+                const v4i cv = ld_stream(reinterpret_cast<const v4i *>(crd + off));
+                const v2d va = ld_stream(reinterpret_cast<const v2d *>(vals + off));
+                const v2d vb = ld_stream(reinterpret_cast<const v2d *>(vals + off + 2));
+                c[4 * g] = cv.x; c[4 * g + 1] = cv.y; c[4 * g + 2] = cv.z; c[4 * g + 3] = cv.w;
+                v[4 * g] = va.x; v[4 * g + 1] = va.y; v[4 * g + 2] = vb.x; v[4 * g + 3] = vb.y;
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < NPT; ++g) {
+                c[g] = ld_stream(crd + t0 + g * THREADS + tid);
+                v[g] = ld_stream(vals + t0 + g * THREADS + tid);
+            }
+        }
+        double xg[NPT];
+#pragma unroll
+        for (int g = 0; g < NPT; ++g) xg[g] = x[c[g]];
+#pragma unroll
+        for (int g = 0; g < NPT; ++g) prod[g] = v[g] * xg[g];
+    }
+
+    const int p_r0 = pos[r0], p_r1 = pos[r1];
+    const int rbeg = (t == 0) ? 0 : r0;
+    int my_lo = 0, my_hi = 0;
+    if (rbeg + tid < rows) {
+        my_lo = pos[rbeg + tid];
+        my_hi = pos[rbeg + tid + 1];
+    }
+
+    if (!full) {   // last tile: guarded
+#pragma unroll
+        for (int g = 0; g < NPT; ++g) {
+            const int i = index(g);
+            prod[g] = i < cnt ? vals[t0 + i] * x[crd[t0 + i]] : 0.0;
+        }
+    }
+
+    const bool has_carry = (t > 0) && (p_r0 < t0);
+    const int rend = (p_r1 == t1) ? r1 : r1 + 1;
+    if (tid == 0 && !has_carry) carry_row[t] = -1;
+    auto emit = [&](int r, double v) {
+        if (has_carry && r == r0) {
+            carry_row[t] = r;
+            carry_val[t] = v;
+        } else {
+            y[r] = v;
+        }
+    };
+
+    if (rend - rbeg == 1) {   // the tile lies inside a single row
+        double s = 0.0;
+#pragma unroll
+        for (int g = 0; g < NPT; ++g) s += prod[g];
+        s = wave_sum_f64(s);
+        if (lane == 0) swave[wave] = s;
+        __syncthreads();
+        if (tid == 0) {
+            double tot = swave[0];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) tot += swave[w];
+            emit(rbeg, tot);
+        }
+        return;
+    }
+
+    if (tid == 0) nlong = 0;
+#pragma unroll
+    for (int g = 0; g < NPT; ++g) sprod[skew<1>(index(g))] = prod[g];
+    __syncthreads();
+    for (int r = rbeg + tid; r < rend; r += THREADS) {
+        int lo = my_lo - t0, hi = my_hi - t0;
+        if (r + THREADS < rend) { my_lo = pos[r + THREADS]; my_hi = pos[r + THREADS + 1]; }
+        lo = lo < 0 ? 0 : lo;
+        hi = hi > cnt ? cnt : hi;
+        if (hi - lo < LONG) {
+            double s = 0.0;
+            int i = lo;
+            for (; i + 4 <= hi; i += 4) {
+                const double a = sprod[skew<1>(i)], b = sprod[skew<1>(i + 1)], c = sprod[skew<1>(i + 2)],
+                             d = sprod[skew<1>(i + 3)];
+                s += a; s += b; s += c; s += d;
+            }
+            for (; i < hi; ++i) s += sprod[skew<1>(i)];
+            emit(r, s);
+        } else {
+            const int e = atomicAdd(&nlong, 1);
+            if (e < MAXLONG) { slong[3 * e] = r; slong[3 * e + 1] = lo; slong[3 * e + 2] = hi; }
+        }
+    }
+    __syncthreads();
+    const int nl = nlong < MAXLONG ? nlong : MAXLONG;
+    for (int e = wave; e < nl; e += NW) {
+        const int r = slong[3 * e], lo = slong[3 * e + 1], hi = slong[3 * e + 2];
+        double s = 0.0;
+        for (int i = lo + lane; i < hi; i += WAVE) s += sprod[skew<1>(i)];
+        s = wave_sum_f64(s);
+        if (lane == 0) emit(r, s);
+    }
+}
+
+bool spmv_csr_f64_tile_ok(int32_t tile) { return tile == 256 || tile == 512 || tile == 1024 || tile == 2048; }
+
+template <int THREADS, int NPT>
+static void go(bool vec, int grid, hipStream_t s, int rows, int nnz, const int *pos, const int *crd, const double *vals,
+               const double *x, double *y, const Workspace &w, int ntiles)
+{
+    double *cv = reinterpret_cast<double *>(w.carry_val);
+    if (vec)
+        hipLaunchKernelGGL((k_spmv_pos_f64<THREADS, NPT, true>), dim3(grid), dim3(THREADS), 0, s, rows, nnz, pos, crd, vals,
+                           x, y, w.tile_row, w.carry_row, cv, ntiles);
+    else
+        hipLaunchKernelGGL((k_spmv_pos_f64<THREADS, NPT, false>), dim3(grid), dim3(THREADS), 0, s, rows, nnz, pos, crd,
+                           vals, x, y, w.tile_row, w.carry_row, cv, ntiles);
+}
+
+hipError_t launch_spmv_csr_f64_main(int32_t rows, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                                    const double *vals, const double *x, double *y, int32_t tile, const Workspace &w,
+                                    hipStream_t s)
+{
+    const int ntiles = (int)(((int64_t)nnz + tile - 1) / tile);
+    if (ntiles == 0) return hipSuccess;
+    const int grid = xcd_grid(ntiles);
+    const bool vec = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
+    switch (tile) {
+        case 256:  go<64, 4>(vec, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles); break;
+        case 512:  go<128, 4>(vec, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles); break;
+        case 1024: go<256, 4>(vec, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles); break;
+        case 2048: go<256, 8>(vec, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace psk

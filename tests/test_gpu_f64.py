@@ -1,0 +1,99 @@
+"""GPU parity for the fp64 CSR SpMV: |got - ref| <= 1e-14 * sum |a x| + 1e-300 per row against the
+extended-precision oracle (fp64 unit round-off 1.1e-16; a row segment is summed from < 45 rounded
+operations, carries add one more)."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from conftest import ADVERSARIAL_KINDS, adversarial_lengths
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import paper_2001_00532_amd as psk  # noqa: E402
+
+REL, FLOOR = 1e-14, 1e-300
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run(name, A, tile, offset=0):
+    vals = wl.dense_uniform_f64(A.nnz, 5, wl.S_VALS)
+    x = wl.dense_uniform_f64(A.cols, 6, wl.S_X)
+    ref, mag = oracle.spmv_csr_f64(A.pos, A.crd, vals, x, threads=8)
+    if offset:   # operands that are 8- but not 16-byte aligned: the 4/8-byte load path
+        crd_d = torch.empty(A.nnz + 4, dtype=torch.int32, device="cuda")[offset:offset + A.nnz]
+        crd_d.copy_(dev(A.crd))
+        vals_d = torch.empty(A.nnz + 1, dtype=torch.float64, device="cuda")[1:]
+        vals_d.copy_(dev(vals))
+    else:
+        crd_d, vals_d = dev(A.crd), dev(vals)
+    y = torch.full((A.rows,), float("nan"), dtype=torch.float64, device="cuda")
+    say("f64", name, "tile", tile, "offset", offset, "rows", A.rows, "nnz", A.nnz)
+    psk.psk_spmv_csr_f64(A.rows, A.cols, A.nnz, dev(A.pos), crd_d, vals_d, dev(x), y, tile=tile)
+    torch.cuda.synchronize()
+    ok, worst = oracle.within_tolerance(y.cpu().numpy(), ref, mag, REL, FLOOR)
+    assert ok, "%s tile %d: worst |err|/bound = %.3g" % (name, tile, worst)
+    return y
+
+
+@pytest.mark.parametrize("tile", [0, 256, 512, 1024, 2048])
+def test_f64_structures(tile):
+    rng = np.random.default_rng(21)
+    for kind in ADVERSARIAL_KINDS:
+        A = wl.csr_from_lengths(adversarial_lengths(rng, 3001, 5003, kind), 5003, seed=21)
+        run(kind, A, tile)
+    run("powerlaw", wl.config(2, 0.01)["A"], tile)
+    run("stencil", wl.config(3, 0.01)["A"], tile)
+
+
+def test_f64_unaligned_and_edges():
+    rng = np.random.default_rng(22)
+    A = wl.csr_from_lengths(adversarial_lengths(rng, 2000, 3000, "mixed"), 3000, seed=22)
+    run("unaligned", A, 1024, offset=1)
+    run("unaligned", A, 256, offset=3)
+    run("one entry", wl.csr_from_lengths(np.array([0, 1, 0]), 4, seed=1), 0)
+    run("empty", wl.csr_from_lengths(np.zeros(17, dtype=np.int64), 5, seed=1), 0)
+    run("exact multiple of the tile", wl.csr_from_lengths(np.full(512, 8), 100, seed=2), 1024)
+
+
+def test_f64_is_deterministic_and_uses_fp64():
+    A = wl.config(2, 0.02)["A"]
+    y1 = run("det", A, 0)
+    y2 = run("det", A, 0)
+    assert torch.equal(y1, y2)
+    # an fp32 computation of the same product misses the fp64 bar by orders of magnitude
+    vals = wl.dense_uniform_f64(A.nnz, 5, wl.S_VALS)
+    x = wl.dense_uniform_f64(A.cols, 6, wl.S_X)
+    ref, mag = oracle.spmv_csr_f64(A.pos, A.crd, vals, x, threads=8)
+    y32 = torch.empty(A.rows, device="cuda")
+    psk.psk_spmv_csr(A.rows, A.cols, A.nnz, dev(A.pos), dev(A.crd), dev(vals.astype(np.float32)),
+                     dev(x.astype(np.float32)), y32)
+    ok, _ = oracle.within_tolerance(y32.double().cpu().numpy(), ref, mag, REL, FLOOR)
+    assert not ok
+
+
+def test_f64_full_size_powerlaw_sampled():
+    A = wl.config(2)["A"]
+    vals = wl.dense_uniform_f64(A.nnz, 5, wl.S_VALS)
+    x = wl.dense_uniform_f64(A.cols, 6, wl.S_X)
+    y = torch.full((A.rows,), float("nan"), dtype=torch.float64, device="cuda")
+    say("f64 full size", A.rows, A.nnz)
+    psk.psk_spmv_csr_f64(A.rows, A.cols, A.nnz, dev(A.pos), dev(A.crd), dev(vals), dev(x), y)
+    torch.cuda.synchronize()
+    assert not torch.isnan(y).any()
+    lens = np.diff(A.pos)
+    sel = np.unique(np.concatenate([np.random.default_rng(5).integers(0, A.rows, 20000), np.argsort(lens)[-50:]])).astype(np.int64)
+    ref, mag = oracle.spmv_csr_f64(A.pos, A.crd, vals, x, sel=sel, threads=16)
+    ok, worst = oracle.within_tolerance(y[torch.from_numpy(sel).cuda()].cpu().numpy(), ref, mag, REL, FLOOR)
+    assert ok, "worst %.3g" % worst
