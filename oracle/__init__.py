@@ -46,6 +46,8 @@ def _lib():
         lib.oracle_spmv_csr.restype = None
         lib.oracle_spmv_csr_f64.argtypes = [i64, p, p, p, p, p, p, p, i64, ci]
         lib.oracle_spmv_csr_f64.restype = None
+        lib.oracle_spmv_dcsr.argtypes = [i64, i64, p, p, p, p, p, p, p]
+        lib.oracle_spmv_dcsr.restype = None
         lib.oracle_spmm_csr.argtypes = [i64, i64, p, p, p, p, i64, p, p, p, i64, ci]
         lib.oracle_spmm_csr.restype = None
         lib.oracle_spmv_bcsr.argtypes = [i64, i32, p, p, p, p, p, p, p, i64, ci]
@@ -110,6 +112,16 @@ def spmv_csr_f64(pos, crd, vals, x, sel=None, threads: int = 1):
     mag = np.empty(n, dtype=np.float64)
     _lib().oracle_spmv_csr_f64(rows, pos.ctypes.data, crd.ctypes.data, vals.ctypes.data, x.ctypes.data,
                                y.ctypes.data, mag.ctypes.data, sp, ns, int(threads))
+    return y, mag
+
+
+def spmv_dcsr(rows: int, crd_i, pos, crd, vals, x):
+    """DCSR operand: crd_i [nstored] row coordinates, pos [nstored+1].  Returns (y, mag), `rows` float64 each."""
+    crd_i, pos, crd, vals, x = _i32(crd_i), _i32(pos), _i32(crd), _f32(vals), _f32(x)
+    y = np.empty(int(rows), dtype=np.float64)
+    mag = np.empty(int(rows), dtype=np.float64)
+    _lib().oracle_spmv_dcsr(int(rows), crd_i.size, crd_i.ctypes.data, pos.ctypes.data, crd.ctypes.data,
+                            vals.ctypes.data, x.ctypes.data, y.ctypes.data, mag.ctypes.data)
     return y, mag
 
 

@@ -263,6 +263,25 @@ void oracle_partition_csf3(int64_t nslices, int64_t nfibers, int64_t nnz, const 
     }
 }
 
+/* y(i) = A(i,j) * x(j) with A in DCSR: both levels compressed (Section 2 names DCSR among the concrete
+ * forms of a coordinate hierarchy).  Stored row s has coordinate crd_i[s] (strictly increasing) and the
+ * entries pos[s] .. pos[s+1]-1; rows that are not stored are zero.  y and mag have `rows` doubles. */
+void oracle_spmv_dcsr(int64_t rows, int64_t nstored, const int32_t *crd_i, const int32_t *pos,
+                      const int32_t *crd, const float *vals, const float *x, double *y, double *mag)
+{
+    for (int64_t i = 0; i < rows; ++i) { y[i] = 0.0; if (mag) mag[i] = 0.0; }
+    for (int64_t s = 0; s < nstored; ++s) {
+        double acc = 0.0, m = 0.0;
+        for (int64_t p = pos[s]; p < pos[s + 1]; ++p) {
+            double t = (double)vals[p] * (double)x[crd[p]];
+            acc += t;
+            m += fabs(t);
+        }
+        y[crd_i[s]] = acc;
+        if (mag) mag[crd_i[s]] = m;
+    }
+}
+
 /*
  * Structural validity of a CSR/BCSR index structure: pos[0]=0, pos monotone,
  * pos[rows]=nnz, 0 <= crd < cols.  Returns 0 if valid, else a code 1..4.

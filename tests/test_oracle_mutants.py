@@ -40,6 +40,9 @@ MUTANTS = [
      "    int64_t i = 0;\n    for (int64_t t = 0; t <= ntiles; ++t) {\n        i = t;\n        int64_t first = t * tile;"),
     ("partition_stops_at_empty_rows", "while (i < rows && (int64_t)pos[i + 1] <= first) ++i;", "if (i < rows && (int64_t)pos[i + 1] <= first) ++i;"),
     ("num_tiles_floor", "(nnz + tile - 1) / tile", "nnz / tile"),
+    ("dcsr_writes_by_stored_index", "        y[crd_i[s]] = acc;", "        y[s] = acc;"),
+    ("dcsr_absent_rows_not_zeroed", "for (int64_t i = 0; i < rows; ++i) { y[i] = 0.0; if (mag) mag[i] = 0.0; }",
+     "for (int64_t i = 0; i < nstored; ++i) { y[i] = 0.0; if (mag) mag[i] = 0.0; }"),
     ("f64_sums_in_double", "long double acc = 0.0L, m = 0.0L;", "double acc = 0.0, m = 0.0;"),
     ("f64_x_indexed_by_position", "(long double)vals[p] * (long double)x[crd[p]];", "(long double)vals[p] * (long double)x[p % 3];"),
     ("f64_operands_read_as_float", "(long double)vals[p] * (long double)x[crd[p]];", "(long double)(float)vals[p] * (long double)x[crd[p]];"),
@@ -119,6 +122,15 @@ def pins_pass(lib) -> bool:
                      Fraction(0))
             if abs(Fraction(float(y64[i])) - ex) > Fraction(1, 2 ** 50):
                 return False
+        # DCSR: hand-worked case (rows 1 and 4 of a 6 x 3 matrix), output buffers pre-filled with garbage
+        real_empty = np.empty
+        np.empty = lambda *a, **k: np.full(*a, 7.5, **k) if k.get("dtype") == np.float64 else real_empty(*a, **k)
+        try:
+            y, mag = oracle.spmv_dcsr(6, [1, 4], [0, 2, 3], [0, 2, 1], [2.0, -1.0, 3.0], [1.0, 2.0, 3.0])
+        finally:
+            np.empty = real_empty
+        if y.tolist() != [0.0, -1.0, 0.0, 0.0, 6.0, 0.0] or mag.tolist() != [0.0, 5.0, 0.0, 0.0, 6.0, 0.0]:
+            return False
         # partition: closed form, last-tile clamp, empty rows
         p = (np.arange(51) * 7).astype(np.int32)
         if oracle.partition(p, 13).tolist() != [min(t * 13, 350) // 7 for t in range(27)] + [50]:

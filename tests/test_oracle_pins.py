@@ -409,3 +409,41 @@ def test_f64_generator_uses_more_than_fp32_precision():
     v = wl.dense_uniform_f64(1000, 1, wl.S_VALS)
     assert v.dtype == np.float64 and np.any(v != v.astype(np.float32).astype(np.float64))
     assert v.min() >= -1.0 and v.max() < 1.0 + 2.0 ** -23
+
+
+# ------------------------------------------------------------------ DCSR SpMV oracle
+def _dense_of_dcsr(A):
+    D = np.zeros((A.rows, A.cols))
+    for s in range(A.nstored):
+        for p in range(A.pos[s], A.pos[s + 1]):
+            D[A.crd_i[s], A.crd[p]] += float(A.vals[p])
+    return D
+
+
+def test_dcsr_oracle_against_dense_brute_force():
+    rng = np.random.default_rng(77)
+    for rows, nstored, cols in ((40, 9, 23), (1000, 37, 50), (12, 12, 7), (5, 0, 3)):
+        A = wl.dcsr_from_lengths(rows, rng.integers(0, min(cols, 9) + 1, size=nstored), cols, seed=77)
+        assert np.all(np.diff(A.crd_i) > 0) and (nstored == 0 or (A.crd_i[0] >= 0 and A.crd_i[-1] < rows))
+        x = wl.dense_uniform(cols, 77, wl.S_X)
+        y, mag = oracle.spmv_dcsr(rows, A.crd_i, A.pos, A.crd, A.vals, x)
+        D = _dense_of_dcsr(A)
+        assert np.allclose(y, D @ x.astype(np.float64), rtol=0, atol=1e-13)
+        assert np.allclose(mag, np.abs(D) @ np.abs(x.astype(np.float64)), rtol=0, atol=1e-13)
+        absent = np.setdiff1d(np.arange(rows), A.crd_i)
+        assert np.all(y[absent] == 0.0) and np.all(mag[absent] == 0.0)
+
+
+def test_dcsr_oracle_hand_worked():
+    # rows 1 and 4 of a 6 x 3 matrix: [2 0 -1] and [0 3 0]; x = [1 2 3]
+    y, mag = oracle.spmv_dcsr(6, [1, 4], [0, 2, 3], [0, 2, 1], [2.0, -1.0, 3.0], [1.0, 2.0, 3.0])
+    assert y.tolist() == [0.0, -1.0, 0.0, 0.0, 6.0, 0.0]
+    assert mag.tolist() == [0.0, 5.0, 0.0, 0.0, 6.0, 0.0]
+
+
+def test_dcsr_oracle_reduces_to_csr_when_every_row_is_stored():
+    A = wl.csr_from_lengths(np.random.default_rng(5).integers(0, 30, size=200), 90, seed=5)
+    x = wl.dense_uniform(90, 5, wl.S_X)
+    y0, m0 = oracle.spmv_csr(A.pos, A.crd, A.vals, x)
+    y1, m1 = oracle.spmv_dcsr(200, np.arange(200), A.pos, A.crd, A.vals, x)
+    assert np.array_equal(y0, y1) and np.array_equal(m0, m1)

@@ -115,6 +115,42 @@ def csr_from_lengths(lengths, cols: int, seed: int, lo: float = -1.0, hi: float 
     return CSR(rows, int(cols), pos, crd, vals, bs)
 
 
+@dataclass
+class DCSR:
+    rows: int          # extent of the row dimension
+    cols: int
+    crd_i: np.ndarray  # int32 [nstored]  coordinates of the stored rows, strictly increasing
+    pos: np.ndarray    # int32 [nstored+1]
+    crd: np.ndarray    # int32 [nnz]
+    vals: np.ndarray   # float32 [nnz]
+
+    @property
+    def nstored(self) -> int:
+        return int(self.crd_i.shape[0])
+
+    @property
+    def nnz(self) -> int:
+        return int(self.pos[-1])
+
+
+def dcsr_from_lengths(rows: int, lengths, cols: int, seed: int) -> DCSR:
+    """DCSR with len(lengths) stored rows (a stored row may still be empty) placed at distinct,
+    sorted row coordinates drawn uniformly from [0, rows)."""
+    A = csr_from_lengths(lengths, cols, seed)
+    n = A.rows
+    if n > rows:
+        raise ValueError("more stored rows than rows")
+    if n == rows:
+        crd_i = np.arange(rows, dtype=np.int32)
+    else:
+        # distinct sorted coordinates: stratified draw, one per equal slice of [0, rows)
+        u = dense_uniform(n, seed, S_LEN, 0.0, 1.0).astype(np.float64)
+        lo = (np.arange(n, dtype=np.int64) * rows) // max(1, n)
+        hi = ((np.arange(n, dtype=np.int64) + 1) * rows) // max(1, n)
+        crd_i = (lo + np.minimum((u * (hi - lo)).astype(np.int64), hi - lo - 1)).astype(np.int32)
+    return DCSR(int(rows), int(cols), crd_i, A.pos, A.crd, A.vals)
+
+
 def csr_uniform(rows: int, cols: int, per_row: int, seed: int, bs: int = 1) -> CSR:
     """Exactly ``per_row`` stored entries in every row."""
     return csr_from_lengths(np.full(rows, per_row, dtype=np.int64), cols, seed, bs=bs)
