@@ -21,6 +21,8 @@ Workloads (names of the evaluated configurations):
   mttkrp              MTTKRP A(i,j) = B(i,k,l) C(k,j) D(l,j): B 500k x 100k x 100k in three compressed levels,
                       ~4M fibers, ~46M nonzeros (Zipf leaves per fiber), j = 64 (the paper's third kernel;
                       synthetic stand-in for the FROSTT tensors it uses)
+  dcsr                SpMV on a hypersparse DCSR operand: 2^26 rows of which 10^6 are stored, Zipf row lengths
+                      (alpha 1.8, <= 50 000), 2^21 columns, ~21 M nonzeros; --cut positions|rows
   fewlong             CSR SpMV, 100 x 100000 with 10000 per row (Section 8.5: too few rows for a
                       row-split kernel to fill the GPU)
   expskew             CSR SpMV, 65536 x 1M, 4M nonzeros, row lengths ~ base**rank shuffled
@@ -62,6 +64,7 @@ WORKLOADS = {
     "bcsr_spmm": (5, "bcsr_spmm"),
     "uniform28": (0, "csr_spmv"),
     "mttkrp": (0, "mttkrp"),
+    "dcsr": (0, "dcsr"),
     "fewlong": (0, "csr_spmv"),
     "expskew": (0, "csr_spmv"),
     "copy": (0, "copy"),
@@ -215,6 +218,93 @@ def bench_mttkrp(args, torch, psk, wl):
     print(json.dumps(rec))
 
 
+def bench_dcsr(args, torch, psk, wl):
+    """SpMV on the synthetic hypersparse matrix, cut at the column level or at the row level."""
+    t_gen = time.time()
+    Ls = wl.zipf_lengths(1_000_000, 1.8, 1, 50_000, wl.BASE_SEED + 11)
+    A = wl.dcsr_from_lengths(1 << 26, Ls, 1 << 21, seed=wl.BASE_SEED + 11)
+    xh = wl.dense_uniform(A.cols, wl.BASE_SEED + 11, wl.S_X)
+    t_gen = time.time() - t_gen
+    cut = psk.PSK_CUT_POSITIONS if args.cut == "positions" else psk.PSK_CUT_ROWS
+    tile = args.tile or psk.psk_default_tile(psk.PSK_OP_SPMV_CSR)
+    nnz, ns = A.nnz, A.nstored
+    comp = 8 * nnz + 4 * (ns + 1) + 4 * ns + 4 * A.cols + 4 * A.rows
+    fl = 2 * nnz
+    dev = torch.device("cuda:0")
+    copies = args.copies or 3
+    sets = []
+    for _ in range(copies):
+        s = {k_: torch.from_numpy(getattr(A, k_)).to(dev) for k_ in ("crd_i", "pos", "crd", "vals")}
+        s["x"] = torch.from_numpy(xh).to(dev)
+        s["y"] = torch.empty(A.rows, device=dev)
+        s["ws"] = psk.workspace(psk.PSK_OP_SPMV_CSR, ns, nnz, tile=tile, device=dev)
+        sets.append(s)
+    stream = torch.cuda.current_stream()
+
+    def step(s, phases=psk.PSK_PHASE_ALL):
+        psk.psk_spmv_dcsr(A.rows, A.cols, nnz, s["crd_i"], s["pos"], s["crd"], s["vals"], s["x"], s["y"], cut=cut,
+                          tile=tile, phases=phases, ws=s["ws"], stream=stream)
+
+    for i in range(args.warmup):
+        step(sets[i % copies])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(sets[i % copies])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    def time_phase(phases, reps=16, warm=8):
+        ts = []
+        for i in range(warm + reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            step(sets[i % copies], phases)
+            e1.record(stream)
+            e1.synchronize()
+            if i >= warm:
+                ts.append(e0.elapsed_time(e1))
+        return ts
+
+    main_ms = time_phase(psk.PSK_PHASE_MAIN)
+    all_ms = time_phase(psk.PSK_PHASE_ALL)
+    main_avg = sum(main_ms) / len(main_ms)
+    achieved = comp / (main_avg * 1e-3) / 1e9
+    rec = {
+        "metric": "SpMV/SpMM GFLOP/s and achieved HBM GB/s (% of MI355X peak), 1 GPU",
+        "value": round(fl / (wall / args.steps) / 1e9, 3), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(wall / args.steps * 1e3, 6), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "dcsr: %d rows (%d stored), %d cols, nnz %d (max row %d), cut at the %s level, tile %d, "
+                               "%d operand copies rotated" % (A.rows, ns, A.cols, nnz, int(Ls.max()), args.cut, tile, copies),
+                   "rows": A.rows, "stored_rows": ns, "cols": A.cols, "nnz": nnz, "cut": args.cut, "tile": tile,
+                   "seed": wl.BASE_SEED + 11},
+        "ns_per_nnz": round(wall / args.steps * 1e9 / nnz, 6),
+        "phases_us_median": {"main": round(statistics.median(main_ms) * 1e3, 2),
+                             "all": round(statistics.median(all_ms) * 1e3, 2)},
+        "roofline": {"bound": "hbm", "kernel": "k_fill_zero + " + ("k_spmv_pos" if args.cut == "positions" else "k_spmv_wave_per_row"),
+                     "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "algorithmic_bytes": comp,
+                     "avg_launch_us": round(main_avg * 1e3, 2), "launches_per_step": 2,
+                     "byte_model": "A once + x once + y once (the zero-fill of y is part of the main phase)"},
+    }
+    if not args.no_cpu:
+        import oracle
+
+        ts = []
+        for r in range(4):
+            t = time.perf_counter()
+            oracle.spmv_dcsr(A.rows, A.crd_i, A.pos, A.crd, A.vals, xh)
+            if r:
+                ts.append(time.perf_counter() - t)
+        tmed = statistics.median(ts)
+        rec["cpu_baseline"] = {"value": round(fl / tmed / 1e9, 3), "unit": "GFLOP/s", "cores": 1, "kind": "oracle",
+                               "sample": "the whole workload, fp64 accumulation, single thread, 1 warm-up + 3 runs, "
+                                         "median %.3f s" % tmed}
+    rec["generate_s"] = round(t_gen, 2)
+    print(json.dumps(rec))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -226,6 +316,8 @@ def main():
                     help="column passes of the CSR SpMV (0 = ask psk_analyze_csr)")
     ap.add_argument("--skew-base", type=float, default=1.00256, help="base of the expskew workload")
     ap.add_argument("--copies", type=int, default=0, help="operand copies rotated between steps (0 = auto)")
+    ap.add_argument("--cut", choices=["positions", "rows"], default="positions",
+                    help="dcsr: level of the position cut (column level = equal nonzeros, row level = equal stored rows)")
     ap.add_argument("--f64", action="store_true", help="CSR SpMV workloads: fp64 values, vector and result")
     ap.add_argument("--rank", type=int, default=64, help="mttkrp: number of columns j of the factor matrices")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
@@ -250,6 +342,8 @@ def main():
         return bench_copy(args, torch)
     if kind == "mttkrp":
         return bench_mttkrp(args, torch, psk, wl)
+    if kind == "dcsr":
+        return bench_dcsr(args, torch, psk, wl)
     t_gen = time.time()
     if args.workload == "uniform28":
         A28 = wl.csr_uniform(2_000_000, 2_000_000, 28, wl.BASE_SEED + 6)

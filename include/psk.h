@@ -238,6 +238,25 @@ int psk_spmv_csr_f64(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos
                      void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * y = A x with A in DCSR, the doubly compressed form for hypersparse matrices (Section 2 names it next
+ * to CSR; Section 3, last paragraphs: a position cut can be taken at any level of the hierarchy).
+ * Only `nstored` rows are stored: crd_i [nstored] holds their coordinates (strictly increasing, in
+ * [0, rows)), pos [nstored + 1], crd and vals [nnz] are as in CSR but indexed by stored row.  y has
+ * `rows` entries; rows that are not stored (and stored rows without entries) become +0.
+ *   cut = PSK_CUT_POSITIONS: tiles of `tile` positions of the column level (equal work per tile; a row
+ *         may be divided; table, carries and fix-up as in psk_spmv_csr, the table holds stored-row
+ *         indices).  tile, workspace: as psk_spmv_csr with rows = nstored and col_passes = 1.
+ *   cut = PSK_CUT_ROWS: tiles of four positions of the row level, one wave per stored row (equal
+ *         number of stored rows per tile; no row is divided, so no table, no carries, no fix-up:
+ *         only PSK_PHASE_MAIN does anything).  `tile` must still be a valid value (0 is).
+ * The main phase zero-fills y first.
+ */
+enum { PSK_CUT_POSITIONS = 0, PSK_CUT_ROWS = 1 };
+int psk_spmv_dcsr(int64_t rows, int64_t cols, int64_t nstored, int64_t nnz, const int32_t *crd_i,
+                  const int32_t *pos, const int32_t *crd, const float *vals, const float *x, float *y,
+                  int cut, int32_t tile, int phases, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Baseline with the schedule's own race strategy (appendix "SPMV on a GPU": the thread level is
  * parallelised with OutputRaceStrategy::Atomics; Section 6.3, first strategy): same position cut and tile
  * kernel as psk_spmv_csr, but y is zero-filled first and the part of a row that other tiles also hold is

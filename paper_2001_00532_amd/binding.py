@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libpsk.so")
 PSK_OK = 0
 PSK_OP_SPMV_CSR, PSK_OP_SPMM_CSR, PSK_OP_SPMV_BCSR, PSK_OP_SPMM_BCSR, PSK_OP_MTTKRP_CSF3 = 0, 1, 2, 3, 4
 PSK_OP_SPMV_CSR_F64 = 5
+PSK_CUT_POSITIONS, PSK_CUT_ROWS = 0, 1
 PSK_PHASE_PARTITION, PSK_PHASE_MAIN, PSK_PHASE_FIXUP, PSK_PHASE_ALL = 1, 2, 4, 7
 PSK_ROWSPLIT_THREAD_PER_ROW, PSK_ROWSPLIT_WAVE_PER_ROW = 0, 1
 
@@ -24,7 +25,7 @@ EXPORTS = [
     "psk_status_string", "psk_version", "psk_default_tile", "psk_num_tiles", "psk_workspace_bytes",
     "psk_partition_csr", "psk_analyze_csr", "psk_spmv_csr", "psk_spmm_csr", "psk_spmv_bcsr", "psk_spmm_bcsr",
     "psk_spmv_csr_rowsplit", "psk_spmm_csr_rowsplit", "psk_spmv_csr_atomics", "psk_mttkrp_csf3",
-    "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64",
+    "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64", "psk_spmv_dcsr",
 ]
 
 
@@ -72,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.psk_spmv_csr_notemp.restype = ci
         L.psk_spmv_csr_f64.argtypes = [i64, i64, i64, p, p, p, p, p, i32, ci, p, sz, p]
         L.psk_spmv_csr_f64.restype = ci
+        L.psk_spmv_dcsr.argtypes = [i64, i64, i64, i64, p, p, p, p, p, p, ci, i32, ci, p, sz, p]
+        L.psk_spmv_dcsr.restype = ci
         L.psk_spmv_csr_rowsplit.argtypes = [i64, i64, i64, p, p, p, p, p, ci, p]
         L.psk_spmv_csr_rowsplit.restype = ci
         L.psk_spmm_csr_rowsplit.argtypes = [i64, i64, i64, p, p, p, p, i32, i64, p, i64, p]
@@ -249,6 +252,19 @@ def psk_spmv_csr_f64(rows, cols, nnz, pos, crd, vals, x, y, tile=0, phases=PSK_P
                                 _ptr(vals, torch.float64), _ptr(x, torch.float64), _ptr(y, torch.float64),
                                 int(tile), int(phases), _ptr(ws), ws.numel(), _stream(stream))
     _check(st, "psk_spmv_csr_f64")
+    return y
+
+
+def psk_spmv_dcsr(rows, cols, nnz, crd_i, pos, crd, vals, x, y, cut=PSK_CUT_POSITIONS, tile=0, phases=PSK_PHASE_ALL,
+                  ws=None, stream=None):
+    nstored = int(crd_i.numel())
+    if ws is None:
+        ws = workspace(PSK_OP_SPMV_CSR, nstored, nnz, tile=tile, device=pos.device)
+    st = lib().psk_spmv_dcsr(int(rows), int(cols), nstored, int(nnz), _ptr(crd_i, torch.int32), _ptr(pos, torch.int32),
+                             _ptr(crd, torch.int32), _ptr(vals, torch.float32), _ptr(x, torch.float32),
+                             _ptr(y, torch.float32), int(cut), int(tile), int(phases), _ptr(ws), ws.numel(),
+                             _stream(stream))
+    _check(st, "psk_spmv_dcsr")
     return y
 
 

@@ -190,6 +190,42 @@ int psk_spmv_csr_f64(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos
     return hip_status(e);
 }
 
+int psk_spmv_dcsr(int64_t rows, int64_t cols, int64_t nstored, int64_t nnz, const int32_t *crd_i, const int32_t *pos,
+                  const int32_t *crd, const float *vals, const float *x, float *y, int cut, int32_t tile, int phases,
+                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (rows < 0 || rows > kMaxI32 || nstored < 0 || nstored > rows) return PSK_ERR_SIZE;
+    if (cut != PSK_CUT_POSITIONS && cut != PSK_CUT_ROWS) return PSK_ERR_UNSUPPORTED;
+    if (nstored > 0 && !crd_i) return PSK_ERR_NULL;
+    Workspace ws;
+    int st = check_common(PSK_OP_SPMV_CSR, nstored, cols, nnz, pos, crd, vals, 1, 1, &tile, phases, workspace,
+                          workspace_bytes, &ws);
+    if (st != PSK_OK) return st;
+    if ((rows > 0 && !y) || (nnz > 0 && !x)) return PSK_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int32_t ntiles = (int32_t)psk_num_tiles(nnz, tile);
+    hipError_t e = hipSuccess;
+    if (cut == PSK_CUT_ROWS) {
+        // tiles of four stored rows, one wave each: no row is divided, so there is no table and no carry
+        if (phases & PSK_PHASE_MAIN) {
+            e = launch_fill_zero(y, rows, s);
+            if (e == hipSuccess)
+                e = launch_spmv_rowsplit((int32_t)nstored, pos, crd, vals, x, y, PSK_ROWSPLIT_WAVE_PER_ROW, s, crd_i);
+        }
+        return hip_status(e);
+    }
+    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(nstored, nnz, pos, tile, 0, ws.tile_row, s);
+    if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
+        e = launch_fill_zero(y, rows, s);
+        if (ntiles > 0 && e == hipSuccess)
+            e = launch_spmv_csr_main((int32_t)nstored, (int32_t)cols, (int32_t)nnz, pos, crd, vals, x, y, tile, 1, ws, s,
+                                     crd_i);
+    }
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess && ntiles > 0)
+        e = launch_carry_fixup(ntiles, 1, 1, 1, tile, pos, ws, y, s, nullptr, crd_i);
+    return hip_status(e);
+}
+
 int psk_spmv_csr_atomics(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
                          const float *vals, const float *x, float *y, int32_t tile, int phases, void *workspace,
                          size_t workspace_bytes, void *stream)

@@ -48,9 +48,11 @@ hipError_t launch_carry_fixup(int32_t ntiles, int32_t nsub, int32_t k, int64_t l
 bool spmv_csr_tile_ok(int32_t tile);
 hipError_t launch_spmv_csr_main(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
                                 const float *vals, const float *x, float *y, int32_t tile, int32_t col_passes,
-                                const Workspace &w, hipStream_t s);
+                                const Workspace &w, hipStream_t s, const int32_t *rowmap = nullptr);
+// rowmap (optional, both launchers): row r of the hierarchy is row rowmap[r] of y (DCSR)
 hipError_t launch_spmv_rowsplit(int32_t rows, const int32_t *pos, const int32_t *crd, const float *vals,
-                                const float *x, float *y, int variant, hipStream_t s);
+                                const float *x, float *y, int variant, hipStream_t s,
+                                const int32_t *rowmap = nullptr);
 
 // CSR SpMV, fp64 operands (carry records are doubles: the workspace is carved with width 2)
 bool spmv_csr_f64_tile_ok(int32_t tile);

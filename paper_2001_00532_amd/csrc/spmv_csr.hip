@@ -60,6 +60,9 @@ __device__ __forceinline__ void run_select(const RunPlan &p, v4f_u wA, v4f_u wB,
 
 // VARIANT 0: one pass, carries.  1: a column pass (window [clo, chi), accum adds to earlier passes).
 // 2: one pass with the schedule's atomics instead of carries (baseline).
+// 4: one pass over a DCSR operand: `rows` counts the stored rows, row s of the hierarchy is row rowmap[s]
+//    of y (Section 3: the cut may be taken at any level of any coordinate hierarchy; y is zero-filled
+//    by the caller because rows that are not stored are written by nobody).
 // 3: one pass without the per-thread temporary and without the unrolled load loop (the ablation of
 //    Section 8.3): each thread walks its positions in a rolled loop, one load -> gather -> multiply -> LDS
 //    store after the other.
@@ -71,14 +74,14 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
                                                       const int *__restrict__ tile_row,
                                                       int *__restrict__ carry_row,
                                                       float *__restrict__ carry_val, int ntiles, int clo,
-                                                      int chi, int accum)
+                                                      int chi, int accum, const int *__restrict__ rowmap)
 {
     constexpr int T = THREADS * NPT;
     constexpr int NW = THREADS / WAVE;
     constexpr int LONG = 32;
     constexpr int MAXLONG = T / LONG;
     constexpr bool VEC = MODE != 0;
-    constexpr bool WIN = VARIANT == 1, ATOM = VARIANT == 2, NOTEMP = VARIANT == 3;
+    constexpr bool WIN = VARIANT == 1, ATOM = VARIANT == 2, NOTEMP = VARIANT == 3, ROWMAP = VARIANT == 4;
     static_assert(NPT % 4 == 0, "NPT must be a multiple of 4");
     __shared__ float sprod[skewed_size<1>(T)];
     __shared__ int slong[MAXLONG * 3];
@@ -214,6 +217,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
         if (has_carry && r == r0) {
             carry_row[t] = r;
             carry_val[t] = (WIN && accum) ? carry_val[t] + v : v;
+        } else if (ROWMAP) {
+            y[rowmap[r]] = v;
         } else {
             y[r] = (WIN && accum) ? y[r] + v : v;
         }
@@ -284,13 +289,14 @@ bool spmv_csr_tile_ok(int32_t tile)
 template <int THREADS, int NPT>
 static void launch_pos(int mode, int grid, hipStream_t s, int rows, int cols, int nnz, const int *pos, const int *crd,
                        const float *vals, const float *x, float *y, const Workspace &w, int ntiles, int clo, int chi,
-                       int accum)
+                       int accum, const int *rowmap)
 {
 #define PSK_GO(M, W)                                                                                             \
     hipLaunchKernelGGL((k_spmv_pos<THREADS, NPT, M, W>), dim3(grid), dim3(THREADS), 0, s, rows, cols, nnz, pos,  \
-                       crd, vals, x, y, w.tile_row, w.carry_row, w.carry_val, ntiles, clo, chi, accum)
-    const int variant = accum >= 2 ? accum : ((clo > 0 || chi < cols) ? 1 : 0);
+                       crd, vals, x, y, w.tile_row, w.carry_row, w.carry_val, ntiles, clo, chi, accum, rowmap)
+    const int variant = rowmap ? 4 : (accum >= 2 ? accum : ((clo > 0 || chi < cols) ? 1 : 0));
     if (variant == 3) PSK_GO(0, 3);
+    else if (variant == 4) { if (mode == 1) PSK_GO(1, 4); else PSK_GO(0, 4); }
     else if (mode == 1) { if (variant == 2) PSK_GO(1, 2); else if (variant == 1) PSK_GO(1, 1); else PSK_GO(1, 0); }
     else { if (variant == 2) PSK_GO(0, 2); else if (variant == 1) PSK_GO(0, 1); else PSK_GO(0, 0); }
 #undef PSK_GO
@@ -298,7 +304,7 @@ static void launch_pos(int mode, int grid, hipStream_t s, int rows, int cols, in
 
 hipError_t launch_spmv_csr_main(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
                                 const float *vals, const float *x, float *y, int32_t tile, int32_t col_passes,
-                                const Workspace &w, hipStream_t s)
+                                const Workspace &w, hipStream_t s, const int32_t *rowmap)
 {
     const int ntiles = (int)(((int64_t)nnz + tile - 1) / tile);
     if (ntiles == 0) return hipSuccess;
@@ -313,11 +319,11 @@ hipError_t launch_spmv_csr_main(int32_t rows, int32_t cols, int32_t nnz, const i
     const bool aligned = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
     const int vec = aligned ? 1 : 0;
     switch (tile) {
-        case 256:  launch_pos<64, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
-        case 512:  launch_pos<128, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
-        case 1024: launch_pos<256, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
-        case 2048: launch_pos<256, 8>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
-        case 4096: launch_pos<256, 16>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
+        case 256:  launch_pos<64, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap); break;
+        case 512:  launch_pos<128, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap); break;
+        case 1024: launch_pos<256, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap); break;
+        case 2048: launch_pos<256, 8>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap); break;
+        case 4096: launch_pos<256, 16>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap); break;
         default: return hipErrorInvalidValue;
     }
     }
@@ -347,7 +353,8 @@ __global__ __launch_bounds__(256) void k_spmv_wave_per_row(int rows, const int *
                                                            const int *__restrict__ crd,
                                                            const float *__restrict__ vals,
                                                            const float *__restrict__ x,
-                                                           float *__restrict__ y)
+                                                           float *__restrict__ y,
+                                                           const int *__restrict__ rowmap)
 {
     const int lane = threadIdx.x & (WAVE - 1);
     const int r = blockIdx.x * (256 / WAVE) + threadIdx.x / WAVE;
@@ -356,18 +363,19 @@ __global__ __launch_bounds__(256) void k_spmv_wave_per_row(int rows, const int *
     float s = 0.0f;
     for (int p = pos[r] + lane; p < pe; p += WAVE) s += vals[p] * x[crd[p]];
     s = wave_sum(s);
-    if (lane == 0) y[r] = s;
+    if (lane == 0) y[rowmap ? rowmap[r] : r] = s;
 }
 
 hipError_t launch_spmv_rowsplit(int32_t rows, const int32_t *pos, const int32_t *crd, const float *vals,
-                                const float *x, float *y, int variant, hipStream_t s)
+                                const float *x, float *y, int variant, hipStream_t s, const int32_t *rowmap)
 {
     if (rows == 0) return hipSuccess;
     if (variant == 0)
         hipLaunchKernelGGL(k_spmv_thread_per_row, dim3((rows + 255) / 256), dim3(256), 0, s, rows, pos, crd, vals, x,
                            y);
     else
-        hipLaunchKernelGGL(k_spmv_wave_per_row, dim3((rows + 3) / 4), dim3(256), 0, s, rows, pos, crd, vals, x, y);
+        hipLaunchKernelGGL(k_spmv_wave_per_row, dim3((rows + 3) / 4), dim3(256), 0, s, rows, pos, crd, vals, x, y,
+                           rowmap);
     return hipGetLastError();
 }
 
