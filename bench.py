@@ -316,6 +316,8 @@ def main():
                     help="column passes of the CSR SpMV (0 = ask psk_analyze_csr)")
     ap.add_argument("--skew-base", type=float, default=1.00256, help="base of the expskew workload")
     ap.add_argument("--copies", type=int, default=0, help="operand copies rotated between steps (0 = auto)")
+    ap.add_argument("--parts", type=int, action="append",
+                    help="--baselines: number of parts for the divided variant (repeatable; default 0 = 2048)")
     ap.add_argument("--cut", choices=["positions", "rows"], default="positions",
                     help="dcsr: level of the position cut (column level = equal nonzeros, row level = equal stored rows)")
     ap.add_argument("--f64", action="store_true", help="CSR SpMV workloads: fp64 values, vector and result")
@@ -537,6 +539,19 @@ def main():
             if i >= 4:
                 ts.append(e0.elapsed_time(e1))
         base["position_space_atomics_us_median"] = round(statistics.median(ts) * 1e3, 2)
+        for parts in (args.parts or [0]):     # the position space divided into a fixed number of parts
+            ts = []
+            for i in range(12):
+                s = sets[i % copies]
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                psk.psk_spmv_csr_divide(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"],
+                                        parts=parts, ws=s["ws"], stream=stream)
+                e1.record(stream)
+                e1.synchronize()
+                if i >= 4:
+                    ts.append(e0.elapsed_time(e1))
+            base["position_space_divided_parts_%d_us_median" % parts] = round(statistics.median(ts) * 1e3, 2)
         for name, phases in (("position_space_no_temporary_us_median", psk.PSK_PHASE_ALL),
                              ("position_space_no_temporary_main_us_median", psk.PSK_PHASE_MAIN)):
             ts = []

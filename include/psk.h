@@ -257,6 +257,20 @@ int psk_spmv_dcsr(int64_t rows, int64_t cols, int64_t nstored, int64_t nnz, cons
                   int cut, int32_t tile, int phases, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * y = A x, CSR, with the position space DIVIDED instead of split (Section 5 "Divide": the number of
+ * pieces is fixed, so the number of searches for a piece's first coordinate does not grow with the
+ * matrix).  `parts` persistent workgroups (0 = 2048; fewer when the matrix has fewer than that many
+ * chunks of 2048 positions), each of which finds its first row with one binary search inside the
+ * kernel, then walks its equal share of the positions chunk by chunk and tracks the rows (Section 6.2).
+ * No table and no partition step (PSK_PHASE_PARTITION does nothing); one carry record per part, added
+ * by the same fix-up as psk_spmv_csr.  Workspace: psk_workspace_bytes(PSK_OP_SPMV_CSR, rows, nnz, 1, 1,
+ * 2048) or more.  Same result bar as psk_spmv_csr; deterministic for a given `parts`.
+ */
+int psk_spmv_csr_divide(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                        const float *vals, const float *x, float *y, int32_t parts, int phases,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Baseline with the schedule's own race strategy (appendix "SPMV on a GPU": the thread level is
  * parallelised with OutputRaceStrategy::Atomics; Section 6.3, first strategy): same position cut and tile
  * kernel as psk_spmv_csr, but y is zero-filled first and the part of a row that other tiles also hold is

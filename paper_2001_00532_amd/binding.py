@@ -25,7 +25,7 @@ EXPORTS = [
     "psk_status_string", "psk_version", "psk_default_tile", "psk_num_tiles", "psk_workspace_bytes",
     "psk_partition_csr", "psk_analyze_csr", "psk_spmv_csr", "psk_spmm_csr", "psk_spmv_bcsr", "psk_spmm_bcsr",
     "psk_spmv_csr_rowsplit", "psk_spmm_csr_rowsplit", "psk_spmv_csr_atomics", "psk_mttkrp_csf3",
-    "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64", "psk_spmv_dcsr",
+    "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64", "psk_spmv_dcsr", "psk_spmv_csr_divide",
 ]
 
 
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.psk_spmv_csr_f64.restype = ci
         L.psk_spmv_dcsr.argtypes = [i64, i64, i64, i64, p, p, p, p, p, p, ci, i32, ci, p, sz, p]
         L.psk_spmv_dcsr.restype = ci
+        L.psk_spmv_csr_divide.argtypes = [i64, i64, i64, p, p, p, p, p, i32, ci, p, sz, p]
+        L.psk_spmv_csr_divide.restype = ci
         L.psk_spmv_csr_rowsplit.argtypes = [i64, i64, i64, p, p, p, p, p, ci, p]
         L.psk_spmv_csr_rowsplit.restype = ci
         L.psk_spmm_csr_rowsplit.argtypes = [i64, i64, i64, p, p, p, p, i32, i64, p, i64, p]
@@ -265,6 +267,16 @@ def psk_spmv_dcsr(rows, cols, nnz, crd_i, pos, crd, vals, x, y, cut=PSK_CUT_POSI
                              _ptr(y, torch.float32), int(cut), int(tile), int(phases), _ptr(ws), ws.numel(),
                              _stream(stream))
     _check(st, "psk_spmv_dcsr")
+    return y
+
+
+def psk_spmv_csr_divide(rows, cols, nnz, pos, crd, vals, x, y, parts=0, phases=PSK_PHASE_ALL, ws=None, stream=None):
+    if ws is None:
+        ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=2048, device=pos.device)
+    st = lib().psk_spmv_csr_divide(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
+                                   _ptr(vals, torch.float32), _ptr(x, torch.float32), _ptr(y, torch.float32),
+                                   int(parts), int(phases), _ptr(ws), ws.numel(), _stream(stream))
+    _check(st, "psk_spmv_csr_divide")
     return y
 
 

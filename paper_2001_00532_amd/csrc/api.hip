@@ -226,6 +226,32 @@ int psk_spmv_dcsr(int64_t rows, int64_t cols, int64_t nstored, int64_t nnz, cons
     return hip_status(e);
 }
 
+int psk_spmv_csr_divide(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                        const float *vals, const float *x, float *y, int32_t parts, int phases, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    if (parts < 0 || rows > kMaxI32 - 4096) return PSK_ERR_SIZE;
+    int32_t tile = kDivideChunk;
+    Workspace ws;
+    int st = check_common(PSK_OP_SPMV_CSR, rows, cols, nnz, pos, crd, vals, 1, 1, &tile, phases, workspace,
+                          workspace_bytes, &ws);
+    if (st != PSK_OK) return st;
+    if ((rows > 0 && !y) || (nnz > 0 && !x)) return PSK_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t nchunks = psk_num_tiles(nnz, tile);
+    if (parts == 0) parts = 2048;                       // eight resident workgroups on each of the 256 CUs
+    const int64_t cpp = nchunks == 0 ? 1 : (nchunks + parts - 1) / parts;
+    const int32_t nparts = (int32_t)((nchunks + cpp - 1) / cpp);
+    hipError_t e = hipSuccess;
+    if (phases & PSK_PHASE_MAIN) {
+        if (nparts == 0) e = launch_fill_zero(y, rows, s);
+        else e = launch_spmv_csr_divide((int32_t)rows, (int32_t)nnz, pos, crd, vals, x, y, nparts, (int32_t)cpp, ws, s);
+    }
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess && nparts > 1)
+        e = launch_carry_fixup(nparts, 1, 1, 1, (int32_t)(cpp * tile), pos, ws, y, s);
+    return hip_status(e);
+}
+
 int psk_spmv_csr_atomics(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
                          const float *vals, const float *x, float *y, int32_t tile, int phases, void *workspace,
                          size_t workspace_bytes, void *stream)
