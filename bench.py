@@ -315,6 +315,8 @@ def main():
     ap.add_argument("--col-passes", type=int, default=0,
                     help="column passes of the CSR SpMV (0 = ask psk_analyze_csr)")
     ap.add_argument("--skew-base", type=float, default=1.00256, help="base of the expskew workload")
+    ap.add_argument("--skew-rows", type=int, default=65536, help="rows of the expskew workload")
+    ap.add_argument("--skew-nnz", type=int, default=4_000_000, help="nonzeros of the expskew workload")
     ap.add_argument("--copies", type=int, default=0, help="operand copies rotated between steps (0 = auto)")
     ap.add_argument("--parts", type=int, action="append",
                     help="--baselines: number of parts for the divided variant (repeatable; default 0 = 2048)")
@@ -354,7 +356,7 @@ def main():
         Af = wl.csr_uniform(100, 100_000, 10_000, wl.BASE_SEED + 7)
         cfg = {"A": Af, "x": wl.dense_uniform(100_000, wl.BASE_SEED + 7, wl.S_X)}
     elif args.workload == "expskew":
-        Ls = wl.exponential_lengths(65536, 4_000_000, args.skew_base, 1_000_000, wl.BASE_SEED + 8)
+        Ls = wl.exponential_lengths(args.skew_rows, args.skew_nnz, args.skew_base, 1_000_000, wl.BASE_SEED + 8)
         Ae = wl.csr_from_lengths(Ls, 1_000_000, wl.BASE_SEED + 8)
         cfg = {"A": Ae, "x": wl.dense_uniform(1_000_000, wl.BASE_SEED + 8, wl.S_X)}
     else:

@@ -155,6 +155,20 @@ int psk_analyze_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos,
                     void *workspace, size_t workspace_bytes, int32_t *col_passes, void *stream);
 
 /*
+ * Which schedule for y = A x on this matrix: the position cut (psk_spmv_csr) or the row split with one
+ * wave per row (psk_spmv_csr_rowsplit)?  Section 8.4 shows that the answer depends on the skew of the
+ * row lengths.  Rule, from sweeps on MI355X: the row split only when the matrix is small
+ * (nnz <= 6 * 2^20, where the position path's partition and fix-up launches are a visible share), the
+ * mean row has at least 48 entries (a wave is mostly busy) and the longest row is at most 3.5 times the
+ * mean; otherwise the position cut.  `schedule` is a HOST pointer and receives PSK_SCHEDULE_*.
+ * Like psk_analyze_csr this call SYNCHRONISES `stream` when it has to look at pos (it reads the longest
+ * row back); `workspace` needs 256 bytes.
+ */
+enum { PSK_SCHEDULE_POSITIONS = 0, PSK_SCHEDULE_ROWS = 1 };
+int psk_suggest_schedule_csr(int64_t rows, int64_t nnz, const int32_t *pos, void *workspace,
+                             size_t workspace_bytes, int32_t *schedule, void *stream);
+
+/*
  * C = A B, CSR A, position-space schedule (appendix "SPMM on a GPU"): positions are
  * split over workgroups and waves, the columns of B over the lanes of a wave, the
  * loop over a wave's positions is innermost.  B is cols x k with row stride ldb

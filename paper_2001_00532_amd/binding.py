@@ -18,6 +18,7 @@ PSK_OK = 0
 PSK_OP_SPMV_CSR, PSK_OP_SPMM_CSR, PSK_OP_SPMV_BCSR, PSK_OP_SPMM_BCSR, PSK_OP_MTTKRP_CSF3 = 0, 1, 2, 3, 4
 PSK_OP_SPMV_CSR_F64 = 5
 PSK_CUT_POSITIONS, PSK_CUT_ROWS = 0, 1
+PSK_SCHEDULE_POSITIONS, PSK_SCHEDULE_ROWS = 0, 1
 PSK_PHASE_PARTITION, PSK_PHASE_MAIN, PSK_PHASE_FIXUP, PSK_PHASE_ALL = 1, 2, 4, 7
 PSK_ROWSPLIT_THREAD_PER_ROW, PSK_ROWSPLIT_WAVE_PER_ROW = 0, 1
 
@@ -25,7 +26,7 @@ EXPORTS = [
     "psk_status_string", "psk_version", "psk_default_tile", "psk_num_tiles", "psk_workspace_bytes",
     "psk_partition_csr", "psk_analyze_csr", "psk_spmv_csr", "psk_spmm_csr", "psk_spmv_bcsr", "psk_spmm_bcsr",
     "psk_spmv_csr_rowsplit", "psk_spmm_csr_rowsplit", "psk_spmv_csr_atomics", "psk_mttkrp_csf3",
-    "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64", "psk_spmv_dcsr", "psk_spmv_csr_divide",
+    "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64", "psk_spmv_dcsr", "psk_spmv_csr_divide", "psk_suggest_schedule_csr",
 ]
 
 
@@ -75,6 +76,8 @@ def lib() -> ctypes.CDLL:
         L.psk_spmv_csr_f64.restype = ci
         L.psk_spmv_dcsr.argtypes = [i64, i64, i64, i64, p, p, p, p, p, p, ci, i32, ci, p, sz, p]
         L.psk_spmv_dcsr.restype = ci
+        L.psk_suggest_schedule_csr.argtypes = [i64, i64, p, p, sz, p, p]
+        L.psk_suggest_schedule_csr.restype = ci
         L.psk_spmv_csr_divide.argtypes = [i64, i64, i64, p, p, p, p, p, i32, ci, p, sz, p]
         L.psk_spmv_csr_divide.restype = ci
         L.psk_spmv_csr_rowsplit.argtypes = [i64, i64, i64, p, p, p, p, p, ci, p]
@@ -159,6 +162,17 @@ def psk_analyze_csr(rows, cols, nnz, pos, crd, ws=None, stream=None) -> int:
     st = lib().psk_analyze_csr(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                                _ptr(ws), ws.numel(), ctypes.byref(out), _stream(stream))
     _check(st, "psk_analyze_csr")
+    return int(out.value)
+
+
+def psk_suggest_schedule_csr(rows, nnz, pos, ws=None, stream=None) -> int:
+    """PSK_SCHEDULE_POSITIONS or PSK_SCHEDULE_ROWS for y = A x on this matrix (may synchronise the stream)."""
+    if ws is None:
+        ws = torch.empty(256, dtype=torch.uint8, device=pos.device)
+    out = ctypes.c_int32(-1)
+    st = lib().psk_suggest_schedule_csr(int(rows), int(nnz), _ptr(pos, torch.int32), _ptr(ws), ws.numel(),
+                                        ctypes.byref(out), _stream(stream))
+    _check(st, "psk_suggest_schedule_csr")
     return int(out.value)
 
 

@@ -144,6 +144,26 @@ int psk_analyze_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos,
     return PSK_OK;
 }
 
+int psk_suggest_schedule_csr(int64_t rows, int64_t nnz, const int32_t *pos, void *workspace, size_t workspace_bytes,
+                             int32_t *schedule, void *stream)
+{
+    if (rows < 0 || nnz < 0 || nnz > kMaxI32 || rows > kMaxI32 - 1) return PSK_ERR_SIZE;
+    if (!schedule || !pos) return PSK_ERR_NULL;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < 256) return PSK_ERR_WORKSPACE;
+    *schedule = PSK_SCHEDULE_POSITIONS;
+    // Row-split can only win where the two extra launches of the position path are a visible share of
+    // the time (small problems) and the rows fill a wave (long enough, and alike).
+    if (rows == 0 || nnz > (int64_t(6) << 20) || nnz < 48 * rows) return PSK_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t *dev = static_cast<int32_t *>(workspace);
+    int32_t longest = 0;
+    if (launch_max_row((int32_t)rows, pos, dev, s) != hipSuccess) return PSK_ERR_HIP;
+    if (hipMemcpyAsync(&longest, dev, sizeof(longest), hipMemcpyDeviceToHost, s) != hipSuccess) return PSK_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return PSK_ERR_HIP;
+    if (2 * (int64_t)longest * rows <= 7 * nnz) *schedule = PSK_SCHEDULE_ROWS;   // longest <= 3.5 x mean
+    return PSK_OK;
+}
+
 int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
                  const float *vals, const float *x, float *y, int32_t tile, int32_t col_passes, int phases,
                  void *workspace, size_t workspace_bytes, void *stream)

@@ -126,6 +126,32 @@ hipError_t launch_probe_locality(int32_t nnz, const int32_t *crd, int32_t *resul
     return hipGetLastError();
 }
 
+// Longest row: result[0] = max_i (pos[i+1] - pos[i]); result must hold 0 before the launch.
+__global__ __launch_bounds__(256) void k_max_row(int rows, const int *__restrict__ pos, int *__restrict__ result)
+{
+    int m = 0;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < rows; i += (long long)gridDim.x * blockDim.x) {
+        const int len = pos[i + 1] - pos[i];
+        m = len > m ? len : m;
+    }
+#pragma unroll
+    for (int k = 1; k < WAVE; k <<= 1) {
+        const int o = __shfl_xor(m, k, WAVE);
+        m = o > m ? o : m;
+    }
+    if ((threadIdx.x & (WAVE - 1)) == 0 && m > 0) atomicMax(result, m);
+}
+
+hipError_t launch_max_row(int32_t rows, const int32_t *pos, int32_t *result, hipStream_t s)
+{
+    hipError_t e = launch_fill_zero(reinterpret_cast<float *>(result), 1, s);   // +0.0f is the integer 0
+    if (e != hipSuccess || rows <= 0) return e;
+    int64_t blocks = ((int64_t)rows + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(k_max_row, dim3((unsigned)blocks), dim3(256), 0, s, rows, pos, result);
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void k_fill_zero(float *__restrict__ p, long long n)
 {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;

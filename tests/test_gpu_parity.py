@@ -317,6 +317,26 @@ def test_analyze_small_problems_need_no_passes():
     assert psk.psk_analyze_csr(A.rows, A.cols, A.nnz, D.pos, D.crd) == 1
 
 
+def test_suggest_schedule_follows_its_rule():
+    """Row split only for small matrices with long, alike rows; the position cut otherwise."""
+    def ask(lengths):
+        pos = np.zeros(len(lengths) + 1, dtype=np.int32)
+        pos[1:] = np.cumsum(lengths)
+        return psk.psk_suggest_schedule_csr(len(lengths), int(pos[-1]), dev(pos))
+
+    assert ask(np.full(65536, 61)) == psk.PSK_SCHEDULE_ROWS
+    assert ask(np.full(4096, 977)) == psk.PSK_SCHEDULE_ROWS
+    assert ask(np.full(262144, 15)) == psk.PSK_SCHEDULE_POSITIONS           # short rows
+    assert ask(np.full(262144, 61)) == psk.PSK_SCHEDULE_POSITIONS           # 16 M nonzeros: not small
+    skew = np.full(16384, 244)
+    skew[7] = 244 * 4
+    assert ask(skew) == psk.PSK_SCHEDULE_POSITIONS                          # one row 4 x the mean
+    skew[7] = 244 * 3
+    assert ask(skew) == psk.PSK_SCHEDULE_ROWS
+    assert ask(np.diff(wl.config(2, 0.02)["A"].pos)) == psk.PSK_SCHEDULE_POSITIONS
+    assert ask(np.zeros(0, dtype=np.int64)) == psk.PSK_SCHEDULE_POSITIONS
+
+
 # ------------------------------------------------------------------ the schedule's atomics strategy (baseline)
 def test_spmv_atomics_baseline():
     rng = np.random.default_rng(8)
