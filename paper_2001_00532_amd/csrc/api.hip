@@ -331,8 +331,7 @@ int psk_spmm_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
     if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, 0, ws.tile_row, s);
     if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
         if (ntiles == 0) {
-            if (ldc == k) e = launch_fill_zero(C, rows * (int64_t)k, s);
-            else for (int64_t r = 0; r < rows && e == hipSuccess; ++r) e = launch_fill_zero(C + r * ldc, k, s);
+            e = launch_fill_zero_2d(C, rows, k, ldc, s);
         } else {
             e = launch_spmm_csr_main((int32_t)rows, (int32_t)nnz, pos, crd, vals, B, k, ldb, C, ldc, tile, ws, s);
         }
@@ -384,8 +383,7 @@ int psk_spmm_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, con
     if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(brows, nblocks, pos, tile, 0, ws.tile_row, s);
     if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
         if (ntiles == 0) {
-            if (ldc == k) e = launch_fill_zero(C, brows * bs * (int64_t)k, s);
-            else for (int64_t r = 0; r < brows * bs && e == hipSuccess; ++r) e = launch_fill_zero(C + r * ldc, k, s);
+            e = launch_fill_zero_2d(C, brows * bs, k, ldc, s);
         } else {
             e = launch_spmm_bcsr4_main((int32_t)brows, (int32_t)nblocks, pos, crd, vals, B, k, ldb, C, ldc, tile, ws, s);
         }
@@ -429,10 +427,7 @@ int psk_mttkrp_csf3(int64_t dim_i, int64_t dim_k, int64_t dim_l, int64_t nslices
                                   ws.tile_aux, s);
     if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
         // a compressed first level leaves rows of A without a slice: clear them all first; so does nnz = 0
-        if (crd_i || ntiles == 0) {
-            if (lda == j) e = launch_fill_zero(A, dim_i * (int64_t)j, s);
-            else for (int64_t r = 0; r < dim_i && e == hipSuccess; ++r) e = launch_fill_zero(A + r * lda, j, s);
-        }
+        if (crd_i || ntiles == 0) e = launch_fill_zero_2d(A, dim_i, j, lda, s);
         if (ntiles > 0 && e == hipSuccess)
             e = launch_mttkrp_main((int32_t)nslices, (int32_t)nnz, crd_i, pos_k, crd_k, pos_l, crd_l, vals, C, ldc, D,
                                    ldd, j, A, lda, tile, ws, ws.tile_aux, s);

@@ -168,6 +168,25 @@ hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s)
     return hipGetLastError();
 }
 
+__global__ __launch_bounds__(256) void k_fill_zero_2d(float *__restrict__ p, long long rows, int width, long long ld)
+{
+    const long long n = rows * width;
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[(i / width) * ld + i % width] = 0.0f;
+}
+
+// rows x width block of a row-major array with leading dimension ld
+hipError_t launch_fill_zero_2d(float *p, int64_t rows, int32_t width, int64_t ld, hipStream_t s)
+{
+    if (ld == width) return launch_fill_zero(p, rows * width, s);
+    if (rows <= 0 || width <= 0) return hipSuccess;
+    int64_t blocks = (rows * width + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(k_fill_zero_2d, dim3((unsigned)blocks), dim3(256), 0, s, p, (long long)rows, width, (long long)ld);
+    return hipGetLastError();
+}
+
 // Carry fix-up.  Tile t left carry_row[t] = r >= 0 when its first positions belong to a row r that
 // began in an earlier tile, together with `width` partial sums.  The records of one row sit in
 // consecutive tiles: from the tile after the one holding pos[r] to the tile holding the row's last

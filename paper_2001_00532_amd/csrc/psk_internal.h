@@ -35,6 +35,7 @@ inline Workspace carve(void *base, int64_t ntiles, int64_t width)
 hipError_t launch_partition(int64_t rows, int64_t nnz, const int32_t *pos, int32_t tile, int method,
                             int32_t *tile_row, hipStream_t s);
 hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s);
+hipError_t launch_fill_zero_2d(float *p, int64_t rows, int32_t width, int64_t ld, hipStream_t s);
 hipError_t launch_max_row(int32_t rows, const int32_t *pos, int32_t *result, hipStream_t s);
 hipError_t launch_probe_locality(int32_t nnz, const int32_t *crd, int32_t *result, hipStream_t s);
 // Adds the per-tile carry records to the output: element e of a record of `nsub*k` floats goes to

@@ -30,7 +30,7 @@ def test_sizes_and_strings():
     assert psk.psk_num_tiles(0, 1024) == 0 and psk.psk_num_tiles(1, 1024) == 1
     assert psk.psk_num_tiles(1024, 1024) == 1 and psk.psk_num_tiles(1025, 1024) == 2
     assert psk.psk_num_tiles(10, 0) == -1
-    for op in range(4):
+    for op in range(6):
         assert psk.psk_default_tile(op) > 0
     assert psk.psk_default_tile(9) == -1
     w = psk.psk_workspace_bytes(psk.PSK_OP_SPMV_CSR, 100, 10_000, tile=1024)
@@ -38,6 +38,10 @@ def test_sizes_and_strings():
     assert psk.psk_workspace_bytes(psk.PSK_OP_SPMM_CSR, 100, 10_000, k=128, tile=1024) > w
     assert psk.psk_workspace_bytes(psk.PSK_OP_SPMM_CSR, 100, 10_000, k=0, tile=1024) == 0
     assert psk.psk_workspace_bytes(7, 100, 10_000) == 0
+    # fp64 carries are doubles: twice the record space of the fp32 SpMV
+    assert psk.psk_workspace_bytes(psk.PSK_OP_SPMV_CSR_F64, 100, 10_000_000, tile=1024) > \
+        psk.psk_workspace_bytes(psk.PSK_OP_SPMV_CSR, 100, 10_000_000, tile=1024)
+    assert psk.psk_workspace_bytes(psk.PSK_OP_MTTKRP_CSF3, 100, 10_000, k=64) > w
     assert psk.psk_workspace_bytes(psk.PSK_OP_SPMV_CSR, 0, 0) >= 256
     assert psk.status_string(0) == "ok" and "tile" in psk.status_string(3)
     assert psk.status_string(99) == "unknown status"
@@ -81,6 +85,26 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.psk_analyze_csr(4, 4, 4, one, one, null, 0, ctypes.byref(out), null) == 4
     assert L.psk_analyze_csr(4, 4, 4, one, one, one, 256, None, null) == 1
     assert L.psk_analyze_csr(4, 4, 4, one, one, one, 256, ctypes.byref(out), null) == 0 and out.value == 1   # small: no launch
+    # the widened entry points: MTTKRP, fp64, DCSR, divided, ablations, selector
+    assert L.psk_mttkrp_csf3(4, 4, 4, 4, 4, 4, null, null, one, one, one, one, one, 8, one, 8, 8, one, 8, 0, 7, one, big, null) == 1
+    assert L.psk_mttkrp_csf3(4, 4, 4, 4, 4, 4, null, one, one, one, one, one, one, 8, one, 8, 0, one, 8, 0, 7, one, big, null) == 2   # j = 0
+    assert L.psk_mttkrp_csf3(4, 4, 4, 4, 4, 4, null, one, one, one, one, one, one, 4, one, 8, 8, one, 8, 0, 7, one, big, null) == 2   # ldc < j
+    assert L.psk_mttkrp_csf3(4, 4, 4, 4, 4, 4, null, one, one, one, one, one, one, 8, one, 8, 8, one, 8, 100, 7, one, big, null) == 3
+    assert L.psk_partition_csf3(4, 4, 4, null, one, 4, one, one, null) == 1
+    assert L.psk_partition_csf3(4, 4, 4, one, one, 0, one, one, null) == 3
+    assert L.psk_spmv_csr_f64(4, 4, 4, one, one, one, one, null, 0, 7, one, big, null) == 1
+    assert L.psk_spmv_csr_f64(4, 4, 4, one, one, ctypes.c_void_p(260), one, one, 0, 7, one, big, null) == 7
+    assert L.psk_spmv_csr_f64(4, 4, 4, one, one, one, one, one, 4096, 7, one, big, null) == 3
+    assert L.psk_spmv_dcsr(8, 4, 9, 4, one, one, one, one, one, one, 0, 0, 7, one, big, null) == 2      # nstored > rows
+    assert L.psk_spmv_dcsr(8, 4, 2, 4, null, one, one, one, one, one, 0, 0, 7, one, big, null) == 1
+    assert L.psk_spmv_dcsr(8, 4, 2, 4, one, one, one, one, one, one, 2, 0, 7, one, big, null) == 5      # cut
+    assert L.psk_spmv_csr_divide(4, 4, 4, one, one, one, one, one, -1, 7, one, big, null) == 2
+    assert L.psk_spmv_csr_divide(4, 4, 4, one, one, one, one, one, 0, 7, null, big, null) == 4
+    assert L.psk_spmv_csr_notemp(4, 4, 4, one, one, one, one, one, 100, 7, one, big, null) == 3
+    assert L.psk_spmv_csr_atomics(4, 4, 4, one, one, null, one, one, 0, 7, one, big, null) == 1
+    assert L.psk_suggest_schedule_csr(4, 4, one, one, 256, None, null) == 1
+    assert L.psk_suggest_schedule_csr(4, 4, one, null, 0, ctypes.byref(out), null) == 4
+    assert L.psk_suggest_schedule_csr(4, 4, one, one, 256, ctypes.byref(out), null) == 0 and out.value == 0  # short rows: no launch
     # ALIGNMENT (BCSR)
     assert L.psk_spmv_bcsr(4, 4, 4, 4, one, one, ctypes.c_void_p(260), one, one, 0, 7, one, big, null) == 7
 

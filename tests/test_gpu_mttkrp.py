@@ -92,6 +92,25 @@ def test_mttkrp_any_rank_and_strides(j):
     run_case("powerlaw strided", T, j, 1024, ld_extra=4)
 
 
+def test_mttkrp_strided_output_with_rows_that_have_no_slice():
+    """Rows of A without a slice (compressed first level) and empty tensors are cleared inside the row
+    stride only: the padding columns keep what they held."""
+    for name, fps, lpf, dims, ci in tensors():
+        if name not in ("compressed_i", "all_empty"):
+            continue
+        T = wl.csf3_from_lengths(fps, lpf, dims, seed=35, compressed_i=ci)
+        say("mttkrp strided", name)
+        run_case(name, T, 48, 512, ld_extra=16)
+        I = T.dims[0]
+        Afull = torch.full((I, 64), 5.0, device="cuda")
+        C = dev(wl.dense_uniform(T.dims[1] * 48, 7, wl.S_B).reshape(-1, 48))
+        D = dev(wl.dense_uniform(T.dims[2] * 48, 8, wl.S_B).reshape(-1, 48))
+        psk.psk_mttkrp_csf3(T.dims, dev(T.crd_i), dev(T.pos_k), dev(T.crd_k), dev(T.pos_l), dev(T.crd_l), dev(T.vals),
+                            C, D, Afull[:, :48])
+        torch.cuda.synchronize()
+        assert torch.all(Afull[:, 48:] == 5.0)
+
+
 def test_mttkrp_deterministic_and_partition_reuse():
     T = wl.csf3_powerlaw(3000, 700, 900, 5, 1.7, 500, seed=45)
     I, K, L = T.dims
