@@ -82,11 +82,12 @@ def algorithmic_bytes(kind, A, k):
         a = 8 * nnz + 4 * (rows + 1)
         return a + 4 * k * cols + 4 * k * rows, a + 4 * k * nnz + 4 * k * rows
     if kind == "bcsr_spmv":
-        b = 68 * nnz + 4 * (rows + 1) + 16 * cols + 16 * rows
+        b = (4 * A.bs * A.bs + 4) * nnz + 4 * (rows + 1) + 4 * A.bs * cols + 4 * A.bs * rows
         return b, b
     if kind == "bcsr_spmm":
-        a = 68 * nnz + 4 * (rows + 1)
-        return a + 16 * k * cols + 16 * k * rows, a + 16 * k * nnz + 16 * k * rows
+        a = (4 * A.bs * A.bs + 4) * nnz + 4 * (rows + 1)
+        w = 4 * A.bs * k
+        return a + w * cols + w * rows, a + w * nnz + w * rows
     raise ValueError(kind)
 
 
@@ -322,6 +323,8 @@ def main():
                     help="--baselines: number of parts for the divided variant (repeatable; default 0 = 2048)")
     ap.add_argument("--cut", choices=["positions", "rows"], default="positions",
                     help="dcsr: level of the position cut (column level = equal nonzeros, row level = equal stored rows)")
+    ap.add_argument("--bs", type=int, default=4, choices=[2, 4, 8],
+                    help="bcsr_spmv / bcsr_spmm: block edge (the 10^6 x 10^6 matrix with 32 entries per row is re-blocked)")
     ap.add_argument("--f64", action="store_true", help="CSR SpMV workloads: fp64 values, vector and result")
     ap.add_argument("--rank", type=int, default=64, help="mttkrp: number of columns j of the factor matrices")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
@@ -359,6 +362,11 @@ def main():
         Ls = wl.exponential_lengths(args.skew_rows, args.skew_nnz, args.skew_base, 1_000_000, wl.BASE_SEED + 8)
         Ae = wl.csr_from_lengths(Ls, 1_000_000, wl.BASE_SEED + 8)
         cfg = {"A": Ae, "x": wl.dense_uniform(1_000_000, wl.BASE_SEED + 8, wl.S_X)}
+    elif kind.startswith("bcsr") and args.bs != 4:
+        br = 1_000_000 // args.bs
+        Ab = wl.csr_uniform(br, br, 32 // args.bs, wl.BASE_SEED + 5, bs=args.bs)
+        cfg = {"A": Ab, "k": 64, "x": wl.dense_uniform(br * args.bs, wl.BASE_SEED + 5, wl.S_X),
+               "B": wl.dense_uniform(br * args.bs * 64, wl.BASE_SEED + 5, wl.S_B).reshape(br * args.bs, 64)}
     else:
         cfg = wl.config(cfg_no)
     A = cfg["A"]
@@ -384,7 +392,7 @@ def main():
           "bcsr_spmm": psk.PSK_OP_SPMM_BCSR}[kind]
     if f64:
         op = psk.PSK_OP_SPMV_CSR_F64
-    tile = args.tile or psk.psk_default_tile(op)
+    tile = args.tile or (psk.psk_default_tile_bcsr(op, A.bs) if kind.startswith("bcsr") else psk.psk_default_tile(op))
     tile_given = bool(args.tile)
 
     # rotate over enough operand copies that a step never finds its inputs in the 256 MB memory-side cache
@@ -420,10 +428,10 @@ def main():
             psk.psk_spmm_csr(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"], tile=tile,
                              phases=phases, ws=s["ws"], stream=stream)
         elif kind == "bcsr_spmv":
-            psk.psk_spmv_bcsr(A.rows, A.cols, A.nnz, 4, s["pos"], s["crd"], s["vals"], s["dense"], s["out"],
+            psk.psk_spmv_bcsr(A.rows, A.cols, A.nnz, A.bs, s["pos"], s["crd"], s["vals"], s["dense"], s["out"],
                               tile=tile, phases=phases, ws=s["ws"], stream=stream)
         else:
-            psk.psk_spmm_bcsr(A.rows, A.cols, A.nnz, 4, s["pos"], s["crd"], s["vals"], s["dense"], s["out"],
+            psk.psk_spmm_bcsr(A.rows, A.cols, A.nnz, A.bs, s["pos"], s["crd"], s["vals"], s["dense"], s["out"],
                               tile=tile, phases=phases, ws=s["ws"], stream=stream)
 
     # ---- warm-up, then exactly K timed steps bracketed by synchronize
@@ -480,7 +488,7 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": "%s: %s, %d x %d%s, nnz %d (max row %d, mean %.2f), tile %d, col_passes %d, k %d, %d operand copies rotated"
-                        % (args.workload, kind, A.rows * A.bs, A.cols * A.bs, " in 4x4 blocks" if A.bs > 1 else "",
+                        % (args.workload, kind, A.rows * A.bs, A.cols * A.bs, " in %dx%d blocks" % (A.bs, A.bs) if A.bs > 1 else "",
                            A.nnz * A.bs * A.bs, int(L.max()) if L.size else 0, float(L.mean()) if L.size else 0.0,
                            tile, col_passes, k, copies),
             "rows": A.rows * A.bs, "cols": A.cols * A.bs, "nnz": A.nnz * A.bs * A.bs, "k": k, "tile": tile,
@@ -593,9 +601,9 @@ def main():
             elif kind == "csr_spmm":
                 oracle.spmm_csr(A.pos, A.crd, A.vals, dense_h, sel=sel, threads=cores)
             elif kind == "bcsr_spmv":
-                oracle.spmv_bcsr(A.pos, A.crd, A.vals, dense_h, 4, threads=cores)
+                oracle.spmv_bcsr(A.pos, A.crd, A.vals, dense_h, A.bs, threads=cores)
             else:
-                oracle.spmm_bcsr(A.pos, A.crd, A.vals, dense_h, 4, sel=sel, threads=cores)
+                oracle.spmm_bcsr(A.pos, A.crd, A.vals, dense_h, A.bs, sel=sel, threads=cores)
 
         run_oracle()
         ts = []

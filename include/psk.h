@@ -94,6 +94,8 @@ int psk_version(void);
 /* Default position-tile size of an operation (what tile = 0 selects); -1 for an unknown op.
  * For the BCSR operations the unit is blocks. */
 int32_t psk_default_tile(int op);
+/* The same for a BCSR operation with block edge bs (the SpMV tile sets differ with bs); -1 if unsupported. */
+int32_t psk_default_tile_bcsr(int op, int32_t bs);
 
 /* ceil(nnz / tile): number of tiles of the position cut; 0 when nnz <= 0; -1 when tile <= 0. */
 int64_t psk_num_tiles(int64_t nnz, int32_t tile);
@@ -183,14 +185,16 @@ int psk_spmm_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
  * BCSR (Section 1): brows x bcols blocks of bs x bs floats, nblocks stored blocks;
  * pos/crd index blocks; the position cut is taken at the block level (Section 3:
  * a cut may be placed at any level of the hierarchy), `tile` counts blocks.
- * x has bcols*bs entries, y brows*bs.  bs = 4 only (other sizes: PSK_ERR_UNSUPPORTED).
- * vals and x must be 16-byte aligned.  tile in {0, 64, 128, 256, 512}.
+ * x has bcols*bs entries, y brows*bs.  bs in {2, 4, 8} (other sizes: PSK_ERR_UNSUPPORTED).
+ * vals must be 16-byte aligned, x 16-byte (bs = 2: 8-byte) aligned.
+ * tile (0 = default): bs = 4: {64, 128, 256, 512}, default 512; bs = 2: {512, 1024, 2048}, default 1024;
+ * bs = 8: {32, 64, 128}, default 64.  Workspace: psk_workspace_bytes(PSK_OP_SPMV_BCSR, brows, nblocks, 1, bs, tile).
  */
 int psk_spmv_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, const int32_t *pos,
                   const int32_t *crd, const float *vals, const float *x, float *y, int32_t tile,
                   int phases, void *workspace, size_t workspace_bytes, void *stream);
 
-/* C = A B with BCSR A: B is (bcols*bs) x k, C is (brows*bs) x k.  bs = 4 only.
+/* C = A B with BCSR A: B is (bcols*bs) x k, C is (brows*bs) x k.  bs in {2, 4, 8}.
  * vals must be 16-byte aligned.  tile in {0, 64, 128, 256, 512}. */
 int psk_spmm_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, const int32_t *pos,
                   const int32_t *crd, const float *vals, const float *B, int32_t k, int64_t ldb,

@@ -26,7 +26,7 @@ EXPORTS = [
     "psk_status_string", "psk_version", "psk_default_tile", "psk_num_tiles", "psk_workspace_bytes",
     "psk_partition_csr", "psk_analyze_csr", "psk_spmv_csr", "psk_spmm_csr", "psk_spmv_bcsr", "psk_spmm_bcsr",
     "psk_spmv_csr_rowsplit", "psk_spmm_csr_rowsplit", "psk_spmv_csr_atomics", "psk_mttkrp_csf3",
-    "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64", "psk_spmv_dcsr", "psk_spmv_csr_divide", "psk_suggest_schedule_csr",
+    "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64", "psk_spmv_dcsr", "psk_spmv_csr_divide", "psk_suggest_schedule_csr", "psk_default_tile_bcsr",
 ]
 
 
@@ -76,6 +76,8 @@ def lib() -> ctypes.CDLL:
         L.psk_spmv_csr_f64.restype = ci
         L.psk_spmv_dcsr.argtypes = [i64, i64, i64, i64, p, p, p, p, p, p, ci, i32, ci, p, sz, p]
         L.psk_spmv_dcsr.restype = ci
+        L.psk_default_tile_bcsr.argtypes = [ci, i32]
+        L.psk_default_tile_bcsr.restype = i32
         L.psk_suggest_schedule_csr.argtypes = [i64, i64, p, p, sz, p, p]
         L.psk_suggest_schedule_csr.restype = ci
         L.psk_spmv_csr_divide.argtypes = [i64, i64, i64, p, p, p, p, p, i32, ci, p, sz, p]
@@ -121,6 +123,10 @@ def psk_version() -> int:
 
 def psk_default_tile(op: int) -> int:
     return int(lib().psk_default_tile(int(op)))
+
+
+def psk_default_tile_bcsr(op: int, bs: int) -> int:
+    return int(lib().psk_default_tile_bcsr(int(op), int(bs)))
 
 
 def psk_num_tiles(nnz: int, tile: int) -> int:

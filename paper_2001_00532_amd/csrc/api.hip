@@ -8,8 +8,10 @@ namespace {
 
 constexpr int64_t kMaxI32 = 2147483647ll;
 
-int32_t default_tile(int op)
+int32_t default_tile(int op, int32_t bs = 4)
 {
+    if (op == PSK_OP_SPMV_BCSR && bs == 2) return 1024;
+    if (op == PSK_OP_SPMV_BCSR && bs == 8) return 64;
     switch (op) {
         case PSK_OP_SPMV_CSR: return 2048;
         case PSK_OP_SPMM_CSR: return 512;
@@ -21,8 +23,9 @@ int32_t default_tile(int op)
     }
 }
 
-bool tile_ok(int op, int32_t tile)
+bool tile_ok(int op, int32_t tile, int32_t bs = 4)
 {
+    if (op == PSK_OP_SPMV_BCSR && bs != 4) return bcsr_g_tile_ok(bs, tile);
     switch (op) {
         case PSK_OP_SPMV_CSR: return spmv_csr_tile_ok(tile);
         case PSK_OP_SPMM_CSR: return spmm_csr_tile_ok(tile);
@@ -58,8 +61,8 @@ int check_common(int op, int64_t rows, int64_t cols, int64_t nnz, const void *po
     if (!pos) return PSK_ERR_NULL;
     if (nnz > 0 && (!crd || !vals)) return PSK_ERR_NULL;
     if (phases <= 0 || (phases & ~PSK_PHASE_ALL)) return PSK_ERR_UNSUPPORTED;
-    if (*tile == 0) *tile = default_tile(op);
-    if (!tile_ok(op, *tile)) return PSK_ERR_TILE;
+    if (*tile == 0) *tile = default_tile(op, bs);
+    if (!tile_ok(op, *tile, bs)) return PSK_ERR_TILE;
     const size_t need = psk_workspace_bytes(op, rows, nnz, k, bs, *tile);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < need) return PSK_ERR_WORKSPACE;
     const int64_t ntiles = psk_num_tiles(nnz, *tile);
@@ -92,6 +95,12 @@ int psk_version(void) { return 100; }
 
 int32_t psk_default_tile(int op) { return default_tile(op); }
 
+int32_t psk_default_tile_bcsr(int op, int32_t bs)
+{
+    if ((op != PSK_OP_SPMV_BCSR && op != PSK_OP_SPMM_BCSR) || (bs != 2 && bs != 4 && bs != 8)) return -1;
+    return default_tile(op, bs);
+}
+
 int64_t psk_num_tiles(int64_t nnz, int32_t tile)
 {
     if (tile <= 0) return -1;
@@ -102,7 +111,7 @@ size_t psk_workspace_bytes(int op, int64_t rows, int64_t nnz, int32_t k, int32_t
 {
     (void)rows;
     // CSR SpMV picks 2048, or 1024 with column passes: size for the smaller one, which needs more
-    if (tile == 0) tile = op == PSK_OP_SPMV_CSR ? 1024 : default_tile(op);
+    if (tile == 0) tile = op == PSK_OP_SPMV_CSR ? 1024 : default_tile(op, bs);
     if (tile <= 0 || nnz < 0 || nnz > kMaxI32) return 0;
     if ((op == PSK_OP_SPMM_CSR || op == PSK_OP_SPMM_BCSR || op == PSK_OP_MTTKRP_CSF3) && k <= 0) return 0;
     if ((op == PSK_OP_SPMV_BCSR || op == PSK_OP_SPMM_BCSR) && bs <= 0) return 0;
@@ -344,21 +353,23 @@ int psk_spmv_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, con
                   const int32_t *crd, const float *vals, const float *x, float *y, int32_t tile, int phases,
                   void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (bs != 4) return bs <= 0 ? PSK_ERR_SIZE : PSK_ERR_UNSUPPORTED;
+    if (bs != 2 && bs != 4 && bs != 8) return bs <= 0 ? PSK_ERR_SIZE : PSK_ERR_UNSUPPORTED;
     if (brows > (kMaxI32 - 1) / bs || bcols > kMaxI32 / bs || nblocks > kMaxI32 / (bs * bs)) return PSK_ERR_SIZE;
     Workspace ws;
     int st = check_common(PSK_OP_SPMV_BCSR, brows, bcols, nblocks, pos, crd, vals, 1, bs, &tile, phases,
                           workspace, workspace_bytes, &ws);
     if (st != PSK_OK) return st;
     if ((brows > 0 && !y) || (nblocks > 0 && !x)) return PSK_ERR_NULL;
-    if ((reinterpret_cast<uintptr_t>(vals) | reinterpret_cast<uintptr_t>(x)) & 15) return PSK_ERR_ALIGNMENT;
+    if ((reinterpret_cast<uintptr_t>(vals) & 15) || (reinterpret_cast<uintptr_t>(x) & (bs == 2 ? 7 : 15)))
+        return PSK_ERR_ALIGNMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int32_t ntiles = (int32_t)psk_num_tiles(nblocks, tile);
     hipError_t e = hipSuccess;
     if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(brows, nblocks, pos, tile, 0, ws.tile_row, s);
     if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
         if (ntiles == 0) e = launch_fill_zero(y, brows * bs, s);
-        else e = launch_spmv_bcsr4_main((int32_t)brows, (int32_t)nblocks, pos, crd, vals, x, y, tile, ws, s);
+        else if (bs == 4) e = launch_spmv_bcsr4_main((int32_t)brows, (int32_t)nblocks, pos, crd, vals, x, y, tile, ws, s);
+        else e = launch_spmv_bcsr_g_main(bs, (int32_t)brows, (int32_t)nblocks, pos, crd, vals, x, y, tile, ws, s);
     }
     if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, bs, bs, tile, pos, ws, y, s);
     return hip_status(e);
@@ -368,7 +379,7 @@ int psk_spmm_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, con
                   const int32_t *crd, const float *vals, const float *B, int32_t k, int64_t ldb, float *C,
                   int64_t ldc, int32_t tile, int phases, void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (bs != 4) return bs <= 0 ? PSK_ERR_SIZE : PSK_ERR_UNSUPPORTED;
+    if (bs != 2 && bs != 4 && bs != 8) return bs <= 0 ? PSK_ERR_SIZE : PSK_ERR_UNSUPPORTED;
     if (k <= 0 || ldb < k || ldc < k) return PSK_ERR_SIZE;
     if (brows > (kMaxI32 - 1) / bs || bcols > kMaxI32 / bs || nblocks > kMaxI32 / (bs * bs)) return PSK_ERR_SIZE;
     Workspace ws;
@@ -385,7 +396,7 @@ int psk_spmm_bcsr(int64_t brows, int64_t bcols, int64_t nblocks, int32_t bs, con
         if (ntiles == 0) {
             e = launch_fill_zero_2d(C, brows * bs, k, ldc, s);
         } else {
-            e = launch_spmm_bcsr4_main((int32_t)brows, (int32_t)nblocks, pos, crd, vals, B, k, ldb, C, ldc, tile, ws, s);
+            e = launch_spmm_bcsr_main(bs, (int32_t)brows, (int32_t)nblocks, pos, crd, vals, B, k, ldb, C, ldc, tile, ws, s);
         }
     }
     if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, bs, k, ldc, tile, pos, ws, C, s);

@@ -80,12 +80,16 @@ hipError_t launch_spmm_rowsplit(int32_t rows, const int32_t *pos, const int32_t 
                                 const float *B, int32_t k, int64_t ldb, float *C, int64_t ldc,
                                 hipStream_t s);
 
-// BCSR (bs = 4)
+// BCSR (SpMV: bs = 4 has its own kernel, 2 and 8 share one; SpMM: bs in {2, 4, 8})
 bool bcsr_tile_ok(int32_t tile);
+bool bcsr_g_tile_ok(int32_t bs, int32_t tile);
+hipError_t launch_spmv_bcsr_g_main(int32_t bs, int32_t brows, int32_t nblocks, const int32_t *pos, const int32_t *crd,
+                                   const float *vals, const float *x, float *y, int32_t tile, const Workspace &w,
+                                   hipStream_t s);
 hipError_t launch_spmv_bcsr4_main(int32_t brows, int32_t nblocks, const int32_t *pos, const int32_t *crd,
                                   const float *vals, const float *x, float *y, int32_t tile,
                                   const Workspace &w, hipStream_t s);
-hipError_t launch_spmm_bcsr4_main(int32_t brows, int32_t nblocks, const int32_t *pos, const int32_t *crd,
+hipError_t launch_spmm_bcsr_main(int32_t bs, int32_t brows, int32_t nblocks, const int32_t *pos, const int32_t *crd,
                                   const float *vals, const float *B, int32_t k, int64_t ldb, float *C,
                                   int64_t ldc, int32_t tile, const Workspace &w, hipStream_t s);
 

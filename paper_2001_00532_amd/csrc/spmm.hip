@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) void k_spmm_pos(int rows, int nnz, const int *
                                                   float *__restrict__ carry_val, int ntiles, int T)
 {
     constexpr int THREADS = 256, NW = THREADS / WAVE, KW = WAVE * VEC;
-    constexpr int U = (BS == 1) ? 8 : 2;          // positions whose B rows are in flight together
+    constexpr int U = BS == 1 ? 8 : (BS == 2 ? 4 : (BS == 4 ? 2 : 1));   // positions whose B rows are in flight together
     extern __shared__ int sflag[];                // T ints
     __shared__ float srec[2 * NW][BS][KW];
     __shared__ int srec_row[2 * NW];              // -2 unused, -1 open segment, >= 0 row that ended
@@ -238,15 +238,17 @@ static hipError_t launch_spmm_pos(int32_t rows, int32_t nnz, const int32_t *pos,
 {
     const int ntiles = (int)(((int64_t)nnz + tile - 1) / tile);
     if (ntiles == 0) return hipSuccess;
-    const int vec = pick_vec(B, k, ldb, C, ldc);
+    int vec = pick_vec(B, k, ldb, C, ldc);
+    if (BS == 8 && vec == 4) vec = 2;             // 8 x 8 blocks: the LDS records of four columns per lane do not fit
     const int kw = WAVE * vec;
     const dim3 grid(xcd_grid(ntiles), (k + kw - 1) / kw);
     const size_t lds = (size_t)tile * sizeof(int);
 #define PSK_GO(V)                                                                                              \
     hipLaunchKernelGGL((k_spmm_pos<BS, V>), grid, dim3(256), lds, s, rows, nnz, pos, crd, vals, B, k,          \
                        (long long)ldb, C, (long long)ldc, w.tile_row, w.carry_row, w.carry_val, ntiles, tile)
-    if (vec == 4) PSK_GO(4);
-    else if (vec == 2) PSK_GO(2);
+    if (vec == 4) {
+        if constexpr (BS < 8) PSK_GO(4);
+    } else if (vec == 2) PSK_GO(2);
     else PSK_GO(1);
 #undef PSK_GO
     return hipGetLastError();
@@ -259,11 +261,14 @@ hipError_t launch_spmm_csr_main(int32_t rows, int32_t nnz, const int32_t *pos, c
     return launch_spmm_pos<1>(rows, nnz, pos, crd, vals, B, k, ldb, C, ldc, tile, w, s);
 }
 
-hipError_t launch_spmm_bcsr4_main(int32_t brows, int32_t nblocks, const int32_t *pos, const int32_t *crd,
-                                  const float *vals, const float *B, int32_t k, int64_t ldb, float *C,
-                                  int64_t ldc, int32_t tile, const Workspace &w, hipStream_t s)
+hipError_t launch_spmm_bcsr_main(int32_t bs, int32_t brows, int32_t nblocks, const int32_t *pos, const int32_t *crd,
+                                 const float *vals, const float *B, int32_t k, int64_t ldb, float *C,
+                                 int64_t ldc, int32_t tile, const Workspace &w, hipStream_t s)
 {
-    return launch_spmm_pos<4>(brows, nblocks, pos, crd, vals, B, k, ldb, C, ldc, tile, w, s);
+    if (bs == 2) return launch_spmm_pos<2>(brows, nblocks, pos, crd, vals, B, k, ldb, C, ldc, tile, w, s);
+    if (bs == 4) return launch_spmm_pos<4>(brows, nblocks, pos, crd, vals, B, k, ldb, C, ldc, tile, w, s);
+    if (bs == 8) return launch_spmm_pos<8>(brows, nblocks, pos, crd, vals, B, k, ldb, C, ldc, tile, w, s);
+    return hipErrorInvalidValue;
 }
 
 // Row-split SpMM baseline: one wave per row, lanes over columns (64 at a time), serial over the

@@ -33,6 +33,9 @@ def test_sizes_and_strings():
     for op in range(6):
         assert psk.psk_default_tile(op) > 0
     assert psk.psk_default_tile(9) == -1
+    assert psk.psk_default_tile_bcsr(psk.PSK_OP_SPMV_BCSR, 4) == psk.psk_default_tile(psk.PSK_OP_SPMV_BCSR)
+    assert psk.psk_default_tile_bcsr(psk.PSK_OP_SPMV_BCSR, 2) > 0 and psk.psk_default_tile_bcsr(psk.PSK_OP_SPMV_BCSR, 8) > 0
+    assert psk.psk_default_tile_bcsr(psk.PSK_OP_SPMV_BCSR, 3) == -1 and psk.psk_default_tile_bcsr(psk.PSK_OP_SPMV_CSR, 4) == -1
     w = psk.psk_workspace_bytes(psk.PSK_OP_SPMV_CSR, 100, 10_000, tile=1024)
     assert w >= 256 and w % 256 == 0
     assert psk.psk_workspace_bytes(psk.PSK_OP_SPMM_CSR, 100, 10_000, k=128, tile=1024) > w
@@ -78,7 +81,8 @@ def test_argument_errors_are_reported_before_any_launch():
     # UNSUPPORTED
     assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 1, 0, one, big, null) == 5
     assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 1, 8, one, big, null) == 5
-    assert L.psk_spmv_bcsr(4, 4, 4, 2, one, one, one, one, one, 0, 7, one, big, null) == 5
+    assert L.psk_spmv_bcsr(4, 4, 4, 3, one, one, one, one, one, 0, 7, one, big, null) == 5
+    assert L.psk_spmv_bcsr(4, 4, 4, 2, one, one, one, one, one, 64, 7, one, big, null) == 3              # tile of another block size
     assert L.psk_spmv_csr_rowsplit(4, 4, 4, one, one, one, one, one, 2, null) == 5
     assert L.psk_spmv_csr(4, 4, 4, one, one, one, one, one, 0, 9, 7, one, big, null) == 2                # col_passes
     out = ctypes.c_int32(-1)

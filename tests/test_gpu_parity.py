@@ -276,6 +276,33 @@ def test_bcsr_spmm(k):
             check(C.cpu().numpy(), ref, mag, "bcsr spmm %s k=%d tile %d" % (name, k, tile))
 
 
+@pytest.mark.parametrize("bs,tiles", [(2, [0, 512, 1024, 2048]), (8, [0, 32, 64, 128])])
+def test_bcsr_other_block_sizes(bs, tiles):
+    """2 x 2 and 8 x 8 blocks: SpMV (kernel of its own) and SpMM (the 4 x 4 kernel's template)."""
+    rng = np.random.default_rng(60 + bs)
+    cases = [(kind, wl.csr_from_lengths(adversarial_lengths(rng, 1203, 1501, kind), 1501, seed=53, bs=bs))
+             for kind in ADVERSARIAL_KINDS]
+    cases.append(("eight per block row", wl.csr_from_lengths(np.full(6000, 8), 6000, seed=54, bs=bs)))
+    for name, A in cases:
+        x = wl.dense_uniform(A.cols * bs, 53, wl.S_X)
+        ref, mag = oracle.spmv_bcsr(A.pos, A.crd, A.vals, x, bs, threads=8)
+        D, xd = DevCSR(A), dev(x)
+        for tile in tiles:
+            say("bcsr spmv", name, "bs", bs, "tile", tile, "blocks", A.nnz)
+            y = torch.full((A.rows * bs,), float("nan"), device="cuda")
+            psk.psk_spmv_bcsr(A.rows, A.cols, A.nnz, bs, D.pos, D.crd, D.vals, xd, y, tile=tile)
+            torch.cuda.synchronize()
+            check(y.cpu().numpy(), ref, mag, "bcsr spmv %s bs %d tile %d" % (name, bs, tile))
+        for k in (64, 40, 256):
+            B = wl.dense_uniform(A.cols * bs * k, 55, wl.S_B).reshape(A.cols * bs, k)
+            refC, magC = oracle.spmm_bcsr(A.pos, A.crd, A.vals, B, bs, threads=8)
+            say("bcsr spmm", name, "bs", bs, "k", k)
+            C = torch.full((A.rows * bs, k), float("nan"), device="cuda")
+            psk.psk_spmm_bcsr(A.rows, A.cols, A.nnz, bs, D.pos, D.crd, D.vals, dev(B), C, tile=128)
+            torch.cuda.synchronize()
+            check(C.cpu().numpy(), refC, magC, "bcsr spmm %s bs %d k %d" % (name, bs, k))
+
+
 # ------------------------------------------------------------------ cross checks that need no oracle
 def test_three_way_agreement_and_tile_invariance():
     c = wl.config(2, 0.01)
