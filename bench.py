@@ -52,6 +52,9 @@ MEASURED_TRAFFIC_BYTES = {
     ("spmm", 512, 1): 8775522994,          # profiles/k_spmm_pos_csr_spmm_k128.txt
     ("bcsr_spmv", 512, 1): 191661400,      # profiles/k_spmv_bcsr4_bcsr_spmv.txt
     ("bcsr_spmm", 64, 1): 2411765634,      # profiles/k_spmm_pos_bcsr_spmm_n64.txt
+    ("powerlaw_f64", 1024, 1): 5796716538,  # profiles/k_spmv_pos_f64_powerlaw.txt
+    ("stencil_f64", 1024, 1): 1405408380,   # profiles/k_spmv_pos_f64_stencil.txt
+    ("dcsr", 2048, 1): 1605536491 + 268435456 + 20685,   # profiles/k_spmv_pos_dcsr_hypersparse.txt: tile kernel + zero-fill of y
     ("mttkrp", 2048, 1): 11818248693,      # profiles/k_mttkrp_pos_mttkrp_j64.txt (L2 <-> fabric, j = 64)
 }
 
@@ -285,7 +288,9 @@ def bench_dcsr(args, torch, psk, wl):
                              "all": round(statistics.median(all_ms) * 1e3, 2)},
         "roofline": {"bound": "hbm", "kernel": "k_fill_zero + " + ("k_spmv_pos" if args.cut == "positions" else "k_spmv_wave_per_row"),
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "algorithmic_bytes": comp,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(("dcsr", tile, 1)) if args.cut == "positions" else None,
+                     "algorithmic_bytes": comp,
                      "avg_launch_us": round(main_avg * 1e3, 2), "launches_per_step": 2,
                      "byte_model": "A once + x once + y once (the zero-fill of y is part of the main phase)"},
     }
@@ -469,7 +474,7 @@ def main():
     main_avg = sum(main_ms) / len(main_ms)
     kernel_bytes = noreuse_bytes if kind.endswith("spmm") else comp_bytes
     achieved = kernel_bytes / (main_avg * 1e-3) / 1e9
-    traffic = None if f64 else MEASURED_TRAFFIC_BYTES.get((args.workload, tile, col_passes))
+    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload + ("_f64" if f64 else ""), tile, col_passes))
     if traffic is not None:
         traffic *= col_passes           # like `achieved`: all launches of the tile kernel in one product
 
