@@ -94,6 +94,21 @@ def algorithmic_bytes(kind, A, k):
     raise ValueError(kind)
 
 
+def time_cpu(fn, budget_s=10.0, max_runs=25):
+    """One warm-up call, then repeated calls for about budget_s seconds of CPU work (3..max_runs calls);
+    returns (median seconds, calls)."""
+    t = time.perf_counter()
+    fn()
+    first = time.perf_counter() - t
+    n = int(max(3, min(max_runs, budget_s / max(first, 1e-6))))
+    ts = []
+    for _ in range(n):
+        t = time.perf_counter()
+        fn()
+        ts.append(time.perf_counter() - t)
+    return statistics.median(ts), n
+
+
 def flops(kind, A, k):
     per = 2 * (A.bs * A.bs)
     return per * A.nnz * (k if kind.endswith("spmm") else 1)
@@ -204,20 +219,12 @@ def bench_mttkrp(args, torch, psk, wl):
         import oracle
 
         cores = oracle.threads_used(len(os.sched_getaffinity(0)))
-        sel = np.arange(0, T.nslices, 8, dtype=np.int64)
-        leaves_per_slice = T.pos_l[T.pos_k[1:]] - T.pos_l[T.pos_k[:-1]]
-        frac = float(leaves_per_slice[sel].sum()) / max(1, nnz)
-        ts = []
-        for r in range(4):
-            t = time.perf_counter()
-            oracle.mttkrp_csf3(T.pos_k, T.crd_k, T.pos_l, T.crd_l, T.vals, Ch, Dh, sel=sel, threads=cores)
-            if r:
-                ts.append(time.perf_counter() - t)
-        tmed = statistics.median(ts)
+        frac = 1.0
+        tmed, nruns = time_cpu(lambda: oracle.mttkrp_csf3(T.pos_k, T.crd_k, T.pos_l, T.crd_l, T.vals, Ch, Dh, threads=cores))
         rec["cpu_baseline"] = {"value": round(fl * frac / tmed / 1e9, 3), "unit": "GFLOP/s", "cores": cores,
                                "kind": "oracle",
-                               "sample": "every 8th slice (%.3f of the nonzeros), fp64, OpenMP over slices, 1 warm-up + "
-                                         "3 runs, median %.3f s" % (frac, tmed)}
+                               "sample": "the whole tensor, fp64, OpenMP over slices, 1 warm-up + %d runs, median %.3f s"
+                                         % (nruns, tmed)}
     rec["generate_s"] = round(t_gen, 2)
     print(json.dumps(rec))
 
@@ -297,16 +304,10 @@ def bench_dcsr(args, torch, psk, wl):
     if not args.no_cpu:
         import oracle
 
-        ts = []
-        for r in range(4):
-            t = time.perf_counter()
-            oracle.spmv_dcsr(A.rows, A.crd_i, A.pos, A.crd, A.vals, xh)
-            if r:
-                ts.append(time.perf_counter() - t)
-        tmed = statistics.median(ts)
+        tmed, nruns = time_cpu(lambda: oracle.spmv_dcsr(A.rows, A.crd_i, A.pos, A.crd, A.vals, xh))
         rec["cpu_baseline"] = {"value": round(fl / tmed / 1e9, 3), "unit": "GFLOP/s", "cores": 1, "kind": "oracle",
-                               "sample": "the whole workload, fp64 accumulation, single thread, 1 warm-up + 3 runs, "
-                                         "median %.3f s" % tmed}
+                               "sample": "the whole workload, fp64 accumulation, single thread, 1 warm-up + %d runs, "
+                                         "median %.3f s" % (nruns, tmed)}
     rec["generate_s"] = round(t_gen, 2)
     print(json.dumps(rec))
 
@@ -610,19 +611,14 @@ def main():
             else:
                 oracle.spmm_bcsr(A.pos, A.crd, A.vals, dense_h, A.bs, sel=sel, threads=cores)
 
-        run_oracle()
-        ts = []
-        for _ in range(3):
-            t = time.perf_counter()
-            run_oracle()
-            ts.append(time.perf_counter() - t)
-        tmed = statistics.median(ts)
+        tmed, nruns = time_cpu(run_oracle)
         rec["cpu_baseline"] = {
             "value": round(fl * frac / tmed / 1e9, 3),
             "unit": "GFLOP/s",
             "cores": cores,
             "kind": "oracle",
-            "sample": "%s, fp64 accumulation, OpenMP over rows, 1 warm-up + 3 runs, median %.3f s" % (sample, tmed),
+            "sample": "%s, fp64 accumulation, OpenMP over rows, 1 warm-up + %d runs, median %.3f s"
+                      % (sample, nruns, tmed),
         }
     rec["generate_s"] = round(t_gen, 2)
     print(json.dumps(rec))
