@@ -15,6 +15,12 @@
  * a dense bs x bs block per stored position, row-major inside the block,
  * vals[(p*bs + ii)*bs + ji]).
  *
+ * Further down, the same cut on other operands and statements: A in DCSR (both
+ * levels compressed), fp64 values, the MTTKRP statement of the appendix on a
+ * three-level compressed tensor, a variant that divides the position space
+ * into a fixed number of parts, and the baselines/ablations of Section 8.
+ * Each entry point states what differs from the conventions below.
+ *
  * Conventions for every entry point
  *  - Every pointer is a DEVICE pointer owned by the caller.  The library does
  *    not allocate, free or keep any of them.  Scratch memory is passed in as
@@ -24,10 +30,14 @@
  *    synchronises.  Calls that share a workspace must be stream-ordered.
  *  - Index arrays are int32, values and dense operands fp32; products and sums
  *    are fp32 on the device (carries between tiles are combined in fp64).
+ *    psk_spmv_csr_f64 is all fp64.
  *  - Outputs are assigned, not accumulated: rows without stored entries
  *    become +0.0f.  Inputs and outputs must not overlap.
  *  - Results are run-to-run deterministic: every y(i) / C(i,k) has one writer
- *    and a fixed summation order for a given tile size.
+ *    and a fixed summation order for a given tile size (the one exception is
+ *    the baseline psk_spmv_csr_atomics).
+ *  - Only psk_analyze_csr and psk_suggest_schedule_csr may synchronise the
+ *    stream (they read one number back); they say so.
  *  - Preconditions that are NOT checked on the device (caller's contract):
  *    pos[0] = 0, pos non-decreasing, pos[rows] = nnz, 0 <= crd[p] < cols.
  *    Columns inside a row need not be sorted or distinct (duplicates add up).
@@ -64,7 +74,7 @@ typedef enum {
     PSK_ERR_WORKSPACE = 4,   /* workspace NULL, misaligned or smaller than psk_workspace_bytes */
     PSK_ERR_UNSUPPORTED = 5, /* unknown op / variant / phases */
     PSK_ERR_HIP = 6,         /* the HIP runtime reported an error at launch */
-    PSK_ERR_ALIGNMENT = 7    /* BCSR only: vals (and x for SpMV) must be 16-byte aligned */
+    PSK_ERR_ALIGNMENT = 7    /* BCSR: vals (and x for SpMV) not 16-byte aligned; fp64 SpMV: an operand not 8-byte aligned */
 } psk_status;
 
 typedef enum {
