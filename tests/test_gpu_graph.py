@@ -1,0 +1,73 @@
+"""The entry points only enqueue kernels on the caller's stream (no allocation, no synchronisation, no
+memset nodes), so a product can be captured into a HIP graph and replayed.  Every replay is checked
+against the eager result, with eager work and synchronisations between the replays."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import paper_2001_00532_amd as psk  # noqa: E402
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def test_captured_products_replay_correctly():
+    c = wl.config(2, 0.02)
+    A = c["A"]
+    pos, crd, vals = dev(A.pos), dev(A.crd), dev(A.vals)
+    x = dev(c["x"])
+    y = torch.zeros(A.rows, device="cuda")
+    ws = psk.workspace(psk.PSK_OP_SPMV_CSR, A.rows, A.nnz)
+    c4 = wl.config(4, 0.002)
+    M = c4["A"]
+    mpos, mcrd, mvals, B = dev(M.pos), dev(M.crd), dev(M.vals), dev(c4["B"])
+    C = torch.zeros((M.rows, 128), device="cuda")
+    ws2 = psk.workspace(psk.PSK_OP_SPMM_CSR, M.rows, M.nnz, k=128)
+
+    # warm-up on a side stream, then capture
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        psk.psk_spmv_csr(A.rows, A.cols, A.nnz, pos, crd, vals, x, y, col_passes=2, ws=ws)
+        psk.psk_spmm_csr(M.rows, M.cols, M.nnz, mpos, mcrd, mvals, B, C, ws=ws2)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    say("capturing")
+    with torch.cuda.graph(g):
+        psk.psk_spmv_csr(A.rows, A.cols, A.nnz, pos, crd, vals, x, y, col_passes=2, ws=ws)
+        psk.psk_spmm_csr(M.rows, M.cols, M.nnz, mpos, mcrd, mvals, B, C, ws=ws2)
+    for rep in range(4):
+        xh = wl.dense_uniform(A.cols, 100 + rep, wl.S_X)
+        Bh = wl.dense_uniform(M.cols * 128, 200 + rep, wl.S_B).reshape(M.cols, 128)
+        x.copy_(dev(xh))
+        B.copy_(dev(Bh))
+        y.fill_(float("nan"))
+        C.fill_(float("nan"))
+        ws.fill_(0xFF)                      # the replay must rebuild the table and the carries itself
+        ws2.fill_(0xFF)
+        say("replay", rep)
+        g.replay()
+        torch.cuda.synchronize()
+        y_eager = torch.empty_like(y)
+        C_eager = torch.empty_like(C)
+        psk.psk_spmv_csr(A.rows, A.cols, A.nnz, pos, crd, vals, x, y_eager, col_passes=2)
+        psk.psk_spmm_csr(M.rows, M.cols, M.nnz, mpos, mcrd, mvals, B, C_eager)
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager) and torch.equal(C, C_eager), "replay %d differs from the eager result" % rep
+        ref, mag = oracle.spmv_csr(A.pos, A.crd, A.vals, xh, threads=8)
+        ok, worst = oracle.within_tolerance(y.cpu().numpy(), ref, mag)
+        assert ok, "replay %d: %.3g" % (rep, worst)
