@@ -31,6 +31,11 @@
  * finds it by binary search; the oracle instead walks the rows once, the way
  * the position loop of Section 3 advances i past row ends and empty rows.
  *
+ * Further down: the same SpMV for fp64 operands (sums in extended precision), for a DCSR operand
+ * (both levels compressed, Section 2), and MTTKRP A(i,j) = B(i,k,l) C(k,j) D(l,j) (Appendix, "MTTKRP
+ * on a CPU") over a three-level compressed tensor with its two-level position cut.  All of them are
+ * pinned by tests/test_oracle_pins.py; none is "parity unpinned".
+ *
  * If `sel` is not NULL only the `nsel` listed rows are computed and outputs
  * are indexed by the position in the list (used to sample very large cases).
  * `threads` > 1 spreads rows over OpenMP threads; each row is still summed
