@@ -43,6 +43,13 @@ MUTANTS = [
     ("dcsr_writes_by_stored_index", "        y[crd_i[s]] = acc;", "        y[s] = acc;"),
     ("dcsr_absent_rows_not_zeroed", "for (int64_t i = 0; i < rows; ++i) { y[i] = 0.0; if (mag) mag[i] = 0.0; }",
      "for (int64_t i = 0; i < nstored; ++i) { y[i] = 0.0; if (mag) mag[i] = 0.0; }"),
+    ("mttkrp_c_indexed_by_leaf", "const float *c = C + (int64_t)crd_k[q] * ldc;", "const float *c = C + (int64_t)crd_l[pos_l[q] < pos_l[q + 1] ? pos_l[q] : 0] * ldc;"),
+    ("mttkrp_d_indexed_by_fiber", "const float *d = D + (int64_t)crd_l[p] * ldd;", "const float *d = D + (int64_t)crd_k[q] * ldd;"),
+    ("mttkrp_drops_last_leaf", "for (int64_t p = pos_l[q]; p < pos_l[q + 1]; ++p) {\n                const float *d", "for (int64_t p = pos_l[q]; p < pos_l[q + 1] - 1; ++p) {\n                const float *d"),
+    ("mttkrp_adds_instead_of_multiplying", "double term = v * (double)c[jj] * (double)d[jj];", "double term = v * ((double)c[jj] + (double)d[jj]);"),
+    ("mttkrp_ignores_ldd", "const float *d = D + (int64_t)crd_l[p] * ldd;", "const float *d = D + (int64_t)crd_l[p] * j;"),
+    ("partition_csf3_slice_from_position", "while (s < nslices && (int64_t)pos_k[s + 1] <= q) ++s;", "while (s < nslices && (int64_t)pos_k[s + 1] <= first) ++s;"),
+    ("partition_csf3_strict", "while (q < nfibers && (int64_t)pos_l[q + 1] <= first) ++q;", "while (q < nfibers && (int64_t)pos_l[q + 1] < first) ++q;"),
     ("f64_sums_in_double", "long double acc = 0.0L, m = 0.0L;", "double acc = 0.0, m = 0.0;"),
     ("f64_x_indexed_by_position", "(long double)vals[p] * (long double)x[crd[p]];", "(long double)vals[p] * (long double)x[p % 3];"),
     ("f64_operands_read_as_float", "(long double)vals[p] * (long double)x[crd[p]];", "(long double)(float)vals[p] * (long double)x[crd[p]];"),
@@ -131,6 +138,22 @@ def pins_pass(lib) -> bool:
             np.empty = real_empty
         if y.tolist() != [0.0, -1.0, 0.0, 0.0, 6.0, 0.0] or mag.tolist() != [0.0, 5.0, 0.0, 0.0, 6.0, 0.0]:
             return False
+        # MTTKRP: hand-worked case, a strided D, and the two-level cut against brute force
+        Cm = np.array([[1.0, 10.0], [2.0, 20.0]], dtype=np.float32)
+        Dm = np.array([[1.0, 1.0, 9.0], [0.5, 2.0, 9.0], [3.0, -1.0, 9.0]], dtype=np.float32)[:, :2]
+        Am, Mm = oracle.mttkrp_csf3([0, 2], [1, 0], [0, 2, 3], [0, 2, 1], [2.0, -1.0, 4.0], Cm, Dm)
+        if Am.tolist() != [[0.0, 140.0]] or Mm.tolist() != [[12.0, 140.0]]:
+            return False
+        Tt = wl.csf3_from_lengths([2, 0, 3, 1], [2, 0, 3, 1, 1, 4], (4, 5, 6), seed=8)
+        for tile in (1, 2, 3):
+            ts, tf = oracle.partition_csf3(Tt.pos_k, Tt.pos_l, tile)
+            nt = -(-Tt.nnz // tile)
+            for t in range(nt + 1):
+                first = min(t * tile, Tt.nnz)
+                qq = max(q for q in range(Tt.nfibers + 1) if Tt.pos_l[q] <= first)
+                ss = max(z for z in range(Tt.nslices + 1) if Tt.pos_k[z] <= qq)
+                if (tf[t], ts[t]) != (qq, ss):
+                    return False
         # partition: closed form, last-tile clamp, empty rows
         p = (np.arange(51) * 7).astype(np.int32)
         if oracle.partition(p, 13).tolist() != [min(t * 13, 350) // 7 for t in range(27)] + [50]:
