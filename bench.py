@@ -237,7 +237,8 @@ def bench_dcsr(args, torch, psk, wl):
     xh = wl.dense_uniform(A.cols, wl.BASE_SEED + 11, wl.S_X)
     t_gen = time.time() - t_gen
     cut = psk.PSK_CUT_POSITIONS if args.cut == "positions" else psk.PSK_CUT_ROWS
-    tile = args.tile or psk.psk_default_tile(psk.PSK_OP_SPMV_CSR)
+    passes = args.col_passes or 1
+    tile = args.tile or (1024 if passes > 1 else psk.psk_default_tile(psk.PSK_OP_SPMV_CSR))
     nnz, ns = A.nnz, A.nstored
     comp = 8 * nnz + 4 * (ns + 1) + 4 * ns + 4 * A.cols + 4 * A.rows
     fl = 2 * nnz
@@ -254,7 +255,7 @@ def bench_dcsr(args, torch, psk, wl):
 
     def step(s, phases=psk.PSK_PHASE_ALL):
         psk.psk_spmv_dcsr(A.rows, A.cols, nnz, s["crd_i"], s["pos"], s["crd"], s["vals"], s["x"], s["y"], cut=cut,
-                          tile=tile, phases=phases, ws=s["ws"], stream=stream)
+                          tile=tile, col_passes=passes, phases=phases, ws=s["ws"], stream=stream)
 
     for i in range(args.warmup):
         step(sets[i % copies])
@@ -289,6 +290,7 @@ def bench_dcsr(args, torch, psk, wl):
         "config": {"workload": "dcsr: %d rows (%d stored), %d cols, nnz %d (max row %d), cut at the %s level, tile %d, "
                                "%d operand copies rotated" % (A.rows, ns, A.cols, nnz, int(Ls.max()), args.cut, tile, copies),
                    "rows": A.rows, "stored_rows": ns, "cols": A.cols, "nnz": nnz, "cut": args.cut, "tile": tile,
+                   "col_passes": passes,
                    "seed": wl.BASE_SEED + 11},
         "ns_per_nnz": round(wall / args.steps * 1e9 / nnz, 6),
         "phases_us_median": {"main": round(statistics.median(main_ms) * 1e3, 2),
@@ -296,7 +298,7 @@ def bench_dcsr(args, torch, psk, wl):
         "roofline": {"bound": "hbm", "kernel": "k_fill_zero + " + ("k_spmv_pos" if args.cut == "positions" else "k_spmv_wave_per_row"),
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(("dcsr", tile, 1)) if args.cut == "positions" else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(("dcsr", tile, passes)) if args.cut == "positions" else None,
                      "algorithmic_bytes": comp,
                      "avg_launch_us": round(main_avg * 1e3, 2), "launches_per_step": 2,
                      "byte_model": "A once + x once + y once (the zero-fill of y is part of the main phase)"},

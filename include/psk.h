@@ -273,16 +273,19 @@ int psk_spmv_csr_f64(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos
  * `rows` entries; rows that are not stored (and stored rows without entries) become +0.
  *   cut = PSK_CUT_POSITIONS: tiles of `tile` positions of the column level (equal work per tile; a row
  *         may be divided; table, carries and fix-up as in psk_spmv_csr, the table holds stored-row
- *         indices).  tile, workspace: as psk_spmv_csr with rows = nstored and col_passes = 1.
+ *         indices).  tile, col_passes, workspace: as psk_spmv_csr with rows = nstored (psk_analyze_csr
+ *         with rows = nstored suggests col_passes).
  *   cut = PSK_CUT_ROWS: tiles of four positions of the row level, one wave per stored row (equal
  *         number of stored rows per tile; no row is divided, so no table, no carries, no fix-up:
- *         only PSK_PHASE_MAIN does anything).  `tile` must still be a valid value (0 is).
+ *         only PSK_PHASE_MAIN does anything).  `tile` must still be a valid value (0 is); col_passes is
+ *         ignored.
  * The main phase zero-fills y first.
  */
 enum { PSK_CUT_POSITIONS = 0, PSK_CUT_ROWS = 1 };
 int psk_spmv_dcsr(int64_t rows, int64_t cols, int64_t nstored, int64_t nnz, const int32_t *crd_i,
                   const int32_t *pos, const int32_t *crd, const float *vals, const float *x, float *y,
-                  int cut, int32_t tile, int phases, void *workspace, size_t workspace_bytes, void *stream);
+                  int cut, int32_t tile, int32_t col_passes, int phases, void *workspace, size_t workspace_bytes,
+                  void *stream);
 
 /*
  * y = A x, CSR, with the position space DIVIDED instead of split (Section 5 "Divide": the number of

@@ -74,7 +74,7 @@ def lib() -> ctypes.CDLL:
         L.psk_spmv_csr_notemp.restype = ci
         L.psk_spmv_csr_f64.argtypes = [i64, i64, i64, p, p, p, p, p, i32, ci, p, sz, p]
         L.psk_spmv_csr_f64.restype = ci
-        L.psk_spmv_dcsr.argtypes = [i64, i64, i64, i64, p, p, p, p, p, p, ci, i32, ci, p, sz, p]
+        L.psk_spmv_dcsr.argtypes = [i64, i64, i64, i64, p, p, p, p, p, p, ci, i32, i32, ci, p, sz, p]
         L.psk_spmv_dcsr.restype = ci
         L.psk_default_tile_bcsr.argtypes = [ci, i32]
         L.psk_default_tile_bcsr.restype = i32
@@ -277,15 +277,15 @@ def psk_spmv_csr_f64(rows, cols, nnz, pos, crd, vals, x, y, tile=0, phases=PSK_P
     return y
 
 
-def psk_spmv_dcsr(rows, cols, nnz, crd_i, pos, crd, vals, x, y, cut=PSK_CUT_POSITIONS, tile=0, phases=PSK_PHASE_ALL,
-                  ws=None, stream=None):
+def psk_spmv_dcsr(rows, cols, nnz, crd_i, pos, crd, vals, x, y, cut=PSK_CUT_POSITIONS, tile=0, col_passes=1,
+                  phases=PSK_PHASE_ALL, ws=None, stream=None):
     nstored = int(crd_i.numel())
     if ws is None:
         ws = workspace(PSK_OP_SPMV_CSR, nstored, nnz, tile=tile, device=pos.device)
     st = lib().psk_spmv_dcsr(int(rows), int(cols), nstored, int(nnz), _ptr(crd_i, torch.int32), _ptr(pos, torch.int32),
                              _ptr(crd, torch.int32), _ptr(vals, torch.float32), _ptr(x, torch.float32),
-                             _ptr(y, torch.float32), int(cut), int(tile), int(phases), _ptr(ws), ws.numel(),
-                             _stream(stream))
+                             _ptr(y, torch.float32), int(cut), int(tile), int(col_passes), int(phases), _ptr(ws),
+                             ws.numel(), _stream(stream))
     _check(st, "psk_spmv_dcsr")
     return y
 

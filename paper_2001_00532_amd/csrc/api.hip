@@ -220,10 +220,13 @@ int psk_spmv_csr_f64(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos
 }
 
 int psk_spmv_dcsr(int64_t rows, int64_t cols, int64_t nstored, int64_t nnz, const int32_t *crd_i, const int32_t *pos,
-                  const int32_t *crd, const float *vals, const float *x, float *y, int cut, int32_t tile, int phases,
-                  void *workspace, size_t workspace_bytes, void *stream)
+                  const int32_t *crd, const float *vals, const float *x, float *y, int cut, int32_t tile,
+                  int32_t col_passes, int phases, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (rows < 0 || rows > kMaxI32 || nstored < 0 || nstored > rows) return PSK_ERR_SIZE;
+    if (col_passes < 0 || col_passes > PSK_MAX_COL_PASSES) return PSK_ERR_SIZE;
+    if (col_passes == 0) col_passes = 1;
+    if (tile == 0 && col_passes > 1) tile = 1024;
     if (cut != PSK_CUT_POSITIONS && cut != PSK_CUT_ROWS) return PSK_ERR_UNSUPPORTED;
     if (nstored > 0 && !crd_i) return PSK_ERR_NULL;
     Workspace ws;
@@ -247,8 +250,8 @@ int psk_spmv_dcsr(int64_t rows, int64_t cols, int64_t nstored, int64_t nnz, cons
     if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
         e = launch_fill_zero(y, rows, s);
         if (ntiles > 0 && e == hipSuccess)
-            e = launch_spmv_csr_main((int32_t)nstored, (int32_t)cols, (int32_t)nnz, pos, crd, vals, x, y, tile, 1, ws, s,
-                                     crd_i);
+            e = launch_spmv_csr_main((int32_t)nstored, (int32_t)cols, (int32_t)nnz, pos, crd, vals, x, y, tile,
+                                     col_passes, ws, s, crd_i);
     }
     if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess && ntiles > 0)
         e = launch_carry_fixup(ntiles, 1, 1, 1, tile, pos, ws, y, s, nullptr, crd_i);

@@ -63,6 +63,7 @@ __device__ __forceinline__ void run_select(const RunPlan &p, v4f_u wA, v4f_u wB,
 // 4: one pass over a DCSR operand: `rows` counts the stored rows, row s of the hierarchy is row rowmap[s]
 //    of y (Section 3: the cut may be taken at any level of any coordinate hierarchy; y is zero-filled
 //    by the caller because rows that are not stored are written by nobody).
+// 5: a column pass (as 1) over a DCSR operand (as 4).
 // 3: one pass without the per-thread temporary and without the unrolled load loop (the ablation of
 //    Section 8.3): each thread walks its positions in a rolled loop, one load -> gather -> multiply -> LDS
 //    store after the other.
@@ -81,7 +82,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
     constexpr int LONG = 32;
     constexpr int MAXLONG = T / LONG;
     constexpr bool VEC = MODE != 0;
-    constexpr bool WIN = VARIANT == 1, ATOM = VARIANT == 2, NOTEMP = VARIANT == 3, ROWMAP = VARIANT == 4;
+    constexpr bool WIN = VARIANT == 1 || VARIANT == 5, ATOM = VARIANT == 2, NOTEMP = VARIANT == 3;
+    constexpr bool ROWMAP = VARIANT == 4 || VARIANT == 5;
     static_assert(NPT % 4 == 0, "NPT must be a multiple of 4");
     __shared__ float sprod[skewed_size<1>(T)];
     __shared__ int slong[MAXLONG * 3];
@@ -218,7 +220,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
             carry_row[t] = r;
             carry_val[t] = (WIN && accum) ? carry_val[t] + v : v;
         } else if (ROWMAP) {
-            y[rowmap[r]] = v;
+            float *dst = y + rowmap[r];
+            *dst = (WIN && accum) ? *dst + v : v;
         } else {
             y[r] = (WIN && accum) ? y[r] + v : v;
         }
@@ -294,9 +297,11 @@ static void launch_pos(int mode, int grid, hipStream_t s, int rows, int cols, in
 #define PSK_GO(M, W)                                                                                             \
     hipLaunchKernelGGL((k_spmv_pos<THREADS, NPT, M, W>), dim3(grid), dim3(THREADS), 0, s, rows, cols, nnz, pos,  \
                        crd, vals, x, y, w.tile_row, w.carry_row, w.carry_val, ntiles, clo, chi, accum, rowmap)
-    const int variant = rowmap ? 4 : (accum >= 2 ? accum : ((clo > 0 || chi < cols) ? 1 : 0));
+    const bool window = clo > 0 || chi < cols;
+    const int variant = rowmap ? (window ? 5 : 4) : (accum >= 2 ? accum : (window ? 1 : 0));
     if (variant == 3) PSK_GO(0, 3);
     else if (variant == 4) { if (mode == 1) PSK_GO(1, 4); else PSK_GO(0, 4); }
+    else if (variant == 5) { if (mode == 1) PSK_GO(1, 5); else PSK_GO(0, 5); }
     else if (mode == 1) { if (variant == 2) PSK_GO(1, 2); else if (variant == 1) PSK_GO(1, 1); else PSK_GO(1, 0); }
     else { if (variant == 2) PSK_GO(0, 2); else if (variant == 1) PSK_GO(0, 1); else PSK_GO(0, 0); }
 #undef PSK_GO

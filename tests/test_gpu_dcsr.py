@@ -28,13 +28,13 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def run(name, A, cut, tile, x=None):
+def run(name, A, cut, tile, x=None, passes=1):
     x = wl.dense_uniform(A.cols, 9, wl.S_X) if x is None else x
     ref, mag = oracle.spmv_dcsr(A.rows, A.crd_i, A.pos, A.crd, A.vals, x)
     y = torch.full((A.rows,), float("nan"), device="cuda")
-    say("dcsr", name, "cut", cut, "tile", tile, "rows", A.rows, "stored", A.nstored, "nnz", A.nnz)
+    say("dcsr", name, "cut", cut, "tile", tile, "passes", passes, "rows", A.rows, "stored", A.nstored, "nnz", A.nnz)
     psk.psk_spmv_dcsr(A.rows, A.cols, A.nnz, dev(A.crd_i), dev(A.pos), dev(A.crd), dev(A.vals), dev(x), y, cut=cut,
-                      tile=tile)
+                      tile=tile, col_passes=passes)
     torch.cuda.synchronize()
     got = y.cpu().numpy()
     ok, worst = oracle.within_tolerance(got, ref, mag, REL, FLOOR)
@@ -55,6 +55,15 @@ def test_dcsr_structures(cut, tile):
     # every row stored: must agree with CSR
     L = rng.integers(0, 40, size=3000)
     run("all stored", wl.dcsr_from_lengths(3000, L, 500, seed=32), cut, tile)
+
+
+@pytest.mark.parametrize("passes", [2, 3, 4])
+def test_dcsr_column_passes(passes):
+    rng = np.random.default_rng(34)
+    for kind in ADVERSARIAL_KINDS:
+        L = adversarial_lengths(rng, 1501, 4001, kind)
+        for tile in (0, 256, 2048):
+            run(kind, wl.dcsr_from_lengths(200_000, L, 4001, seed=34), psk.PSK_CUT_POSITIONS, tile, passes=passes)
 
 
 @pytest.mark.parametrize("cut", CUTS)
@@ -84,3 +93,5 @@ def test_dcsr_hypersparse_full_size(cut):
     L = wl.zipf_lengths(1_000_000, 1.8, 1, 50_000, wl.BASE_SEED + 11)
     A = wl.dcsr_from_lengths(1 << 26, L, 1 << 21, seed=wl.BASE_SEED + 11)
     run("hypersparse", A, cut, 0)
+    if cut == psk.PSK_CUT_POSITIONS:
+        run("hypersparse", A, cut, 0, passes=2)
