@@ -36,7 +36,7 @@
  *  - Results are run-to-run deterministic: every y(i) / C(i,k) has one writer
  *    and a fixed summation order for a given tile size (the one exception is
  *    the baseline psk_spmv_csr_atomics).
- *  - Only psk_analyze_csr and psk_suggest_schedule_csr may synchronise the
+ *  - Only psk_analyze_csr, psk_suggest_schedule_csr and psk_validate_csr synchronise the
  *    stream (they read one number back); they say so.
  *  - Preconditions that are NOT checked on the device (caller's contract):
  *    pos[0] = 0, pos non-decreasing, pos[rows] = nnz, 0 <= crd[p] < cols.
@@ -165,6 +165,17 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
 #define PSK_MAX_COL_PASSES 4
 int psk_analyze_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
                     void *workspace, size_t workspace_bytes, int32_t *col_passes, void *stream);
+
+/*
+ * Checks the preconditions the operations do not check (they would read or write out of bounds on a
+ * malformed structure).  *violation (HOST pointer) receives 0 if pos[0] = 0, pos is non-decreasing,
+ * pos[rows] = nnz and 0 <= crd[p] < cols for all p; otherwise the number of the first condition, in that
+ * order, that fails: 1, 2, 3 or 4.  Works for BCSR (pass block counts) and for each level of the
+ * compressed tensor formats.  One pass over pos and crd; SYNCHRONISES `stream` (it reads the counts
+ * back); `workspace` needs 256 bytes.  Note that the kernel itself trusts nnz and rows as array lengths.
+ */
+int psk_validate_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                     void *workspace, size_t workspace_bytes, int32_t *violation, void *stream);
 
 /*
  * Which schedule for y = A x on this matrix: the position cut (psk_spmv_csr) or the row split with one

@@ -26,7 +26,7 @@ EXPORTS = [
     "psk_status_string", "psk_version", "psk_default_tile", "psk_num_tiles", "psk_workspace_bytes",
     "psk_partition_csr", "psk_analyze_csr", "psk_spmv_csr", "psk_spmm_csr", "psk_spmv_bcsr", "psk_spmm_bcsr",
     "psk_spmv_csr_rowsplit", "psk_spmm_csr_rowsplit", "psk_spmv_csr_atomics", "psk_mttkrp_csf3",
-    "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64", "psk_spmv_dcsr", "psk_spmv_csr_divide", "psk_suggest_schedule_csr", "psk_default_tile_bcsr",
+    "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64", "psk_spmv_dcsr", "psk_spmv_csr_divide", "psk_suggest_schedule_csr", "psk_default_tile_bcsr", "psk_validate_csr",
 ]
 
 
@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.psk_default_tile_bcsr.restype = i32
         L.psk_suggest_schedule_csr.argtypes = [i64, i64, p, p, sz, p, p]
         L.psk_suggest_schedule_csr.restype = ci
+        L.psk_validate_csr.argtypes = [i64, i64, i64, p, p, p, sz, p, p]
+        L.psk_validate_csr.restype = ci
         L.psk_spmv_csr_divide.argtypes = [i64, i64, i64, p, p, p, p, p, i32, ci, p, sz, p]
         L.psk_spmv_csr_divide.restype = ci
         L.psk_spmv_csr_rowsplit.argtypes = [i64, i64, i64, p, p, p, p, p, ci, p]
@@ -168,6 +170,18 @@ def psk_analyze_csr(rows, cols, nnz, pos, crd, ws=None, stream=None) -> int:
     st = lib().psk_analyze_csr(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                                _ptr(ws), ws.numel(), ctypes.byref(out), _stream(stream))
     _check(st, "psk_analyze_csr")
+    return int(out.value)
+
+
+def psk_validate_csr(rows, cols, nnz, pos, crd, ws=None, stream=None) -> int:
+    """0 if the index structure is well formed, else the number (1..4) of the first failing condition
+    (synchronises the stream)."""
+    if ws is None:
+        ws = torch.empty(256, dtype=torch.uint8, device=pos.device)
+    out = ctypes.c_int32(-1)
+    st = lib().psk_validate_csr(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
+                                _ptr(ws), ws.numel(), ctypes.byref(out), _stream(stream))
+    _check(st, "psk_validate_csr")
     return int(out.value)
 
 

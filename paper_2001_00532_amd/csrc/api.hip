@@ -153,6 +153,24 @@ int psk_analyze_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos,
     return PSK_OK;
 }
 
+int psk_validate_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd, void *workspace,
+                     size_t workspace_bytes, int32_t *violation, void *stream)
+{
+    if (rows < 0 || cols < 0 || nnz < 0 || nnz > kMaxI32 || rows > kMaxI32 - 1 || cols > kMaxI32) return PSK_ERR_SIZE;
+    if (!violation || !pos || (nnz > 0 && !crd)) return PSK_ERR_NULL;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < 256) return PSK_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t *dev = static_cast<int32_t *>(workspace);
+    int32_t host[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (launch_validate_csr((int32_t)rows, (int32_t)cols, (int32_t)nnz, pos, crd, dev, s) != hipSuccess) return PSK_ERR_HIP;
+    if (hipMemcpyAsync(host, dev, sizeof(host), hipMemcpyDeviceToHost, s) != hipSuccess) return PSK_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return PSK_ERR_HIP;
+    *violation = 0;
+    for (int c = 1; c <= 4; ++c)
+        if (host[c] != 0) { *violation = c; break; }
+    return PSK_OK;
+}
+
 int psk_suggest_schedule_csr(int64_t rows, int64_t nnz, const int32_t *pos, void *workspace, size_t workspace_bytes,
                              int32_t *schedule, void *stream)
 {

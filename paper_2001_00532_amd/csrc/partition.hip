@@ -152,6 +152,39 @@ hipError_t launch_max_row(int32_t rows, const int32_t *pos, int32_t *result, hip
     return hipGetLastError();
 }
 
+// Structural check of a CSR index structure.  result[c] counts the violations of condition c:
+// 1: pos[0] != 0;  2: pos[i+1] < pos[i];  3: pos[rows] != nnz;  4: crd[p] outside [0, cols).
+// result[0..4] must hold 0 before the launch.
+__global__ __launch_bounds__(256) void k_validate_csr(int rows, int cols, int nnz, const int *__restrict__ pos,
+                                                      const int *__restrict__ crd, int *__restrict__ result)
+{
+    const long long g = (long long)blockIdx.x * blockDim.x + threadIdx.x, stride = (long long)gridDim.x * blockDim.x;
+    int bad2 = 0, bad4 = 0;
+    for (long long i = g; i < rows; i += stride) bad2 += pos[i + 1] < pos[i] ? 1 : 0;
+    for (long long p = g; p < nnz; p += stride) {
+        const int c = crd[p];
+        bad4 += (c < 0 || c >= cols) ? 1 : 0;
+    }
+    if (g == 0) {
+        if (pos[0] != 0) atomicAdd(result + 1, 1);
+        if (pos[rows] != nnz) atomicAdd(result + 3, 1);
+    }
+    if (bad2) atomicAdd(result + 2, bad2);
+    if (bad4) atomicAdd(result + 4, bad4);
+}
+
+hipError_t launch_validate_csr(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                               int32_t *result, hipStream_t s)
+{
+    hipError_t e = launch_fill_zero(reinterpret_cast<float *>(result), 8, s);
+    if (e != hipSuccess) return e;
+    int64_t work = rows > nnz ? rows : nnz;
+    int64_t blocks = (work + 255) / 256;
+    blocks = blocks < 1 ? 1 : (blocks > 4096 ? 4096 : blocks);
+    hipLaunchKernelGGL(k_validate_csr, dim3((unsigned)blocks), dim3(256), 0, s, rows, cols, nnz, pos, crd, result);
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void k_fill_zero(float *__restrict__ p, long long n)
 {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;

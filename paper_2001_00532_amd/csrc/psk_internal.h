@@ -36,6 +36,8 @@ hipError_t launch_partition(int64_t rows, int64_t nnz, const int32_t *pos, int32
                             int32_t *tile_row, hipStream_t s);
 hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s);
 hipError_t launch_fill_zero_2d(float *p, int64_t rows, int32_t width, int64_t ld, hipStream_t s);
+hipError_t launch_validate_csr(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                               int32_t *result, hipStream_t s);
 hipError_t launch_max_row(int32_t rows, const int32_t *pos, int32_t *result, hipStream_t s);
 hipError_t launch_probe_locality(int32_t nnz, const int32_t *crd, int32_t *result, hipStream_t s);
 // Adds the per-tile carry records to the output: element e of a record of `nsub*k` floats goes to

@@ -107,6 +107,8 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.psk_spmv_csr_divide(4, 4, 4, one, one, one, one, one, 0, 7, null, big, null) == 4
     assert L.psk_spmv_csr_notemp(4, 4, 4, one, one, one, one, one, 100, 7, one, big, null) == 3
     assert L.psk_spmv_csr_atomics(4, 4, 4, one, one, null, one, one, 0, 7, one, big, null) == 1
+    assert L.psk_validate_csr(4, 4, 4, one, one, one, 256, None, null) == 1
+    assert L.psk_validate_csr(4, 4, 4, one, one, null, 0, ctypes.byref(out), null) == 4
     assert L.psk_suggest_schedule_csr(4, 4, one, one, 256, None, null) == 1
     assert L.psk_suggest_schedule_csr(4, 4, one, null, 0, ctypes.byref(out), null) == 4
     assert L.psk_suggest_schedule_csr(4, 4, one, one, 256, ctypes.byref(out), null) == 0 and out.value == 0  # short rows: no launch

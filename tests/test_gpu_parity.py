@@ -344,6 +344,28 @@ def test_analyze_small_problems_need_no_passes():
     assert psk.psk_analyze_csr(A.rows, A.cols, A.nnz, D.pos, D.crd) == 1
 
 
+def test_validate_matches_the_oracle_on_broken_structures():
+    """Integer work: the verdict is compared exactly with the oracle's on planted structural errors."""
+    A = wl.csr_from_lengths(np.random.default_rng(12).integers(0, 40, size=5000), 3000, seed=12)
+    cases = [("valid", A.pos, A.crd, A.nnz)]
+    p = A.pos.copy(); p[0] = 1
+    cases.append(("pos[0] != 0", p, A.crd, A.nnz))
+    p = A.pos.copy(); p[2500] = p[2499] - 1 if p[2499] > 0 else p[2501] + 1
+    cases.append(("pos decreases", p, A.crd, A.nnz))
+    cases.append(("pos[rows] != nnz", A.pos, A.crd, A.nnz - 1))
+    c = A.crd.copy(); c[A.nnz // 2] = 3000
+    cases.append(("column too large", A.pos, c, A.nnz))
+    c = A.crd.copy(); c[7] = -1
+    cases.append(("negative column", A.pos, c, A.nnz))
+    p = A.pos.copy(); p[0] = 1; c = A.crd.copy(); c[0] = 99999
+    cases.append(("two errors: the first in order is reported", p, c, A.nnz))
+    for name, pos, crd, nnz in cases:
+        want = oracle.validate_csr(pos, crd, A.cols) if nnz == A.nnz else 3
+        say("validate", name, "expect", want)
+        assert psk.psk_validate_csr(A.rows, A.cols, nnz, dev(pos), dev(crd)) == want, name
+    assert psk.psk_validate_csr(0, 5, 0, dev(np.zeros(1, dtype=np.int32)), dev(np.zeros(0, dtype=np.int32))) == 0
+
+
 def test_suggest_schedule_follows_its_rule():
     """Row split only for small matrices with long, alike rows; the position cut otherwise."""
     def ask(lengths):
