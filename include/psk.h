@@ -158,7 +158,7 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
  * Suggests col_passes for psk_spmv_csr on this matrix (like the tile->row table it depends only on A and
  * can be kept).  Answers 1 when x fits a die's L2 or the matrix is small; otherwise it samples up to
  * 16384 positions and, if fewer than half of them have their successor's column in the same 128-byte
- * line of x, suggests ceil(4*cols bytes / 4 MiB), at most PSK_MAX_COL_PASSES.
+ * line of x, suggests ceil(4*cols bytes / 6 MiB), at most PSK_MAX_COL_PASSES.
  * `col_passes` is a HOST pointer.  Unlike every other call this one SYNCHRONISES `stream` (it reads the
  * sample count back); `workspace` needs 256 bytes.
  */

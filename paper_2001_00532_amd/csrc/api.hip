@@ -147,7 +147,8 @@ int psk_analyze_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos,
     if (hipMemcpyAsync(host, dev, sizeof(host), hipMemcpyDeviceToHost, s) != hipSuccess) return PSK_ERR_HIP;
     if (hipStreamSynchronize(s) != hipSuccess) return PSK_ERR_HIP;
     if (host[1] > 0 && 2 * (int64_t)host[0] < host[1]) {   // fewer than half of the gathers stay in their line
-        const int64_t want = (x_bytes + (int64_t(4) << 20) - 1) / (int64_t(4) << 20);
+        // slices of up to 6 MiB: measured best at x = 8 MB (2 passes), 16 MB (3) and 32 MB (4, the cap)
+        const int64_t want = (x_bytes + (int64_t(6) << 20) - 1) / (int64_t(6) << 20);
         *col_passes = (int32_t)(want > PSK_MAX_COL_PASSES ? PSK_MAX_COL_PASSES : want);
     }
     return PSK_OK;

@@ -113,6 +113,11 @@ def test_analyze_full_size():
     assert psk.psk_analyze_csr(A.rows, A.cols, A.nnz, dev(A.pos), dev(A.crd)) == 2
     A = wl.config(3)["A"]
     assert psk.psk_analyze_csr(A.rows, A.cols, A.nnz, dev(A.pos), dev(A.crd)) == 1
+    # the rule only looks at cols and at sampled column distances: x of 16 MB -> 3, of 32 MB and more -> 4
+    A = wl.csr_uniform(1_000_000, 4_000_000, 4, 5)
+    assert psk.psk_analyze_csr(A.rows, A.cols, A.nnz, dev(A.pos), dev(A.crd)) == 3
+    A = wl.csr_uniform(1_000_000, 20_000_000, 4, 5)
+    assert psk.psk_analyze_csr(A.rows, A.cols, A.nnz, dev(A.pos), dev(A.crd)) == 4
 
 
 def test_mttkrp_full_size():
