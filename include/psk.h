@@ -144,7 +144,8 @@ int psk_partition_csr(int64_t rows, int64_t nnz, const int32_t *pos, int32_t til
  *
  * col_passes (0 or 1 = off, at most PSK_MAX_COL_PASSES): the main step is run that many times, pass q
  * gathering only the columns of the q-th equal slice of [0, cols) and adding to what the earlier passes
- * stored.  A and the row bounds are streamed once per pass; in exchange the slice of x a pass gathers
+ * stored (the first pass records each tile's column range, and a later pass leaves a tile whose range
+ * misses its window untouched).  A and the row bounds are streamed once per pass; in exchange the slice of x a pass gathers
  * from can stay in the 4 MB L2 of a die.  Worth it only for matrices whose columns are scattered over
  * an x larger than that (a gather that misses L2 moves a 128-byte line for 4 useful bytes); it is a
  * loss for banded or otherwise local matrices.  psk_analyze_csr suggests a value.  Results stay

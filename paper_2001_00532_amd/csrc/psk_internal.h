@@ -7,12 +7,14 @@
 namespace psk {
 
 // Workspace carving: [tile_row: ntiles+1 int32][carry_row: ntiles int32][carry_val: ntiles*width float]
-// [tile_aux: ntiles+1 int32 (second table of a two-level cut)], each part starting on a 256-byte boundary.
+// [tile_aux: ntiles+1 int32 (second table of a two-level cut)][tile_cols: ntiles*8 int32 (column range of each
+// tile, one min/max pair per wave, written by the first column pass)], each part starting on a 256-byte boundary.
 struct Workspace {
     int32_t *tile_row;
     int32_t *carry_row;
     float   *carry_val;
     int32_t *tile_aux;
+    int32_t *tile_cols;
     size_t   bytes;
 };
 inline size_t align256(size_t n) { return (n + 255) & ~size_t(255); }
@@ -25,8 +27,10 @@ inline Workspace carve(void *base, int64_t ntiles, int64_t width)
     w.tile_row = reinterpret_cast<int32_t *>(p);
     w.carry_row = reinterpret_cast<int32_t *>(p + a);
     w.carry_val = reinterpret_cast<float *>(p + a + b);
+    const size_t d = align256(size_t(ntiles) * 32 + 4);
     w.tile_aux = reinterpret_cast<int32_t *>(p + a + b + c);
-    w.bytes = a + b + c + a;
+    w.tile_cols = reinterpret_cast<int32_t *>(p + a + b + c + a);
+    w.bytes = a + b + c + a + d;
     return w;
 }
 

@@ -75,7 +75,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
                                                       const int *__restrict__ tile_row,
                                                       int *__restrict__ carry_row,
                                                       float *__restrict__ carry_val, int ntiles, int clo,
-                                                      int chi, int accum, const int *__restrict__ rowmap)
+                                                      int chi, int accum, const int *__restrict__ rowmap,
+                                                      int *__restrict__ tile_cols)
 {
     constexpr int T = THREADS * NPT;
     constexpr int NW = THREADS / WAVE;
@@ -97,6 +98,18 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
     const int t0 = t * T;
     const int cnt = (nnz - t0 < T) ? nnz - t0 : T;
     const int t1 = t0 + cnt;
+
+    // A later column pass leaves at once when the first pass found no column of this tile in its window
+    // (tiles inside a long sorted row lie in one window only).  The price is one dependent load ahead of
+    // the streams for the tiles that stay.
+    if (WIN && accum) {
+        const v4i a = *reinterpret_cast<const v4i *>(tile_cols + (long long)t * 8);
+        const v4i b = *reinterpret_cast<const v4i *>(tile_cols + (long long)t * 8 + 4);
+        int mn = a.x < a.z ? a.x : a.z, mx = a.y > a.w ? a.y : a.w;
+        mn = b.x < mn ? b.x : mn; mn = b.z < mn ? b.z : mn;
+        mx = b.y > mx ? b.y : mx; mx = b.w > mx ? b.w : mx;
+        if (mx < clo || mn >= chi) return;
+    }
 
     // Issue order matters more than anything else here: the tile's row bounds hang off a chain of
     // dependent loads (tile_row -> pos), so that chain is started first and runs underneath the
@@ -204,6 +217,40 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
         }
     }
 
+    if (WIN && !accum) {    // first column pass: leave the tile's column range for the later ones
+        int mn = 0x7fffffff, mx = -1;
+        if (full) {
+            if (MODE == 1) {
+#pragma unroll
+                for (int g = 0; g < NPT / 4; ++g) {
+                    const int lo4 = min(min(cv[g].x, cv[g].y), min(cv[g].z, cv[g].w));
+                    const int hi4 = max(max(cv[g].x, cv[g].y), max(cv[g].z, cv[g].w));
+                    mn = min(mn, lo4);
+                    mx = max(mx, hi4);
+                }
+            } else {
+#pragma unroll
+                for (int g = 0; g < NPT; ++g) { mn = min(mn, cs[g]); mx = max(mx, cs[g]); }
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < NPT; ++g) {
+                const int i = tile_index<MODE, THREADS>(g, tid);
+                if (i < cnt) { const int c = crd[t0 + i]; mn = min(mn, c); mx = max(mx, c); }
+            }
+        }
+#pragma unroll
+        for (int m = 1; m < WAVE; m <<= 1) {
+            mn = min(mn, __shfl_xor(mn, m, WAVE));
+            mx = max(mx, __shfl_xor(mx, m, WAVE));
+        }
+        if (lane == 0) {
+            tile_cols[(long long)t * 8 + 2 * wave] = mn;
+            tile_cols[(long long)t * 8 + 2 * wave + 1] = mx;
+        }
+        if (tid < 2 * (4 - NW)) tile_cols[(long long)t * 8 + 2 * NW + tid] = (tid & 1) ? -1 : 0x7fffffff;
+    }
+
     const bool has_carry = (t > 0) && (p_r0 < t0);
     const int rend = (p_r1 == t1) ? r1 : r1 + 1;   // last tile: r1 = rows and pos[rows] = nnz = t1
     if (tid == 0 && !has_carry && !ATOM) carry_row[t] = -1;
@@ -296,7 +343,8 @@ static void launch_pos(int mode, int grid, hipStream_t s, int rows, int cols, in
 {
 #define PSK_GO(M, W)                                                                                             \
     hipLaunchKernelGGL((k_spmv_pos<THREADS, NPT, M, W>), dim3(grid), dim3(THREADS), 0, s, rows, cols, nnz, pos,  \
-                       crd, vals, x, y, w.tile_row, w.carry_row, w.carry_val, ntiles, clo, chi, accum, rowmap)
+                       crd, vals, x, y, w.tile_row, w.carry_row, w.carry_val, ntiles, clo, chi, accum, rowmap,    \
+                       w.tile_cols)
     const bool window = clo > 0 || chi < cols;
     const int variant = rowmap ? (window ? 5 : 4) : (accum >= 2 ? accum : (window ? 1 : 0));
     if (variant == 3) PSK_GO(0, 3);
