@@ -18,6 +18,8 @@ Workloads (names of the evaluated configurations):
   bcsr_spmm           BCSR 4x4 SpMM with 64 dense columns
   uniform28           CSR SpMV, 2M x 2M, exactly 28 per row at uniform random columns (the uniform
                       matrix of the power-law matrix's size class, for the per-nnz comparison)
+  spmm_dense32        CSR SpMM, 100k x 100k with 1000 random nonzeros per row times a dense 100k x 32 operand (the
+                      shape of the paper's locality experiment, Section 8.6)
   mttkrp              MTTKRP A(i,j) = B(i,k,l) C(k,j) D(l,j): B 500k x 100k x 100k in three compressed levels,
                       ~4M fibers, ~46M nonzeros (Zipf leaves per fiber), j = 64 (the paper's third kernel;
                       synthetic stand-in for the FROSTT tensors it uses)
@@ -66,6 +68,7 @@ WORKLOADS = {
     "bcsr_spmv": (5, "bcsr_spmv"),
     "bcsr_spmm": (5, "bcsr_spmm"),
     "uniform28": (0, "csr_spmv"),
+    "spmm_dense32": (0, "csr_spmm"),
     "mttkrp": (0, "mttkrp"),
     "dcsr": (0, "dcsr"),
     "fewlong": (0, "csr_spmv"),
@@ -331,6 +334,7 @@ def main():
                     help="--baselines: number of parts for the divided variant (repeatable; default 0 = 2048)")
     ap.add_argument("--cut", choices=["positions", "rows"], default="positions",
                     help="dcsr: level of the position cut (column level = equal nonzeros, row level = equal stored rows)")
+    ap.add_argument("--k", type=int, default=0, help="spmm workloads: number of dense columns (0 = the configuration's)")
     ap.add_argument("--bs", type=int, default=4, choices=[2, 4, 8],
                     help="bcsr_spmv / bcsr_spmm: block edge (the 10^6 x 10^6 matrix with 32 entries per row is re-blocked)")
     ap.add_argument("--f64", action="store_true", help="CSR SpMV workloads: fp64 values, vector and result")
@@ -363,6 +367,9 @@ def main():
     if args.workload == "uniform28":
         A28 = wl.csr_uniform(2_000_000, 2_000_000, 28, wl.BASE_SEED + 6)
         cfg = {"A": A28, "x": wl.dense_uniform(2_000_000, wl.BASE_SEED + 6, wl.S_X)}
+    elif args.workload == "spmm_dense32":
+        As = wl.csr_uniform(100_000, 100_000, 1000, wl.BASE_SEED + 12)
+        cfg = {"A": As, "k": 32, "B": wl.dense_uniform(100_000 * 32, wl.BASE_SEED + 12, wl.S_B).reshape(100_000, 32)}
     elif args.workload == "fewlong":
         Af = wl.csr_uniform(100, 100_000, 10_000, wl.BASE_SEED + 7)
         cfg = {"A": Af, "x": wl.dense_uniform(100_000, wl.BASE_SEED + 7, wl.S_X)}
@@ -379,6 +386,9 @@ def main():
         cfg = wl.config(cfg_no)
     A = cfg["A"]
     k = cfg.get("k", 1) if kind.endswith("spmm") else 1
+    if kind.endswith("spmm") and args.k and args.k != k:     # same matrix, another width of the dense operand
+        k = args.k
+        cfg["B"] = wl.dense_uniform(A.cols * A.bs * k, wl.BASE_SEED + cfg_no, wl.S_B).reshape(A.cols * A.bs, k)
     dense_h = cfg["B"] if kind.endswith("spmm") else cfg["x"]
     f64 = args.f64
     if f64 and kind != "csr_spmv":

@@ -196,7 +196,8 @@ int psk_suggest_schedule_csr(int64_t rows, int64_t nnz, const int32_t *pos, void
  * C = A B, CSR A, position-space schedule (appendix "SPMM on a GPU"): positions are
  * split over workgroups and waves, the columns of B over the lanes of a wave, the
  * loop over a wave's positions is innermost.  B is cols x k with row stride ldb
- * (>= k), C is rows x k with row stride ldc (>= k), both in floats.  Any k >= 1.
+ * (>= k), C is rows x k with row stride ldc (>= k), both in floats.  Any k >= 1
+ * (k <= 32 runs a variant in which 2, 4 or 8 groups of lanes take consecutive positions).
  * tile in {0, 256, 512, 1024, 2048}.
  */
 int psk_spmm_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,

@@ -82,6 +82,10 @@ bool spmm_csr_tile_ok(int32_t tile);
 hipError_t launch_spmm_csr_main(int32_t rows, int32_t nnz, const int32_t *pos, const int32_t *crd,
                                 const float *vals, const float *B, int32_t k, int64_t ldb, float *C,
                                 int64_t ldc, int32_t tile, const Workspace &w, hipStream_t s);
+// k <= 32: the wave is split into groups that take consecutive positions
+hipError_t launch_spmm_csr_narrow(int32_t rows, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                                  const float *vals, const float *B, int32_t k, int64_t ldb, float *C, int64_t ldc,
+                                  int32_t tile, const Workspace &w, hipStream_t s);
 hipError_t launch_spmm_rowsplit(int32_t rows, const int32_t *pos, const int32_t *crd, const float *vals,
                                 const float *B, int32_t k, int64_t ldb, float *C, int64_t ldc,
                                 hipStream_t s);

@@ -258,6 +258,7 @@ hipError_t launch_spmm_csr_main(int32_t rows, int32_t nnz, const int32_t *pos, c
                                 const float *vals, const float *B, int32_t k, int64_t ldb, float *C,
                                 int64_t ldc, int32_t tile, const Workspace &w, hipStream_t s)
 {
+    if (k <= 32) return launch_spmm_csr_narrow(rows, nnz, pos, crd, vals, B, k, ldb, C, ldc, tile, w, s);
     return launch_spmm_pos<1>(rows, nnz, pos, crd, vals, B, k, ldb, C, ldc, tile, w, s);
 }
 
