@@ -62,7 +62,11 @@ hipError_t launch_partition_csf3(int32_t nslices, int32_t nfibers, int32_t nnz, 
 // two misses of the D gather costs bandwidth, because the vector memory pipeline returns in order.
 // Segments, records, carries: as in the SpMM kernel (the first and last open segments of each wave are
 // chained by wave 0; a chain whose slice began before the tile becomes the tile's carry record).
-template <int VEC>
+// G > 1 (narrow factor matrices, j <= 64/G, VEC = 1): the wave is split into G groups of 64/G lanes and in one
+// step the groups take G consecutive leaves, so that one load instruction fetches G rows of D.  A lane keeps
+// its group's share of the open fiber and of the open slice; a fiber end multiplies every share by the C row
+// (no exchange needed: the product distributes over the shares), a slice end adds the shares across groups.
+template <int VEC, int G>
 __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const int *__restrict__ crd_i,
                                                     const int *__restrict__ pos_k,
                                                     const int *__restrict__ crd_k,
@@ -77,7 +81,9 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
                                                     int *__restrict__ carry_row,
                                                     float *__restrict__ carry_val, int ntiles, int T)
 {
-    constexpr int THREADS = 256, NW = THREADS / WAVE, KW = WAVE * VEC, U = (VEC == 4 ? 4 : 8), LONGF = 32;
+    static_assert(G == 1 || VEC == 1, "lane groups only with one column per lane");
+    constexpr int THREADS = 256, NW = THREADS / WAVE, GW = WAVE / G, KW = GW * VEC, LONGF = 32;
+    constexpr int U = G > 1 ? 4 : (VEC == 4 ? 4 : 8);   // steps whose D rows are in flight together
     extern __shared__ int smeta[];                // sflag[T], sk[T], long-fiber queue [3 * T / LONGF]
     int *sflag = smeta, *sk = smeta + T, *slong = smeta + 2 * T;
     __shared__ float srec[2 * NW][KW];
@@ -91,8 +97,10 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
     const int t0 = t * T;
     const int cnt = (nnz - t0 < T) ? nnz - t0 : T;
     const int t1 = t0 + cnt;
-    const int col = blockIdx.y * KW + lane * VEC;
+    const int g = lane / GW, gl = lane % GW;      // group of the lane, lane inside the group (G = 1: 0, lane)
+    const int col = blockIdx.y * KW + gl * VEC;
     const bool active = col < jdim;
+    const bool writer = active && g == 0;         // group 0 stores on behalf of the wave
     const int lcol = active ? col : 0;            // lanes past the last column load column 0 and store nothing
 
     for (int i = tid; i < T; i += THREADS) { sflag[i] = -1; sk[i] = 0; }
@@ -123,7 +131,7 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
         while (empty) {
             const int j = __ffsll((long long)empty) - 1;
             empty &= empty - 1;
-            if (active) {
+            if (writer) {
                 const float z[VEC] = {};
                 const long long row = crd_i ? crd_i[rb + j] : rb + j;
                 st_vec<VEC>(A + row * lda + col, z);
@@ -161,13 +169,20 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
     float facc[VEC] = {};                         // sum of b * D(l, :) over the leaves of the open fiber
     bool seen = false;
 
-    auto flush = [&](int f) {
+    auto group_sum = [&](float v) {               // sum over the G lanes that hold the same column
+#pragma unroll
+        for (int m = GW; m < WAVE; m <<= 1) v += __shfl_xor(v, m, WAVE);
+        return v;
+    };
+    auto flush = [&](int f) {                     // G > 1: acc already holds the sum over the groups
         if (!seen) {
             seen = true;
+            if (g == 0) {
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) srec[2 * wave][lane * VEC + v] = acc[v];
+                for (int v = 0; v < VEC; ++v) srec[2 * wave][gl * VEC + v] = acc[v];
+            }
             if (lane == 0) srec_row[2 * wave] = f;
-        } else if (active) {
+        } else if (writer) {
             const long long row = crd_i ? crd_i[f] : f;
             st_vec<VEC>(A + row * lda + col, acc);
         }
@@ -195,6 +210,44 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
         const int f_l = lane < n ? sflag[base + lane] : -1;
         fetch(base + WAVE);
         if (base + lane == wend - 1 && k_l >= 0) k_l = ~k_l;   // the wave's last leaf closes its fiber's partial sum
+        if constexpr (G > 1) {
+        for (int j0 = 0; j0 < n; j0 += U * G) {
+            float c[U], d[U], a[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int jj = (j0 + u * G + g) & (WAVE - 1);      // this group's leaf in step u
+                const long long ll = __shfl(l_l, jj, WAVE);        // lanes past n hold coordinate 0, value 0, no flag
+                const int ke = __shfl(k_l, jj, WAVE);
+                a[u] = __shfl(v_l, jj, WAVE);
+                c[u] = 0.0f;
+                if (ke < 0) c[u] = C[(long long)(~ke) * ldc + lcol];   // this group's leaf closes a fiber
+                d[u] = D[ll * ldd + lcol];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int s0 = j0 + u * G;                          // first leaf of the step
+                if (s0 < n) {
+                    const float term = (s0 + g < n) ? a[u] * d[u] : 0.0f;
+                    bool added = false;
+#pragma unroll
+                    for (int e = 0; e < G; ++e) {
+                        if (rl(k_l, (s0 + e) & (WAVE - 1)) < 0) {   // leaf s0 + e is the last of its fiber
+                            if (!added && g <= e) { facc[0] += term; added = true; }
+                            const float ce = __shfl(c[u], e * GW + gl, WAVE);   // the C row group e fetched
+                            acc[0] = fmaf(ce, facc[0], acc[0]);
+                            facc[0] = 0.0f;
+                            const int f = rl(f_l, (s0 + e) & (WAVE - 1));
+                            if (f >= 0) {                           // ... and of its slice
+                                acc[0] = group_sum(acc[0]);
+                                flush(f);
+                            }
+                        }
+                    }
+                    if (!added) facc[0] += term;
+                }
+            }
+        }
+        } else {
         for (int j0 = 0; j0 < n; j0 += U) {
             float c[U][VEC], d[U][VEC];
 #pragma unroll
@@ -227,17 +280,21 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
                 }
             }
         }
+        }
     }
     if (wbeg < wend) {
         const int slot = seen ? 2 * wave + 1 : 2 * wave;
+        if constexpr (G > 1) acc[0] = group_sum(acc[0]);
+        if (g == 0) {
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) srec[slot][lane * VEC + v] = acc[v];
+            for (int v = 0; v < VEC; ++v) srec[slot][gl * VEC + v] = acc[v];
+        }
         if (lane == 0) srec_row[slot] = -1;
     }
     __syncthreads();
 
-    // ---- chain the records (wave 0)
-    if (wave != 0) return;
+    // ---- chain the records (wave 0, group 0)
+    if (wave != 0 || g != 0) return;
     float run[VEC] = {};
     auto finalize = [&](int r) {
         if (has_carry && r == r0) {
@@ -257,7 +314,7 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
         const int code = srec_row[rec];
         if (code == -2) continue;
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) run[v] += srec[rec][lane * VEC + v];
+        for (int v = 0; v < VEC; ++v) run[v] += srec[rec][gl * VEC + v];
         if (code >= 0) finalize(code);
     }
     if (straddle) finalize(r1);
@@ -277,16 +334,20 @@ hipError_t launch_mttkrp_main(int32_t nslices, int32_t nnz, const int32_t *crd_i
     int vec = 1;
     if (j > 64 && j % 2 == 0 && ldc % 2 == 0 && ldd % 2 == 0 && lda % 2 == 0 && (al & 7) == 0) vec = 2;
     if (j > 128 && j % 4 == 0 && ldc % 4 == 0 && ldd % 4 == 0 && lda % 4 == 0 && (al & 15) == 0) vec = 4;
-    const int kw = WAVE * vec;
+    const int groups = j <= 8 ? 8 : (j <= 16 ? 4 : (j <= 32 ? 2 : 1));
+    const int kw = WAVE * vec / groups;
     const dim3 grid(xcd_grid(ntiles), (j + kw - 1) / kw);
     const size_t lds = ((size_t)2 * tile + 3 * (size_t)(tile / 32)) * sizeof(int);
-#define PSK_GO(V)                                                                                               \
-    hipLaunchKernelGGL((k_mttkrp_pos<V>), grid, dim3(256), lds, s, nslices, nnz, crd_i, pos_k, crd_k, pos_l, crd_l, \
-                       vals, C, (long long)ldc, D, (long long)ldd, j, A, (long long)lda, w.tile_row, tile_fiber,    \
-                       w.carry_row, w.carry_val, ntiles, tile)
-    if (vec == 4) PSK_GO(4);
-    else if (vec == 2) PSK_GO(2);
-    else PSK_GO(1);
+#define PSK_GO(V, GG)                                                                                           \
+    hipLaunchKernelGGL((k_mttkrp_pos<V, GG>), grid, dim3(256), lds, s, nslices, nnz, crd_i, pos_k, crd_k, pos_l,    \
+                       crd_l, vals, C, (long long)ldc, D, (long long)ldd, j, A, (long long)lda, w.tile_row,         \
+                       tile_fiber, w.carry_row, w.carry_val, ntiles, tile)
+    if (groups == 8) PSK_GO(1, 8);
+    else if (groups == 4) PSK_GO(1, 4);
+    else if (groups == 2) PSK_GO(1, 2);
+    else if (vec == 4) PSK_GO(4, 1);
+    else if (vec == 2) PSK_GO(2, 1);
+    else PSK_GO(1, 1);
 #undef PSK_GO
     return hipGetLastError();
 }
