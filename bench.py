@@ -57,7 +57,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("powerlaw_f64", 1024, 1): 5796716538,  # profiles/k_spmv_pos_f64_powerlaw.txt
     ("stencil_f64", 1024, 1): 1405408380,   # profiles/k_spmv_pos_f64_stencil.txt
     ("dcsr", 2048, 1): 1605536491 + 268435456 + 20685,   # profiles/k_spmv_pos_dcsr_hypersparse.txt: tile kernel + zero-fill of y
-    ("mttkrp", 2048, 1): 11818248693,      # profiles/k_mttkrp_pos_mttkrp_j64.txt (L2 <-> fabric, j = 64)
+    ("mttkrp", 2048, 1): 11818221152,      # profiles/k_mttkrp_pos_mttkrp_j64.txt (L2 <-> fabric, j = 64)
 }
 
 WORKLOADS = {
