@@ -285,8 +285,17 @@ __global__ __launch_bounds__(256) void k_carry_fixup(int ntiles, int width, int 
                                                      float *__restrict__ out)
 {
     const long long g = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (g >= (long long)ntiles * width) return;
-    const int t = (int)(g / width), e = (int)(g % width);
+    const long long total = (long long)ntiles * width;
+    if (g >= total) return;
+    int t, e;
+    if (total <= 0xffffffffll) {          // the usual case: a 32-bit division is several times cheaper
+        const unsigned gg = (unsigned)g;
+        t = (int)(gg / (unsigned)width);
+        e = (int)(gg - (unsigned)t * (unsigned)width);
+    } else {
+        t = (int)(g / width);
+        e = (int)(g % width);
+    }
     const int r = carry_row[t];
     if (r < 0) return;
     if (t > 0 && carry_row[t - 1] == r) return;
