@@ -47,17 +47,17 @@ HBM_PEAK_GBS = 8000.0
 # scaled by the copy-kernel calibration; the summaries are under profiles/.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
     # (workload, tile, col_passes): bytes per launch of the tile kernel
-    ("powerlaw", 1024, 2): 629234768,      # profiles/k_spmv_pos_powerlaw_2passes.txt
-    ("powerlaw", 2048, 1): 3559074828,     # profiles/k_spmv_pos_powerlaw_1pass.txt
-    ("uniform28", 1024, 2): 698287113,     # profiles/k_spmv_pos_uniform28.txt
-    ("stencil", 2048, 1): 929631325,       # profiles/k_spmv_pos_stencil.txt
-    ("spmm", 512, 1): 8775522994,          # profiles/k_spmm_pos_csr_spmm_k128.txt
-    ("bcsr_spmv", 512, 1): 191661400,      # profiles/k_spmv_bcsr4_bcsr_spmv.txt
-    ("bcsr_spmm", 64, 1): 2411765634,      # profiles/k_spmm_pos_bcsr_spmm_n64.txt
-    ("powerlaw_f64", 1024, 1): 5796716538,  # profiles/k_spmv_pos_f64_powerlaw.txt
-    ("stencil_f64", 1024, 1): 1405408380,   # profiles/k_spmv_pos_f64_stencil.txt
-    ("dcsr", 2048, 1): 1605536491 + 268435456 + 20685,   # profiles/k_spmv_pos_dcsr_hypersparse.txt: tile kernel + zero-fill of y
-    ("mttkrp", 2048, 1): 11818221152,      # profiles/k_mttkrp_pos_mttkrp_j64.txt (L2 <-> fabric, j = 64)
+    ("powerlaw", 1024, 2): 629236071,      # profiles/k_spmv_pos_powerlaw_2passes.txt
+    ("powerlaw", 2048, 1): 3558251794,     # profiles/k_spmv_pos_powerlaw_1pass.txt
+    ("uniform28", 1024, 2): 697080350,     # profiles/k_spmv_pos_uniform28.txt
+    ("stencil", 2048, 1): 929627715,       # profiles/k_spmv_pos_stencil.txt
+    ("spmm", 512, 1): 8775506057,          # profiles/k_spmm_pos_csr_spmm_k128.txt
+    ("bcsr_spmv", 512, 1): 191721313,      # profiles/k_spmv_bcsr4_bcsr_spmv.txt
+    ("bcsr_spmm", 64, 1): 2411752120,      # profiles/k_spmm_pos_bcsr_spmm_n64.txt
+    ("powerlaw_f64", 1024, 1): 5796620953,  # profiles/k_spmv_pos_f64_powerlaw.txt
+    ("stencil_f64", 1024, 1): 1405422169,   # profiles/k_spmv_pos_f64_stencil.txt
+    ("dcsr", 2048, 1): 1606172701 + 268435456 + 20685,   # profiles/k_spmv_pos_dcsr_hypersparse.txt: tile kernel + zero-fill of y
+    ("mttkrp", 2048, 1): 11818681536,      # profiles/k_mttkrp_pos_mttkrp_j64.txt (L2 <-> fabric, j = 64)
 }
 
 WORKLOADS = {
