@@ -624,6 +624,12 @@ def main():
                 oracle.spmm_bcsr(A.pos, A.crd, A.vals, dense_h, A.bs, sel=sel, threads=cores)
 
         tmed, nruns = time_cpu(run_oracle)
+        cores_all, cores = cores, 1
+        t1, n1 = time_cpu(run_oracle, budget_s=3.0, max_runs=5)      # the same oracle on one thread
+        cores = cores_all
+        rec["cpu_baseline_single_thread"] = {"value": round(fl * frac / t1 / 1e9, 3), "unit": "GFLOP/s", "cores": 1,
+                                             "kind": "oracle", "sample": "%s, 1 warm-up + %d runs, median %.3f s"
+                                                                         % (sample, n1, t1)}
         rec["cpu_baseline"] = {
             "value": round(fl * frac / tmed / 1e9, 3),
             "unit": "GFLOP/s",
