@@ -97,6 +97,16 @@ def algorithmic_bytes(kind, A, k):
     raise ValueError(kind)
 
 
+def input_hash(*arrays):
+    """Hash of the generated operands: the same seed must give the same bytes on every machine."""
+    import hashlib
+
+    h = hashlib.blake2b(digest_size=8)
+    for a in arrays:
+        h.update(np.ascontiguousarray(a).view(np.uint8).reshape(-1).data)
+    return h.hexdigest()
+
+
 def time_cpu(fn, budget_s=10.0, max_runs=25):
     """One warm-up call, then repeated calls for about budget_s seconds of CPU work (3..max_runs calls);
     returns (median seconds, calls)."""
@@ -512,6 +522,7 @@ def main():
             "rows": A.rows * A.bs, "cols": A.cols * A.bs, "nnz": A.nnz * A.bs * A.bs, "k": k, "tile": tile,
             "col_passes": col_passes,
             "seed": wl.BASE_SEED + cfg_no,
+            "input_hash": input_hash(A.pos, A.crd, vals_h, dense_h),
         },
         "gbps_algorithmic_whole_step": round(comp_bytes / (wall / args.steps) / 1e9, 2),
         "pct_of_hbm_peak_whole_step": round(100.0 * comp_bytes / (wall / args.steps) / 1e9 / HBM_PEAK_GBS, 2),

@@ -117,3 +117,18 @@ def test_from_lengths_edge_cases():
     check_structure(A)
     with pytest.raises(ValueError):
         wl.csr_from_lengths([6], 5, seed=1)
+
+
+def test_power_law_configuration_has_the_recorded_bytes():
+    """The generators are counter-based: the same seed gives the same bytes on every machine.  The hash is
+    the one bench.py prints for its default workload (computed by this repository's generators, not taken
+    from anywhere else)."""
+    import hashlib
+
+    c = wl.config(2)
+    A = c["A"]
+    h = hashlib.blake2b(digest_size=8)
+    for a in (A.pos, A.crd, A.vals, c["x"]):
+        h.update(np.ascontiguousarray(a).view(np.uint8).reshape(-1).data)
+    assert h.hexdigest() == "b182aa2126833ff2"
+    assert A.nnz == 56_486_638
