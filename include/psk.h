@@ -268,15 +268,16 @@ int psk_spmv_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t
 /*
  * y = A x with fp64 values, vector and result (the value type of the paper's own schedules: the
  * per-thread temporary of appendix "SPMV on a GPU" is Float64).  Same cut, tile kernel structure,
- * carry records (doubles) and fix-up as psk_spmv_csr; one pass; products and sums in fp64.
+ * carry records (doubles) and fix-up as psk_spmv_csr, column passes included (col_passes as there; x is
+ * twice as large per column, so slices of the same byte size hold half the columns); products and sums in fp64.
  * vals [nnz], x [cols], y [rows] doubles, 8-byte aligned (PSK_ERR_ALIGNMENT otherwise); crd and vals
  * 16-byte aligned selects the 16-byte load path.  tile in {0, 256, 512, 1024, 2048}, 0 = 1024.
  * Workspace from psk_workspace_bytes(PSK_OP_SPMV_CSR_F64, rows, nnz, 1, 1, tile).
  * Deterministic; |y - exact| <= 1e-14 * sum_j |a_ij x_j| per row.
  */
 int psk_spmv_csr_f64(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
-                     const double *vals, const double *x, double *y, int32_t tile, int phases,
-                     void *workspace, size_t workspace_bytes, void *stream);
+                     const double *vals, const double *x, double *y, int32_t tile, int32_t col_passes,
+                     int phases, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * y = A x with A in DCSR, the doubly compressed form for hypersparse matrices (Section 2 names it next

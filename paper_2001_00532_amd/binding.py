@@ -72,7 +72,7 @@ def lib() -> ctypes.CDLL:
         L.psk_spmv_csr_atomics.restype = ci
         L.psk_spmv_csr_notemp.argtypes = [i64, i64, i64, p, p, p, p, p, i32, ci, p, sz, p]
         L.psk_spmv_csr_notemp.restype = ci
-        L.psk_spmv_csr_f64.argtypes = [i64, i64, i64, p, p, p, p, p, i32, ci, p, sz, p]
+        L.psk_spmv_csr_f64.argtypes = [i64, i64, i64, p, p, p, p, p, i32, i32, ci, p, sz, p]
         L.psk_spmv_csr_f64.restype = ci
         L.psk_spmv_dcsr.argtypes = [i64, i64, i64, i64, p, p, p, p, p, p, ci, i32, i32, ci, p, sz, p]
         L.psk_spmv_dcsr.restype = ci
@@ -281,12 +281,13 @@ def psk_spmv_csr_atomics(rows, cols, nnz, pos, crd, vals, x, y, tile=0, phases=P
     return y
 
 
-def psk_spmv_csr_f64(rows, cols, nnz, pos, crd, vals, x, y, tile=0, phases=PSK_PHASE_ALL, ws=None, stream=None):
+def psk_spmv_csr_f64(rows, cols, nnz, pos, crd, vals, x, y, tile=0, col_passes=1, phases=PSK_PHASE_ALL, ws=None,
+                     stream=None):
     if ws is None:
         ws = workspace(PSK_OP_SPMV_CSR_F64, rows, nnz, tile=tile, device=pos.device)
     st = lib().psk_spmv_csr_f64(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                                 _ptr(vals, torch.float64), _ptr(x, torch.float64), _ptr(y, torch.float64),
-                                int(tile), int(phases), _ptr(ws), ws.numel(), _stream(stream))
+                                int(tile), int(col_passes), int(phases), _ptr(ws), ws.numel(), _stream(stream))
     _check(st, "psk_spmv_csr_f64")
     return y
 

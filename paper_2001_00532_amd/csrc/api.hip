@@ -216,9 +216,10 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
 }
 
 int psk_spmv_csr_f64(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
-                     const double *vals, const double *x, double *y, int32_t tile, int phases, void *workspace,
-                     size_t workspace_bytes, void *stream)
+                     const double *vals, const double *x, double *y, int32_t tile, int32_t col_passes, int phases,
+                     void *workspace, size_t workspace_bytes, void *stream)
 {
+    if (col_passes < 0 || col_passes > PSK_MAX_COL_PASSES) return PSK_ERR_SIZE;
     Workspace ws;
     int st = check_common(PSK_OP_SPMV_CSR_F64, rows, cols, nnz, pos, crd, vals, 1, 1, &tile, phases, workspace,
                           workspace_bytes, &ws);
@@ -232,7 +233,8 @@ int psk_spmv_csr_f64(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos
     if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, 0, ws.tile_row, s);
     if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
         if (ntiles == 0) e = launch_fill_zero(reinterpret_cast<float *>(y), 2 * rows, s);
-        else e = launch_spmv_csr_f64_main((int32_t)rows, (int32_t)nnz, pos, crd, vals, x, y, tile, ws, s);
+        else e = launch_spmv_csr_f64_main((int32_t)rows, (int32_t)cols, (int32_t)nnz, pos, crd, vals, x, y, tile, col_passes,
+                                          ws, s);
     }
     if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup_f64(ntiles, tile, pos, ws, y, s);
     return hip_status(e);

@@ -19,14 +19,18 @@ __device__ __forceinline__ double wave_sum_f64(double v)
 // One workgroup per tile of T = THREADS*NPT positions.  VEC: crd is read with 16-byte loads and vals
 // with two 16-byte loads per four positions (both arrays 16-byte aligned), a lane keeps four
 // consecutive positions; otherwise 4- and 8-byte loads at lane-consecutive positions.
-template <int THREADS, int NPT, bool VEC>
+// WIN: a column pass as in the fp32 kernel: only columns in [clo, chi) contribute, accum adds to what the
+// earlier passes stored; the first pass records the tile's column range, later passes skip tiles outside
+// their window.
+template <int THREADS, int NPT, bool VEC, bool WIN>
 __global__ __launch_bounds__(THREADS) void k_spmv_pos_f64(int rows, int nnz, const int *__restrict__ pos,
                                                           const int *__restrict__ crd,
                                                           const double *__restrict__ vals,
                                                           const double *__restrict__ x, double *__restrict__ y,
                                                           const int *__restrict__ tile_row,
                                                           int *__restrict__ carry_row,
-                                                          double *__restrict__ carry_val, int ntiles)
+                                                          double *__restrict__ carry_val, int ntiles, int clo,
+                                                          int chi, int accum, int *__restrict__ tile_cols)
 {
     constexpr int T = THREADS * NPT;
     constexpr int NW = THREADS / WAVE;
@@ -47,10 +51,20 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos_f64(int rows, int nnz, con
     const int t1 = t0 + cnt;
     auto index = [&](int g) { return VEC ? ((g / 4) * THREADS + tid) * 4 + (g & 3) : g * THREADS + tid; };
 
+    if (WIN && accum) {
+        const v4i a = *reinterpret_cast<const v4i *>(tile_cols + (long long)t * 8);
+        const v4i b = *reinterpret_cast<const v4i *>(tile_cols + (long long)t * 8 + 4);
+        int mn = a.x < a.z ? a.x : a.z, mx = a.y > a.w ? a.y : a.w;
+        mn = b.x < mn ? b.x : mn; mn = b.z < mn ? b.z : mn;
+        mx = b.y > mx ? b.y : mx; mx = b.w > mx ? b.w : mx;
+        if (mx < clo || mn >= chi) return;
+    }
+
     // the dependent chain tile_row -> pos is started first and runs underneath the streams
     const int r0 = tile_row[t], r1 = tile_row[t + 1];
 
     double prod[NPT];
+    int cmin = 0x7fffffff, cmax = -1;             // column range of the tile (first column pass)
     const bool full = cnt == T;
     if (full) {
         int c[NPT];
@@ -74,9 +88,13 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos_f64(int rows, int nnz, con
         }
         double xg[NPT];
 #pragma unroll
-        for (int g = 0; g < NPT; ++g) xg[g] = x[c[g]];
+        for (int g = 0; g < NPT; ++g) xg[g] = (!WIN || (c[g] >= clo && c[g] < chi)) ? x[c[g]] : 0.0;
 #pragma unroll
         for (int g = 0; g < NPT; ++g) prod[g] = v[g] * xg[g];
+        if (WIN && !accum) {
+#pragma unroll
+            for (int g = 0; g < NPT; ++g) { cmin = min(cmin, c[g]); cmax = max(cmax, c[g]); }
+        }
     }
 
     const int p_r0 = pos[r0], p_r1 = pos[r1];
@@ -91,8 +109,27 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos_f64(int rows, int nnz, con
 #pragma unroll
         for (int g = 0; g < NPT; ++g) {
             const int i = index(g);
-            prod[g] = i < cnt ? vals[t0 + i] * x[crd[t0 + i]] : 0.0;
+            double pr = 0.0;
+            if (i < cnt) {
+                const int c = crd[t0 + i];
+                cmin = min(cmin, c);
+                cmax = max(cmax, c);
+                if (!WIN || (c >= clo && c < chi)) pr = vals[t0 + i] * x[c];
+            }
+            prod[g] = pr;
         }
+    }
+    if (WIN && !accum) {
+#pragma unroll
+        for (int m = 1; m < WAVE; m <<= 1) {
+            cmin = min(cmin, __shfl_xor(cmin, m, WAVE));
+            cmax = max(cmax, __shfl_xor(cmax, m, WAVE));
+        }
+        if (lane == 0) {
+            tile_cols[(long long)t * 8 + 2 * wave] = cmin;
+            tile_cols[(long long)t * 8 + 2 * wave + 1] = cmax;
+        }
+        if (tid < 2 * (4 - NW)) tile_cols[(long long)t * 8 + 2 * NW + tid] = (tid & 1) ? -1 : 0x7fffffff;
     }
 
     const bool has_carry = (t > 0) && (p_r0 < t0);
@@ -101,9 +138,9 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos_f64(int rows, int nnz, con
     auto emit = [&](int r, double v) {
         if (has_carry && r == r0) {
             carry_row[t] = r;
-            carry_val[t] = v;
+            carry_val[t] = (WIN && accum) ? carry_val[t] + v : v;
         } else {
-            y[r] = v;
+            y[r] = (WIN && accum) ? y[r] + v : v;
         }
     };
 
@@ -161,32 +198,38 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos_f64(int rows, int nnz, con
 bool spmv_csr_f64_tile_ok(int32_t tile) { return tile == 256 || tile == 512 || tile == 1024 || tile == 2048; }
 
 template <int THREADS, int NPT>
-static void go(bool vec, int grid, hipStream_t s, int rows, int nnz, const int *pos, const int *crd, const double *vals,
-               const double *x, double *y, const Workspace &w, int ntiles)
+static void go(bool vec, bool win, int grid, hipStream_t s, int rows, int nnz, const int *pos, const int *crd,
+               const double *vals, const double *x, double *y, const Workspace &w, int ntiles, int clo, int chi, int accum)
 {
     double *cv = reinterpret_cast<double *>(w.carry_val);
-    if (vec)
-        hipLaunchKernelGGL((k_spmv_pos_f64<THREADS, NPT, true>), dim3(grid), dim3(THREADS), 0, s, rows, nnz, pos, crd, vals,
-                           x, y, w.tile_row, w.carry_row, cv, ntiles);
-    else
-        hipLaunchKernelGGL((k_spmv_pos_f64<THREADS, NPT, false>), dim3(grid), dim3(THREADS), 0, s, rows, nnz, pos, crd,
-                           vals, x, y, w.tile_row, w.carry_row, cv, ntiles);
+#define PSK_GO(V, W)                                                                                                  \
+    hipLaunchKernelGGL((k_spmv_pos_f64<THREADS, NPT, V, W>), dim3(grid), dim3(THREADS), 0, s, rows, nnz, pos, crd, vals, \
+                       x, y, w.tile_row, w.carry_row, cv, ntiles, clo, chi, accum, w.tile_cols)
+    if (vec) { if (win) PSK_GO(true, true); else PSK_GO(true, false); }
+    else { if (win) PSK_GO(false, true); else PSK_GO(false, false); }
+#undef PSK_GO
 }
 
-hipError_t launch_spmv_csr_f64_main(int32_t rows, int32_t nnz, const int32_t *pos, const int32_t *crd,
-                                    const double *vals, const double *x, double *y, int32_t tile, const Workspace &w,
-                                    hipStream_t s)
+hipError_t launch_spmv_csr_f64_main(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                                    const double *vals, const double *x, double *y, int32_t tile, int32_t col_passes,
+                                    const Workspace &w, hipStream_t s)
 {
     const int ntiles = (int)(((int64_t)nnz + tile - 1) / tile);
     if (ntiles == 0) return hipSuccess;
     const int grid = xcd_grid(ntiles);
     const bool vec = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
-    switch (tile) {
-        case 256:  go<64, 4>(vec, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles); break;
-        case 512:  go<128, 4>(vec, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles); break;
-        case 1024: go<256, 4>(vec, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles); break;
-        case 2048: go<256, 8>(vec, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles); break;
-        default: return hipErrorInvalidValue;
+    if (col_passes < 1) col_passes = 1;
+    for (int p = 0; p < col_passes; ++p) {
+        const int clo = (int)((int64_t)cols * p / col_passes), chi = (int)((int64_t)cols * (p + 1) / col_passes);
+        const bool win = col_passes > 1;
+        const int accum = p > 0;
+        switch (tile) {
+            case 256:  go<64, 4>(vec, win, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
+            case 512:  go<128, 4>(vec, win, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
+            case 1024: go<256, 4>(vec, win, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
+            case 2048: go<256, 8>(vec, win, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
+            default: return hipErrorInvalidValue;
+        }
     }
     return hipGetLastError();
 }

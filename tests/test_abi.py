@@ -96,9 +96,10 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.psk_mttkrp_csf3(4, 4, 4, 4, 4, 4, null, one, one, one, one, one, one, 8, one, 8, 8, one, 8, 100, 7, one, big, null) == 3
     assert L.psk_partition_csf3(4, 4, 4, null, one, 4, one, one, null) == 1
     assert L.psk_partition_csf3(4, 4, 4, one, one, 0, one, one, null) == 3
-    assert L.psk_spmv_csr_f64(4, 4, 4, one, one, one, one, null, 0, 7, one, big, null) == 1
-    assert L.psk_spmv_csr_f64(4, 4, 4, one, one, ctypes.c_void_p(260), one, one, 0, 7, one, big, null) == 7
-    assert L.psk_spmv_csr_f64(4, 4, 4, one, one, one, one, one, 4096, 7, one, big, null) == 3
+    assert L.psk_spmv_csr_f64(4, 4, 4, one, one, one, one, null, 0, 1, 7, one, big, null) == 1
+    assert L.psk_spmv_csr_f64(4, 4, 4, one, one, ctypes.c_void_p(260), one, one, 0, 1, 7, one, big, null) == 7
+    assert L.psk_spmv_csr_f64(4, 4, 4, one, one, one, one, one, 4096, 1, 7, one, big, null) == 3
+    assert L.psk_spmv_csr_f64(4, 4, 4, one, one, one, one, one, 0, 7, 7, one, big, null) == 2          # col_passes
     assert L.psk_spmv_dcsr(8, 4, 9, 4, one, one, one, one, one, one, 0, 0, 1, 7, one, big, null) == 2      # nstored > rows
     assert L.psk_spmv_dcsr(8, 4, 2, 4, null, one, one, one, one, one, 0, 0, 1, 7, one, big, null) == 1
     assert L.psk_spmv_dcsr(8, 4, 2, 4, one, one, one, one, one, one, 2, 0, 1, 7, one, big, null) == 5      # cut

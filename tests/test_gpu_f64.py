@@ -27,7 +27,7 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def run(name, A, tile, offset=0):
+def run(name, A, tile, offset=0, passes=1):
     vals = wl.dense_uniform_f64(A.nnz, 5, wl.S_VALS)
     x = wl.dense_uniform_f64(A.cols, 6, wl.S_X)
     ref, mag = oracle.spmv_csr_f64(A.pos, A.crd, vals, x, threads=8)
@@ -39,8 +39,8 @@ def run(name, A, tile, offset=0):
     else:
         crd_d, vals_d = dev(A.crd), dev(vals)
     y = torch.full((A.rows,), float("nan"), dtype=torch.float64, device="cuda")
-    say("f64", name, "tile", tile, "offset", offset, "rows", A.rows, "nnz", A.nnz)
-    psk.psk_spmv_csr_f64(A.rows, A.cols, A.nnz, dev(A.pos), crd_d, vals_d, dev(x), y, tile=tile)
+    say("f64", name, "tile", tile, "offset", offset, "passes", passes, "rows", A.rows, "nnz", A.nnz)
+    psk.psk_spmv_csr_f64(A.rows, A.cols, A.nnz, dev(A.pos), crd_d, vals_d, dev(x), y, tile=tile, col_passes=passes)
     torch.cuda.synchronize()
     ok, worst = oracle.within_tolerance(y.cpu().numpy(), ref, mag, REL, FLOOR)
     assert ok, "%s tile %d: worst |err|/bound = %.3g" % (name, tile, worst)
@@ -55,6 +55,17 @@ def test_f64_structures(tile):
         run(kind, A, tile)
     run("powerlaw", wl.config(2, 0.01)["A"], tile)
     run("stencil", wl.config(3, 0.01)["A"], tile)
+
+
+@pytest.mark.parametrize("passes", [2, 3, 4])
+def test_f64_column_passes(passes):
+    rng = np.random.default_rng(23)
+    for kind in ADVERSARIAL_KINDS:
+        A = wl.csr_from_lengths(adversarial_lengths(rng, 3001, 5003, kind), 5003, seed=23)
+        for tile in (0, 256, 2048):
+            run(kind, A, tile, passes=passes)
+    run("powerlaw", wl.config(2, 0.01)["A"], 1024, passes=passes)
+    run("unaligned", wl.config(2, 0.005)["A"], 512, offset=1, passes=passes)
 
 
 def test_f64_unaligned_and_edges():
@@ -89,7 +100,7 @@ def test_f64_full_size_powerlaw_sampled():
     x = wl.dense_uniform_f64(A.cols, 6, wl.S_X)
     y = torch.full((A.rows,), float("nan"), dtype=torch.float64, device="cuda")
     say("f64 full size", A.rows, A.nnz)
-    psk.psk_spmv_csr_f64(A.rows, A.cols, A.nnz, dev(A.pos), dev(A.crd), dev(vals), dev(x), y)
+    psk.psk_spmv_csr_f64(A.rows, A.cols, A.nnz, dev(A.pos), dev(A.crd), dev(vals), dev(x), y, col_passes=3)
     torch.cuda.synchronize()
     assert not torch.isnan(y).any()
     lens = np.diff(A.pos)
