@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void k_mttkrp_pos(int nslices, int nnz, const 
         for (int v = 0; v < VEC; ++v) acc[v] = 0.0f;
     };
 
-    // crd_l and vals of 64 leaves, one per lane; requested one round ahead of their use
+    // crd_l and vals of 64 leaves, one per lane; requested one batch ahead of their use
     int l_n = 0;
     float v_n = 0.0f;
     auto fetch = [&](int base) {

@@ -110,7 +110,7 @@ __global__ __launch_bounds__(256) void k_spmm_pos(int rows, int nnz, const int *
             for (int v = 0; v < VEC; ++v) acc[ii][v] = 0.0f;
     };
 
-    // crd and vals of 64 positions, one per lane; requested one round ahead of their use
+    // crd and vals of 64 positions, one per lane; requested one batch ahead of their use
     int c_n = 0;
     float v_n[BS * BS];
     auto fetch = [&](int base) {
