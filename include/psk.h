@@ -111,8 +111,8 @@ int32_t psk_default_tile_bcsr(int op, int32_t bs);
 int64_t psk_num_tiles(int64_t nnz, int32_t tile);
 
 /*
- * Bytes of workspace an operation needs (tile-row table + one carry record per
- * tile).  `k` is the number of dense columns (ignored for SpMV), `bs` the BCSR
+ * Bytes of workspace an operation needs (tile-row table, one carry record per
+ * tile, a second table for the two-level cut, one column range per tile and wave).  `k` is the number of dense columns (ignored for SpMV), `bs` the BCSR
  * block edge (ignored for CSR), `tile` as passed to the operation (0 = default).
  * Returns 0 on invalid arguments.  Always at least 256.
  */
@@ -145,8 +145,8 @@ int psk_partition_csr(int64_t rows, int64_t nnz, const int32_t *pos, int32_t til
  * col_passes (0 or 1 = off, at most PSK_MAX_COL_PASSES): the main step is run that many times, pass q
  * gathering only the columns of the q-th equal slice of [0, cols) and adding to what the earlier passes
  * stored (the first pass records each tile's column range, and a later pass leaves a tile whose range
- * misses its window untouched).  A and the row bounds are streamed once per pass; in exchange the slice of x a pass gathers
- * from can stay in the 4 MB L2 of a die.  Worth it only for matrices whose columns are scattered over
+ * misses its window untouched).  A and the row bounds are streamed once per pass; in exchange the slice
+ * of x a pass gathers from can stay in the 4 MB L2 of a die.  Worth it only for matrices whose columns are scattered over
  * an x larger than that (a gather that misses L2 moves a 128-byte line for 4 useful bytes); it is a
  * loss for banded or otherwise local matrices.  psk_analyze_csr suggests a value.  Results stay
  * deterministic; they differ from the single-pass result within the usual fp32 reassociation.
@@ -160,8 +160,8 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
  * can be kept).  Answers 1 when x fits a die's L2 or the matrix is small; otherwise it samples up to
  * 16384 positions and, if fewer than half of them have their successor's column in the same 128-byte
  * line of x, suggests ceil(4*cols bytes / 6 MiB), at most PSK_MAX_COL_PASSES.
- * `col_passes` is a HOST pointer.  Unlike every other call this one SYNCHRONISES `stream` (it reads the
- * sample count back); `workspace` needs 256 bytes.
+ * `col_passes` is a HOST pointer.  This call SYNCHRONISES `stream` when it samples (it reads the count
+ * back); `workspace` needs 256 bytes.
  */
 #define PSK_MAX_COL_PASSES 4
 int psk_analyze_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
