@@ -139,12 +139,23 @@ def psk_workspace_bytes(op: int, rows: int, nnz: int, k: int = 1, bs: int = 1, t
     return int(lib().psk_workspace_bytes(int(op), int(rows), int(nnz), int(k), int(bs), int(tile)))
 
 
-def workspace(op: int, rows: int, nnz: int, k: int = 1, bs: int = 1, tile: int = 0, device="cuda"):
-    """A byte tensor of the size the operation needs (torch allocations are 256-byte aligned)."""
+def workspace(op: int, rows: int, nnz: int, k: int = 1, bs: int = 1, tile: int = 0, device="cuda", stream=None):
+    """A byte tensor of the size the operation needs (torch allocations are 256-byte aligned).
+
+    `stream`: the stream the kernels that use it will run on.  The block is allocated under that stream, so
+    torch's caching allocator hands it out again only to work that is ordered after those kernels; a
+    temporary workspace dropped right after an asynchronous call stays valid until the call has run."""
     n = psk_workspace_bytes(op, rows, nnz, k, bs, tile)
     if n == 0:
         raise ValueError("invalid arguments for psk_workspace_bytes")
-    return torch.empty(n, dtype=torch.uint8, device=device)
+    return _alloc_bytes(n, device, stream)
+
+
+def _alloc_bytes(n: int, device, stream=None):
+    if stream is None:
+        return torch.empty(n, dtype=torch.uint8, device=device)
+    with torch.cuda.stream(stream):
+        return torch.empty(n, dtype=torch.uint8, device=device)
 
 
 PSK_PARTITION_AUTO, PSK_PARTITION_SEARCH, PSK_PARTITION_SCAN = 0, 1, 2
@@ -165,7 +176,7 @@ def psk_partition_csr(pos, nnz: int, tile: int, method: int = 0, tile_row=None, 
 def psk_analyze_csr(rows, cols, nnz, pos, crd, ws=None, stream=None) -> int:
     """Suggested col_passes for psk_spmv_csr (synchronises the stream)."""
     if ws is None:
-        ws = torch.empty(256, dtype=torch.uint8, device=pos.device)
+        ws = _alloc_bytes(256, pos.device, stream)
     out = ctypes.c_int32(0)
     st = lib().psk_analyze_csr(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                                _ptr(ws), ws.numel(), ctypes.byref(out), _stream(stream))
@@ -177,7 +188,7 @@ def psk_validate_csr(rows, cols, nnz, pos, crd, ws=None, stream=None) -> int:
     """0 if the index structure is well formed, else the number (1..4) of the first failing condition
     (synchronises the stream)."""
     if ws is None:
-        ws = torch.empty(256, dtype=torch.uint8, device=pos.device)
+        ws = _alloc_bytes(256, pos.device, stream)
     out = ctypes.c_int32(-1)
     st = lib().psk_validate_csr(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                                 _ptr(ws), ws.numel(), ctypes.byref(out), _stream(stream))
@@ -188,7 +199,7 @@ def psk_validate_csr(rows, cols, nnz, pos, crd, ws=None, stream=None) -> int:
 def psk_suggest_schedule_csr(rows, nnz, pos, ws=None, stream=None) -> int:
     """PSK_SCHEDULE_POSITIONS or PSK_SCHEDULE_ROWS for y = A x on this matrix (may synchronise the stream)."""
     if ws is None:
-        ws = torch.empty(256, dtype=torch.uint8, device=pos.device)
+        ws = _alloc_bytes(256, pos.device, stream)
     out = ctypes.c_int32(-1)
     st = lib().psk_suggest_schedule_csr(int(rows), int(nnz), _ptr(pos, torch.int32), _ptr(ws), ws.numel(),
                                         ctypes.byref(out), _stream(stream))
@@ -199,7 +210,7 @@ def psk_suggest_schedule_csr(rows, nnz, pos, ws=None, stream=None) -> int:
 def psk_spmv_csr(rows, cols, nnz, pos, crd, vals, x, y, tile=0, col_passes=1, phases=PSK_PHASE_ALL, ws=None,
                  stream=None):
     if ws is None:
-        ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=tile, device=pos.device)
+        ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmv_csr(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                             _ptr(vals, torch.float32), _ptr(x, torch.float32), _ptr(y, torch.float32), int(tile),
                             int(col_passes), int(phases), _ptr(ws), ws.numel(), _stream(stream))
@@ -210,7 +221,7 @@ def psk_spmv_csr(rows, cols, nnz, pos, crd, vals, x, y, tile=0, col_passes=1, ph
 def psk_spmm_csr(rows, cols, nnz, pos, crd, vals, B, C, tile=0, phases=PSK_PHASE_ALL, ws=None, stream=None):
     k = B.shape[1]
     if ws is None:
-        ws = workspace(PSK_OP_SPMM_CSR, rows, nnz, k=k, tile=tile, device=pos.device)
+        ws = workspace(PSK_OP_SPMM_CSR, rows, nnz, k=k, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmm_csr(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                             _ptr(vals, torch.float32), _ptr(B, torch.float32), int(k), int(B.stride(0)),
                             _ptr(C, torch.float32), int(C.stride(0)), int(tile), int(phases), _ptr(ws),
@@ -222,7 +233,7 @@ def psk_spmm_csr(rows, cols, nnz, pos, crd, vals, B, C, tile=0, phases=PSK_PHASE
 def psk_spmv_bcsr(brows, bcols, nblocks, bs, pos, crd, vals, x, y, tile=0, phases=PSK_PHASE_ALL, ws=None,
                   stream=None):
     if ws is None:
-        ws = workspace(PSK_OP_SPMV_BCSR, brows, nblocks, bs=bs, tile=tile, device=pos.device)
+        ws = workspace(PSK_OP_SPMV_BCSR, brows, nblocks, bs=bs, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmv_bcsr(int(brows), int(bcols), int(nblocks), int(bs), _ptr(pos, torch.int32),
                              _ptr(crd, torch.int32), _ptr(vals, torch.float32), _ptr(x, torch.float32),
                              _ptr(y, torch.float32), int(tile), int(phases), _ptr(ws), ws.numel(), _stream(stream))
@@ -234,7 +245,7 @@ def psk_spmm_bcsr(brows, bcols, nblocks, bs, pos, crd, vals, B, C, tile=0, phase
                   stream=None):
     k = B.shape[1]
     if ws is None:
-        ws = workspace(PSK_OP_SPMM_BCSR, brows, nblocks, k=k, bs=bs, tile=tile, device=pos.device)
+        ws = workspace(PSK_OP_SPMM_BCSR, brows, nblocks, k=k, bs=bs, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmm_bcsr(int(brows), int(bcols), int(nblocks), int(bs), _ptr(pos, torch.int32),
                              _ptr(crd, torch.int32), _ptr(vals, torch.float32), _ptr(B, torch.float32), int(k),
                              int(B.stride(0)), _ptr(C, torch.float32), int(C.stride(0)), int(tile), int(phases),
@@ -260,7 +271,7 @@ def psk_mttkrp_csf3(dims, crd_i, pos_k, crd_k, pos_l, crd_l, vals, C, D, A, tile
     """A (dims[0] x j) = MTTKRP of the three-level tensor with C (dims[1] x j) and D (dims[2] x j)."""
     nslices, nfibers, nnz, j = pos_k.numel() - 1, pos_l.numel() - 1, crd_l.numel(), C.shape[1]
     if ws is None:
-        ws = workspace(PSK_OP_MTTKRP_CSF3, nslices, nnz, k=j, tile=tile, device=pos_k.device)
+        ws = workspace(PSK_OP_MTTKRP_CSF3, nslices, nnz, k=j, tile=tile, device=pos_k.device, stream=stream)
     st = lib().psk_mttkrp_csf3(int(dims[0]), int(dims[1]), int(dims[2]), nslices, nfibers, nnz,
                                _ptr(crd_i, torch.int32), _ptr(pos_k, torch.int32), _ptr(crd_k, torch.int32),
                                _ptr(pos_l, torch.int32), _ptr(crd_l, torch.int32), _ptr(vals, torch.float32),
@@ -273,7 +284,7 @@ def psk_mttkrp_csf3(dims, crd_i, pos_k, crd_k, pos_l, crd_l, vals, C, D, A, tile
 
 def psk_spmv_csr_atomics(rows, cols, nnz, pos, crd, vals, x, y, tile=0, phases=PSK_PHASE_ALL, ws=None, stream=None):
     if ws is None:
-        ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=tile, device=pos.device)
+        ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmv_csr_atomics(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                                     _ptr(vals, torch.float32), _ptr(x, torch.float32), _ptr(y, torch.float32),
                                     int(tile), int(phases), _ptr(ws), ws.numel(), _stream(stream))
@@ -284,7 +295,7 @@ def psk_spmv_csr_atomics(rows, cols, nnz, pos, crd, vals, x, y, tile=0, phases=P
 def psk_spmv_csr_f64(rows, cols, nnz, pos, crd, vals, x, y, tile=0, col_passes=1, phases=PSK_PHASE_ALL, ws=None,
                      stream=None):
     if ws is None:
-        ws = workspace(PSK_OP_SPMV_CSR_F64, rows, nnz, tile=tile, device=pos.device)
+        ws = workspace(PSK_OP_SPMV_CSR_F64, rows, nnz, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmv_csr_f64(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                                 _ptr(vals, torch.float64), _ptr(x, torch.float64), _ptr(y, torch.float64),
                                 int(tile), int(col_passes), int(phases), _ptr(ws), ws.numel(), _stream(stream))
@@ -296,7 +307,7 @@ def psk_spmv_dcsr(rows, cols, nnz, crd_i, pos, crd, vals, x, y, cut=PSK_CUT_POSI
                   phases=PSK_PHASE_ALL, ws=None, stream=None):
     nstored = int(crd_i.numel())
     if ws is None:
-        ws = workspace(PSK_OP_SPMV_CSR, nstored, nnz, tile=tile, device=pos.device)
+        ws = workspace(PSK_OP_SPMV_CSR, nstored, nnz, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmv_dcsr(int(rows), int(cols), nstored, int(nnz), _ptr(crd_i, torch.int32), _ptr(pos, torch.int32),
                              _ptr(crd, torch.int32), _ptr(vals, torch.float32), _ptr(x, torch.float32),
                              _ptr(y, torch.float32), int(cut), int(tile), int(col_passes), int(phases), _ptr(ws),
@@ -307,7 +318,7 @@ def psk_spmv_dcsr(rows, cols, nnz, crd_i, pos, crd, vals, x, y, cut=PSK_CUT_POSI
 
 def psk_spmv_csr_divide(rows, cols, nnz, pos, crd, vals, x, y, parts=0, phases=PSK_PHASE_ALL, ws=None, stream=None):
     if ws is None:
-        ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=2048, device=pos.device)
+        ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=2048, device=pos.device, stream=stream)
     st = lib().psk_spmv_csr_divide(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                                    _ptr(vals, torch.float32), _ptr(x, torch.float32), _ptr(y, torch.float32),
                                    int(parts), int(phases), _ptr(ws), ws.numel(), _stream(stream))
@@ -317,7 +328,7 @@ def psk_spmv_csr_divide(rows, cols, nnz, pos, crd, vals, x, y, parts=0, phases=P
 
 def psk_spmv_csr_notemp(rows, cols, nnz, pos, crd, vals, x, y, tile=0, phases=PSK_PHASE_ALL, ws=None, stream=None):
     if ws is None:
-        ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=tile, device=pos.device)
+        ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmv_csr_notemp(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                                    _ptr(vals, torch.float32), _ptr(x, torch.float32), _ptr(y, torch.float32),
                                    int(tile), int(phases), _ptr(ws), ws.numel(), _stream(stream))

@@ -4,6 +4,10 @@
 
 using namespace psk;
 
+namespace psk {
+thread_local hipError_t tls_launch_status = hipSuccess;
+}
+
 namespace {
 
 constexpr int64_t kMaxI32 = 2147483647ll;
@@ -300,8 +304,10 @@ int psk_spmv_csr_divide(int64_t rows, int64_t cols, int64_t nnz, const int32_t *
         if (nparts == 0) e = launch_fill_zero(y, rows, s);
         else e = launch_spmv_csr_divide((int32_t)rows, (int32_t)nnz, pos, crd, vals, x, y, nparts, (int32_t)cpp, ws, s);
     }
-    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess && nparts > 1)
-        e = launch_carry_fixup(nparts, 1, 1, 1, (int32_t)(cpp * tile), pos, ws, y, s);
+    // two or more parts: cpp < nchunks, hence cpp * tile < nnz <= 2^31 - 1 (one part has no carries to add)
+    const int64_t part_len = cpp * (int64_t)tile;
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess && nparts > 1 && part_len <= kMaxI32)
+        e = launch_carry_fixup(nparts, 1, 1, 1, (int32_t)part_len, pos, ws, y, s);
     return hip_status(e);
 }
 

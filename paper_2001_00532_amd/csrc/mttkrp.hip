@@ -41,9 +41,9 @@ hipError_t launch_partition_csf3(int32_t nslices, int32_t nfibers, int32_t nnz, 
                                  hipStream_t s)
 {
     const int ntiles = nnz <= 0 ? 0 : (int)(((int64_t)nnz + tile - 1) / tile);
-    hipLaunchKernelGGL(k_partition_csf3, dim3((ntiles + 1 + 255) / 256), dim3(256), 0, s, nslices, nfibers, nnz, pos_k,
+    PSK_LAUNCH(k_partition_csf3, dim3((ntiles + 1 + 255) / 256), dim3(256), 0, s, nslices, nfibers, nnz, pos_k,
                        pos_l, tile, ntiles, tile_slice, tile_fiber);
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 // One workgroup (4 waves) per tile of T leaf positions and per chunk of 64*VEC columns.
@@ -339,7 +339,7 @@ hipError_t launch_mttkrp_main(int32_t nslices, int32_t nnz, const int32_t *crd_i
     const dim3 grid(xcd_grid(ntiles), (j + kw - 1) / kw);
     const size_t lds = ((size_t)2 * tile + 3 * (size_t)(tile / 32)) * sizeof(int);
 #define PSK_GO(V, GG)                                                                                           \
-    hipLaunchKernelGGL((k_mttkrp_pos<V, GG>), grid, dim3(256), lds, s, nslices, nnz, crd_i, pos_k, crd_k, pos_l,    \
+    PSK_LAUNCH((k_mttkrp_pos<V, GG>), grid, dim3(256), lds, s, nslices, nnz, crd_i, pos_k, crd_k, pos_l,    \
                        crd_l, vals, C, (long long)ldc, D, (long long)ldd, j, A, (long long)lda, w.tile_row,         \
                        tile_fiber, w.carry_row, w.carry_val, ntiles, tile)
     if (groups == 8) PSK_GO(1, 8);
@@ -349,7 +349,7 @@ hipError_t launch_mttkrp_main(int32_t nslices, int32_t nnz, const int32_t *crd_i
     else if (vec == 2) PSK_GO(2, 1);
     else PSK_GO(1, 1);
 #undef PSK_GO
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 }  // namespace psk

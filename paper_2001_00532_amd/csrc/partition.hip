@@ -84,14 +84,14 @@ hipError_t launch_partition(int64_t rows, int64_t nnz, const int32_t *pos, int32
         if ((tile & (tile - 1)) == 0) { shift = 0; while ((1 << shift) < tile) ++shift; }
         const int vec_ok = (reinterpret_cast<uintptr_t>(pos) & 15) == 0;
         const int64_t threads = (rows + 3) / 4;
-        hipLaunchKernelGGL(k_partition_scan, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, (int)rows,
+        PSK_LAUNCH(k_partition_scan, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, (int)rows,
                            (int)nnz, pos, tile, shift, (int)ntiles, tile_row, vec_ok);
-        return hipGetLastError();
+        return take_launch_status();
     }
     const int64_t n = ntiles + 1;
-    hipLaunchKernelGGL(k_partition, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (int)rows, (int)nnz, pos,
+    PSK_LAUNCH(k_partition, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (int)rows, (int)nnz, pos,
                        tile, (int)ntiles, tile_row);
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 // Gather-locality probe: of up to 16384 evenly spaced positions p, how many have their successor's
@@ -122,8 +122,8 @@ __global__ __launch_bounds__(1024) void k_probe_locality(int nnz, const int *__r
 
 hipError_t launch_probe_locality(int32_t nnz, const int32_t *crd, int32_t *result, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_probe_locality, dim3(1), dim3(1024), 0, s, nnz, crd, result);
-    return hipGetLastError();
+    PSK_LAUNCH(k_probe_locality, dim3(1), dim3(1024), 0, s, nnz, crd, result);
+    return take_launch_status();
 }
 
 // Longest row: result[0] = max_i (pos[i+1] - pos[i]); result must hold 0 before the launch.
@@ -148,8 +148,8 @@ hipError_t launch_max_row(int32_t rows, const int32_t *pos, int32_t *result, hip
     if (e != hipSuccess || rows <= 0) return e;
     int64_t blocks = ((int64_t)rows + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(k_max_row, dim3((unsigned)blocks), dim3(256), 0, s, rows, pos, result);
-    return hipGetLastError();
+    PSK_LAUNCH(k_max_row, dim3((unsigned)blocks), dim3(256), 0, s, rows, pos, result);
+    return take_launch_status();
 }
 
 // Structural check of a CSR index structure.  result[c] counts the violations of condition c:
@@ -181,8 +181,8 @@ hipError_t launch_validate_csr(int32_t rows, int32_t cols, int32_t nnz, const in
     int64_t work = rows > nnz ? rows : nnz;
     int64_t blocks = (work + 255) / 256;
     blocks = blocks < 1 ? 1 : (blocks > 4096 ? 4096 : blocks);
-    hipLaunchKernelGGL(k_validate_csr, dim3((unsigned)blocks), dim3(256), 0, s, rows, cols, nnz, pos, crd, result);
-    return hipGetLastError();
+    PSK_LAUNCH(k_validate_csr, dim3((unsigned)blocks), dim3(256), 0, s, rows, cols, nnz, pos, crd, result);
+    return take_launch_status();
 }
 
 __global__ __launch_bounds__(256) void k_fill_zero(float *__restrict__ p, long long n)
@@ -197,8 +197,8 @@ hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s)
     if (n <= 0) return hipSuccess;
     int64_t blocks = (n + 255) / 256;
     if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)blocks), dim3(256), 0, s, p, (long long)n);
-    return hipGetLastError();
+    PSK_LAUNCH(k_fill_zero, dim3((unsigned)blocks), dim3(256), 0, s, p, (long long)n);
+    return take_launch_status();
 }
 
 __global__ __launch_bounds__(256) void k_fill_zero_2d(float *__restrict__ p, long long rows, int width, long long ld)
@@ -216,8 +216,8 @@ hipError_t launch_fill_zero_2d(float *p, int64_t rows, int32_t width, int64_t ld
     if (rows <= 0 || width <= 0) return hipSuccess;
     int64_t blocks = (rows * width + 255) / 256;
     if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(k_fill_zero_2d, dim3((unsigned)blocks), dim3(256), 0, s, p, (long long)rows, width, (long long)ld);
-    return hipGetLastError();
+    PSK_LAUNCH(k_fill_zero_2d, dim3((unsigned)blocks), dim3(256), 0, s, p, (long long)rows, width, (long long)ld);
+    return take_launch_status();
 }
 
 // Carry fix-up.  Tile t left carry_row[t] = r >= 0 when its first positions belong to a row r that
@@ -322,14 +322,14 @@ hipError_t launch_carry_fixup(int32_t ntiles, int32_t nsub, int32_t k, int64_t l
     if ((tile & (tile - 1)) == 0) { shift = 0; while ((1 << shift) < tile) ++shift; }
     const int width = nsub * k;
     if (width == 1 && !pos2 && !rowmap) {
-        hipLaunchKernelGGL(k_carry_fixup1<float>, dim3((unsigned)((ntiles + 255) / 256)), dim3(256), 0, s, ntiles,
+        PSK_LAUNCH(k_carry_fixup1<float>, dim3((unsigned)((ntiles + 255) / 256)), dim3(256), 0, s, ntiles,
                            (long long)ld, tile, shift, pos, w.carry_row, w.carry_val, out);
-        return hipGetLastError();
+        return take_launch_status();
     }
     const int64_t n = (int64_t)ntiles * width;
-    hipLaunchKernelGGL(k_carry_fixup, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, ntiles, width, nsub, k,
+    PSK_LAUNCH(k_carry_fixup, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, ntiles, width, nsub, k,
                        (long long)ld, tile, shift, pos, pos2, rowmap, w.carry_row, w.carry_val, out);
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 hipError_t launch_carry_fixup_f64(int32_t ntiles, int32_t tile, const int32_t *pos, const Workspace &w, double *out,
@@ -338,9 +338,9 @@ hipError_t launch_carry_fixup_f64(int32_t ntiles, int32_t tile, const int32_t *p
     if (ntiles <= 1) return hipSuccess;
     int shift = -1;
     if ((tile & (tile - 1)) == 0) { shift = 0; while ((1 << shift) < tile) ++shift; }
-    hipLaunchKernelGGL(k_carry_fixup1<double>, dim3((unsigned)((ntiles + 255) / 256)), dim3(256), 0, s, ntiles, 1ll,
+    PSK_LAUNCH(k_carry_fixup1<double>, dim3((unsigned)((ntiles + 255) / 256)), dim3(256), 0, s, ntiles, 1ll,
                        tile, shift, pos, w.carry_row, reinterpret_cast<const double *>(w.carry_val), out);
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 }  // namespace psk

@@ -3,8 +3,39 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <tuple>
+#include <utility>
 
 namespace psk {
+
+// Kernel launches go through hipLaunchKernel so that each launcher reports the status of ITS launches only:
+// the global "last error" of the runtime may hold (and reading it would clear) an error left by the caller's
+// own earlier HIP calls.  A launcher may launch several kernels; the first failure is kept per host thread
+// and handed out (and reset) by take_launch_status().
+extern thread_local hipError_t tls_launch_status;
+inline hipError_t take_launch_status()
+{
+    const hipError_t e = tls_launch_status;
+    tls_launch_status = hipSuccess;
+    return e;
+}
+template <typename... KA, size_t... I>
+inline hipError_t launch_tuple(void (*kern)(KA...), dim3 grid, dim3 block, unsigned shmem, hipStream_t s,
+                               std::tuple<KA...> &args, std::index_sequence<I...>)
+{
+    void *ptrs[sizeof...(KA) ? sizeof...(KA) : 1] = {static_cast<void *>(&std::get<I>(args))...};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kern), grid, block, ptrs, shmem, s);
+}
+template <typename... KA, typename... A>
+inline void launch_kernel(void (*kern)(KA...), dim3 grid, dim3 block, unsigned shmem, hipStream_t s, A &&...a)
+{
+    static_assert(sizeof...(KA) == sizeof...(A), "argument count does not match the kernel's parameters");
+    std::tuple<KA...> args{static_cast<KA>(a)...};
+    const hipError_t e = launch_tuple(kern, grid, block, shmem, s, args, std::index_sequence_for<KA...>{});
+    if (e != hipSuccess && tls_launch_status == hipSuccess) tls_launch_status = e;
+}
+#define PSK_LAUNCH(kern, grid, block, shmem, stream, ...) \
+    ::psk::launch_kernel(kern, grid, block, shmem, stream, __VA_ARGS__)
 
 // Workspace carving: [tile_row: ntiles+1 int32][carry_row: ntiles int32][carry_val: ntiles*width float]
 // [tile_aux: ntiles+1 int32 (second table of a two-level cut)][tile_cols: ntiles*8 int32 (column range of each
@@ -34,7 +65,7 @@ inline Workspace carve(void *base, int64_t ntiles, int64_t width)
     return w;
 }
 
-// Every launcher enqueues on `s` and returns hipGetLastError() of its launches.
+// Every launcher enqueues on `s` and returns the status of its own launches (take_launch_status()).
 
 hipError_t launch_partition(int64_t rows, int64_t nnz, const int32_t *pos, int32_t tile, int method,
                             int32_t *tile_row, hipStream_t s);

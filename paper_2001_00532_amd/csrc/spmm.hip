@@ -244,14 +244,14 @@ static hipError_t launch_spmm_pos(int32_t rows, int32_t nnz, const int32_t *pos,
     const dim3 grid(xcd_grid(ntiles), (k + kw - 1) / kw);
     const size_t lds = (size_t)tile * sizeof(int);
 #define PSK_GO(V)                                                                                              \
-    hipLaunchKernelGGL((k_spmm_pos<BS, V>), grid, dim3(256), lds, s, rows, nnz, pos, crd, vals, B, k,          \
+    PSK_LAUNCH((k_spmm_pos<BS, V>), grid, dim3(256), lds, s, rows, nnz, pos, crd, vals, B, k,          \
                        (long long)ldb, C, (long long)ldc, w.tile_row, w.carry_row, w.carry_val, ntiles, tile)
     if (vec == 4) {
         if constexpr (BS < 8) PSK_GO(4);
     } else if (vec == 2) PSK_GO(2);
     else PSK_GO(1);
 #undef PSK_GO
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 hipError_t launch_spmm_csr_main(int32_t rows, int32_t nnz, const int32_t *pos, const int32_t *crd,
@@ -297,9 +297,9 @@ hipError_t launch_spmm_rowsplit(int32_t rows, const int32_t *pos, const int32_t 
                                 const float *B, int32_t k, int64_t ldb, float *C, int64_t ldc, hipStream_t s)
 {
     if (rows == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_spmm_wave_per_row, dim3((rows + 3) / 4), dim3(256), 0, s, rows, pos, crd, vals, B, k,
+    PSK_LAUNCH(k_spmm_wave_per_row, dim3((rows + 3) / 4), dim3(256), 0, s, rows, pos, crd, vals, B, k,
                        (long long)ldb, C, (long long)ldc);
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 }  // namespace psk

@@ -170,14 +170,14 @@ hipError_t launch_spmm_csr_narrow(int32_t rows, int32_t nnz, const int32_t *pos,
     const dim3 grid(xcd_grid(ntiles));
     const size_t lds = (size_t)tile * sizeof(int);
 #define PSK_GO(GG)                                                                                               \
-    hipLaunchKernelGGL((k_spmm_pos_narrow<GG>), grid, dim3(256), lds, s, rows, nnz, pos, crd, vals, B, k,        \
+    PSK_LAUNCH((k_spmm_pos_narrow<GG>), grid, dim3(256), lds, s, rows, nnz, pos, crd, vals, B, k,        \
                        (long long)ldb, C, (long long)ldc, w.tile_row, w.carry_row, w.carry_val, ntiles, tile)
     if (k <= 8) PSK_GO(8);
     else if (k <= 16) PSK_GO(4);
     else if (k <= 32) PSK_GO(2);
     else return hipErrorInvalidValue;
 #undef PSK_GO
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 }  // namespace psk

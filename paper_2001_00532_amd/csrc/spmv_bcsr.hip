@@ -147,7 +147,7 @@ hipError_t launch_spmv_bcsr4_main(int32_t brows, int32_t nblocks, const int32_t 
     if (ntiles == 0) return hipSuccess;
     const int grid = xcd_grid(ntiles);
 #define PSK_GO(TB)                                                                                           \
-    hipLaunchKernelGGL((k_spmv_bcsr4<TB>), dim3(grid), dim3(256), 0, s, brows, nblocks, pos, crd, vals, x, y, \
+    PSK_LAUNCH((k_spmv_bcsr4<TB>), dim3(grid), dim3(256), 0, s, brows, nblocks, pos, crd, vals, x, y, \
                        w.tile_row, w.carry_row, w.carry_val, ntiles)
     switch (tile) {
         case 64: PSK_GO(64); break;
@@ -157,7 +157,7 @@ hipError_t launch_spmv_bcsr4_main(int32_t brows, int32_t nblocks, const int32_t 
         default: return hipErrorInvalidValue;
     }
 #undef PSK_GO
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 }  // namespace psk

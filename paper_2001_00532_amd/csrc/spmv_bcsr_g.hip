@@ -136,7 +136,7 @@ hipError_t launch_spmv_bcsr_g_main(int32_t bs, int32_t brows, int32_t nblocks, c
     if (ntiles == 0) return hipSuccess;
     const int grid = xcd_grid(ntiles);
 #define PSK_GO(B, TB)                                                                                              \
-    hipLaunchKernelGGL((k_spmv_bcsr_g<B, TB>), dim3(grid), dim3(256), 0, s, brows, nblocks, pos, crd, vals, x, y, \
+    PSK_LAUNCH((k_spmv_bcsr_g<B, TB>), dim3(grid), dim3(256), 0, s, brows, nblocks, pos, crd, vals, x, y, \
                        w.tile_row, w.carry_row, w.carry_val, ntiles)
     if (bs == 2) {
         switch (tile) {
@@ -156,7 +156,7 @@ hipError_t launch_spmv_bcsr_g_main(int32_t bs, int32_t brows, int32_t nblocks, c
         return hipErrorInvalidValue;
     }
 #undef PSK_GO
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 }  // namespace psk

@@ -342,7 +342,7 @@ static void launch_pos(int mode, int grid, hipStream_t s, int rows, int cols, in
                        int accum, const int *rowmap)
 {
 #define PSK_GO(M, W)                                                                                             \
-    hipLaunchKernelGGL((k_spmv_pos<THREADS, NPT, M, W>), dim3(grid), dim3(THREADS), 0, s, rows, cols, nnz, pos,  \
+    PSK_LAUNCH((k_spmv_pos<THREADS, NPT, M, W>), dim3(grid), dim3(THREADS), 0, s, rows, cols, nnz, pos,  \
                        crd, vals, x, y, w.tile_row, w.carry_row, w.carry_val, ntiles, clo, chi, accum, rowmap,    \
                        w.tile_cols)
     const bool window = clo > 0 || chi < cols;
@@ -380,7 +380,7 @@ hipError_t launch_spmv_csr_main(int32_t rows, int32_t cols, int32_t nnz, const i
         default: return hipErrorInvalidValue;
     }
     }
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 // ------------------------------------------------------------------ coordinate-space baselines
@@ -424,12 +424,12 @@ hipError_t launch_spmv_rowsplit(int32_t rows, const int32_t *pos, const int32_t 
 {
     if (rows == 0) return hipSuccess;
     if (variant == 0)
-        hipLaunchKernelGGL(k_spmv_thread_per_row, dim3((rows + 255) / 256), dim3(256), 0, s, rows, pos, crd, vals, x,
+        PSK_LAUNCH(k_spmv_thread_per_row, dim3((rows + 255) / 256), dim3(256), 0, s, rows, pos, crd, vals, x,
                            y);
     else
-        hipLaunchKernelGGL(k_spmv_wave_per_row, dim3((rows + 3) / 4), dim3(256), 0, s, rows, pos, crd, vals, x, y,
+        PSK_LAUNCH(k_spmv_wave_per_row, dim3((rows + 3) / 4), dim3(256), 0, s, rows, pos, crd, vals, x, y,
                            rowmap);
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 }  // namespace psk

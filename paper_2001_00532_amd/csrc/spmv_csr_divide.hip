@@ -61,8 +61,12 @@ __global__ __launch_bounds__(THREADS) void k_spmv_div(int rows, int nnz, const i
         s_pend[1] = 0.0f;
     }
 
+    // The chunks are counted, not stepped by position: near nnz = 2^31 - 1 a position that is advanced past
+    // the end of the part would wrap around.  b0 + c*T < b1 <= nnz for every chunk c of the part.
+    const int nchunks = (int)(((long long)b1 - b0 + T - 1) / T);
     int parity = 0;
-    for (int t0 = b0; t0 < b1; t0 += T, parity ^= 1) {
+    for (int c = 0; c < nchunks; ++c, parity ^= 1) {
+        const int t0 = b0 + c * T;
         const int cnt = (b1 - t0 < T) ? b1 - t0 : T;
         const int t1 = t0 + cnt;
         const bool last = t1 == b1;
@@ -184,12 +188,12 @@ hipError_t launch_spmv_csr_divide(int32_t rows, int32_t nnz, const int32_t *pos,
     if (parts <= 0) return hipSuccess;
     const bool vec = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
     if (vec)
-        hipLaunchKernelGGL((k_spmv_div<256, 8, true>), dim3(parts), dim3(256), 0, s, rows, nnz, pos, crd, vals, x, y,
+        PSK_LAUNCH((k_spmv_div<256, 8, true>), dim3(parts), dim3(256), 0, s, rows, nnz, pos, crd, vals, x, y,
                            w.carry_row, w.carry_val, chunks_per_part);
     else
-        hipLaunchKernelGGL((k_spmv_div<256, 8, false>), dim3(parts), dim3(256), 0, s, rows, nnz, pos, crd, vals, x, y,
+        PSK_LAUNCH((k_spmv_div<256, 8, false>), dim3(parts), dim3(256), 0, s, rows, nnz, pos, crd, vals, x, y,
                            w.carry_row, w.carry_val, chunks_per_part);
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 }  // namespace psk

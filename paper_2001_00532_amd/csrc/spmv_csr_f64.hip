@@ -203,7 +203,7 @@ static void go(bool vec, bool win, int grid, hipStream_t s, int rows, int nnz, c
 {
     double *cv = reinterpret_cast<double *>(w.carry_val);
 #define PSK_GO(V, W)                                                                                                  \
-    hipLaunchKernelGGL((k_spmv_pos_f64<THREADS, NPT, V, W>), dim3(grid), dim3(THREADS), 0, s, rows, nnz, pos, crd, vals, \
+    PSK_LAUNCH((k_spmv_pos_f64<THREADS, NPT, V, W>), dim3(grid), dim3(THREADS), 0, s, rows, nnz, pos, crd, vals, \
                        x, y, w.tile_row, w.carry_row, cv, ntiles, clo, chi, accum, w.tile_cols)
     if (vec) { if (win) PSK_GO(true, true); else PSK_GO(true, false); }
     else { if (win) PSK_GO(false, true); else PSK_GO(false, false); }
@@ -231,7 +231,7 @@ hipError_t launch_spmv_csr_f64_main(int32_t rows, int32_t cols, int32_t nnz, con
             default: return hipErrorInvalidValue;
         }
     }
-    return hipGetLastError();
+    return take_launch_status();
 }
 
 }  // namespace psk

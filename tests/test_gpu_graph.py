@@ -71,3 +71,6 @@ def test_captured_products_replay_correctly():
         ref, mag = oracle.spmv_csr(A.pos, A.crd, A.vals, xh, threads=8)
         ok, worst = oracle.within_tolerance(y.cpu().numpy(), ref, mag)
         assert ok, "replay %d: %.3g" % (rep, worst)
+        ref, mag = oracle.spmm_csr(M.pos, M.crd, M.vals, Bh, threads=8)
+        ok, worst = oracle.within_tolerance(C.cpu().numpy(), ref, mag)
+        assert ok, "replay %d, C: %.3g" % (rep, worst)

@@ -75,3 +75,15 @@ def test_spmv_at_the_int32_limit():
         worst = (np.abs(got - ref[None, :]) / bound[None, :]).max()
         assert worst <= 1.0, "tile %d passes %d: worst |err|/bound = %.3g" % (tile, passes, worst)
         del y, ws
+
+    # the divided variant at the same size: the last part ends within 2048 positions of 2^31, where a chunk
+    # start that is stepped past the end of the part would wrap around (chunks are counted instead)
+    say("divided spmv, 2048 parts")
+    ws = psk.workspace(psk.PSK_OP_SPMV_CSR, rows, nnz, tile=2048)
+    y = torch.full((rows,), float("nan"), device=dev)
+    psk.psk_spmv_csr_divide(rows, cols, nnz, pos, crd, vals, xd, y, parts=0, ws=ws)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().reshape(COPIES, rows_b)
+    assert not np.isnan(got).any()
+    worst = (np.abs(got - ref[None, :]) / (1e-5 * mag + 1e-30)[None, :]).max()
+    assert worst <= 1.0, "divided: worst |err|/bound = %.3g" % worst

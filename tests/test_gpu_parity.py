@@ -199,7 +199,7 @@ def test_spmm_config4_scaled(tile):
     check(run_spmm(DevCSR(A), dev(B), tile), ref, mag, "spmm tile %d" % tile)
 
 
-@pytest.mark.parametrize("k", [1, 17, 64, 100, 128, 130, 256, 300])
+@pytest.mark.parametrize("k", [1, 8, 9, 12, 16, 17, 24, 32, 33, 64, 100, 128, 130, 256, 300])
 def test_spmm_any_k_and_strides(k):
     rng = np.random.default_rng(k)
     rows, cols = 1501, 1203
@@ -274,6 +274,27 @@ def test_bcsr_spmm(k):
             psk.psk_spmm_bcsr(A.rows, A.cols, A.nnz, 4, D.pos, D.crd, D.vals, Bd, C, tile=tile)
             torch.cuda.synchronize()
             check(C.cpu().numpy(), ref, mag, "bcsr spmm %s k=%d tile %d" % (name, k, tile))
+
+
+@pytest.mark.parametrize("bs", [2, 4, 8])
+@pytest.mark.parametrize("k", [64, 40, 7])
+def test_bcsr_spmm_strided_operands(bs, k):
+    """B and C with row strides larger than k (ldb = k + 3, ldc = k + 5): the padding of C stays untouched."""
+    rng = np.random.default_rng(70 + bs)
+    A = wl.csr_from_lengths(adversarial_lengths(rng, 1203, 1501, "mixed"), 1501, seed=57, bs=bs)
+    Bh = wl.dense_uniform(A.cols * bs * (k + 3), 58, wl.S_B).reshape(A.cols * bs, k + 3)
+    ref, mag = oracle.spmm_bcsr(A.pos, A.crd, A.vals, Bh[:, :k], bs, threads=8)
+    D = DevCSR(A)
+    Bd = dev(Bh)[:, :k]
+    for tile in (0, 64):
+        say("bcsr spmm strided bs", bs, "k", k, "tile", tile)
+        Cfull = torch.full((A.rows * bs, k + 5), -7.0, device="cuda")
+        C = Cfull[:, :k]
+        C.fill_(float("nan"))
+        psk.psk_spmm_bcsr(A.rows, A.cols, A.nnz, bs, D.pos, D.crd, D.vals, Bd, C, tile=tile)
+        torch.cuda.synchronize()
+        check(C.cpu().numpy(), ref, mag, "bcsr spmm strided bs %d k %d tile %d" % (bs, k, tile))
+        assert bool((Cfull[:, k:] == -7.0).all()), "columns beyond k were written"
 
 
 @pytest.mark.parametrize("bs,tiles", [(2, [0, 512, 1024, 2048]), (8, [0, 32, 64, 128])])
@@ -360,7 +381,8 @@ def test_validate_matches_the_oracle_on_broken_structures():
     p = A.pos.copy(); p[0] = 1; c = A.crd.copy(); c[0] = 99999
     cases.append(("two errors: the first in order is reported", p, c, A.nnz))
     for name, pos, crd, nnz in cases:
-        want = oracle.validate_csr(pos, crd, A.cols) if nnz == A.nnz else 3
+        # the oracle takes the stated nnz from the length of crd: a shortened crd states nnz - 1
+        want = oracle.validate_csr(pos, crd[:nnz], A.cols)
         say("validate", name, "expect", want)
         assert psk.psk_validate_csr(A.rows, A.cols, nnz, dev(pos), dev(crd)) == want, name
     assert psk.psk_validate_csr(0, 5, 0, dev(np.zeros(1, dtype=np.int32)), dev(np.zeros(0, dtype=np.int32))) == 0

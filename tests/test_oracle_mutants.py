@@ -33,6 +33,7 @@ MUTANTS = [
      "double t = (double)vals[(p * bs + ji) * bs + ii] * (double)x[jb * bs + ji];"),
     ("bcsr_x_offset", "(double)x[jb * bs + ji];", "(double)x[jb + ji];"),
     ("bcsr_spmm_row_of_b", "const float *b = B + (jb * bs + ji) * ldb;", "const float *b = B + (jb * bs + ii) * ldb;"),
+    ("bcsr_spmm_ignores_ldb", "const float *b = B + (jb * bs + ji) * ldb;", "const float *b = B + (jb * bs + ji) * k;"),
     ("partition_strict_compare", "while (i < rows && (int64_t)pos[i + 1] <= first) ++i;", "while (i < rows && (int64_t)pos[i + 1] < first) ++i;"),
     # (removing the clamp of the last tile's first position to nnz is an equivalent mutant: the walk
     # reaches `rows` either way, so it is not listed)
@@ -48,6 +49,7 @@ MUTANTS = [
     ("mttkrp_drops_last_leaf", "for (int64_t p = pos_l[q]; p < pos_l[q + 1]; ++p) {\n                const float *d", "for (int64_t p = pos_l[q]; p < pos_l[q + 1] - 1; ++p) {\n                const float *d"),
     ("mttkrp_adds_instead_of_multiplying", "double term = v * (double)c[jj] * (double)d[jj];", "double term = v * ((double)c[jj] + (double)d[jj]);"),
     ("mttkrp_ignores_ldd", "const float *d = D + (int64_t)crd_l[p] * ldd;", "const float *d = D + (int64_t)crd_l[p] * j;"),
+    ("mttkrp_ignores_ldc", "const float *c = C + (int64_t)crd_k[q] * ldc;", "const float *c = C + (int64_t)crd_k[q] * j;"),
     ("partition_csf3_slice_from_position", "while (s < nslices && (int64_t)pos_k[s + 1] <= q) ++s;", "while (s < nslices && (int64_t)pos_k[s + 1] <= first) ++s;"),
     ("partition_csf3_strict", "while (q < nfibers && (int64_t)pos_l[q + 1] <= first) ++q;", "while (q < nfibers && (int64_t)pos_l[q + 1] < first) ++q;"),
     ("f64_sums_in_double", "long double acc = 0.0L, m = 0.0L;", "double acc = 0.0, m = 0.0;"),
@@ -103,7 +105,7 @@ def pins_pass(lib) -> bool:
             return False
         Ab = wl.csr_from_lengths(np.random.default_rng(2).integers(0, 5, size=17), 13, seed=4, bs=4)
         xb = wl.dense_uniform(13 * 4, 4, wl.S_X)
-        Bb = wl.dense_uniform(13 * 4 * 3, 4, wl.S_B).reshape(13 * 4, 3)
+        Bb = wl.dense_uniform(13 * 4 * 5, 4, wl.S_B).reshape(13 * 4, 5)[:, :3]      # row stride 5, three columns
         Db = dense_of(Ab)
         yb, _ = oracle.spmv_bcsr(Ab.pos, Ab.crd, Ab.vals, xb, 4)
         Cb, _ = oracle.spmm_bcsr(Ab.pos, Ab.crd, Ab.vals, Bb, 4)
@@ -139,7 +141,7 @@ def pins_pass(lib) -> bool:
         if y.tolist() != [0.0, -1.0, 0.0, 0.0, 6.0, 0.0] or mag.tolist() != [0.0, 5.0, 0.0, 0.0, 6.0, 0.0]:
             return False
         # MTTKRP: hand-worked case, a strided D, and the two-level cut against brute force
-        Cm = np.array([[1.0, 10.0], [2.0, 20.0]], dtype=np.float32)
+        Cm = np.array([[1.0, 10.0, 7.0], [2.0, 20.0, 7.0]], dtype=np.float32)[:, :2]      # row stride 3
         Dm = np.array([[1.0, 1.0, 9.0], [0.5, 2.0, 9.0], [3.0, -1.0, 9.0]], dtype=np.float32)[:, :2]
         Am, Mm = oracle.mttkrp_csf3([0, 2], [1, 0], [0, 2, 3], [0, 2, 1], [2.0, -1.0, 4.0], Cm, Dm)
         if Am.tolist() != [[0.0, 140.0]] or Mm.tolist() != [[12.0, 140.0]]:
