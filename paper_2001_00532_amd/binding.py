@@ -27,6 +27,7 @@ EXPORTS = [
     "psk_partition_csr", "psk_analyze_csr", "psk_spmv_csr", "psk_spmm_csr", "psk_spmv_bcsr", "psk_spmm_bcsr",
     "psk_spmv_csr_rowsplit", "psk_spmm_csr_rowsplit", "psk_spmv_csr_atomics", "psk_mttkrp_csf3",
     "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64", "psk_spmv_dcsr", "psk_spmv_csr_divide", "psk_suggest_schedule_csr", "psk_default_tile_bcsr", "psk_validate_csr",
+    "psk_spmv_csr_static", "psk_static_scratch_bytes",
 ]
 
 
@@ -57,6 +58,9 @@ def lib() -> ctypes.CDLL:
         L.psk_analyze_csr.restype = ci
         L.psk_spmv_csr.argtypes = [i64, i64, i64, p, p, p, p, p, i32, i32, ci, p, sz, p]
         L.psk_spmv_csr.restype = ci
+        L.psk_spmv_csr_static.argtypes = [i64, i64, i64, p, p, p, p, p, i32, i32, p]
+        L.psk_spmv_csr_static.restype = ci
+        L.psk_static_scratch_bytes.argtypes, L.psk_static_scratch_bytes.restype = [], sz
         L.psk_spmm_csr.argtypes = [i64, i64, i64, p, p, p, p, i32, i64, p, i64, i32, ci, p, sz, p]
         L.psk_spmm_csr.restype = ci
         L.psk_spmv_bcsr.argtypes = [i64, i64, i64, i32, p, p, p, p, p, i32, ci, p, sz, p]
@@ -215,6 +219,19 @@ def psk_spmv_csr(rows, cols, nnz, pos, crd, vals, x, y, tile=0, col_passes=1, ph
                             _ptr(vals, torch.float32), _ptr(x, torch.float32), _ptr(y, torch.float32), int(tile),
                             int(col_passes), int(phases), _ptr(ws), ws.numel(), _stream(stream))
     _check(st, "psk_spmv_csr")
+    return y
+
+
+def psk_static_scratch_bytes() -> int:
+    return int(lib().psk_static_scratch_bytes())
+
+
+def psk_spmv_csr_static(rows, cols, nnz, pos, crd, vals, x, y, tile=0, col_passes=1, stream=None):
+    """psk_spmv_csr without a workspace: the library's built-in scratch array is used; nothing is allocated."""
+    st = lib().psk_spmv_csr_static(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
+                                   _ptr(vals, torch.float32), _ptr(x, torch.float32), _ptr(y, torch.float32),
+                                   int(tile), int(col_passes), _stream(stream))
+    _check(st, "psk_spmv_csr_static")
     return y
 
 

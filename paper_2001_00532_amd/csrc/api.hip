@@ -1,6 +1,7 @@
 // C-ABI layer: argument validation, workspace carving, phase dispatch.  No kernels here.
 #include "../../include/psk.h"
 #include "psk_internal.h"
+#include <mutex>
 
 using namespace psk;
 
@@ -8,9 +9,35 @@ namespace psk {
 thread_local hipError_t tls_launch_status = hipSuccess;
 }
 
+// Scratch memory of psk_spmv_csr_static: one copy per GPU, held until the process ends.  The name is only a
+// host-side handle; the device address is asked for once per device (static_scratch()) and that pointer is
+// what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[PSK_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int64_t kMaxI32 = 2147483647ll;
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device; NULL (and *err set) when the runtime refuses.
+void *static_scratch(hipError_t *err)
+{
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess || !p) { if (*err == hipSuccess) *err = hipErrorInvalidSymbol; return nullptr; }
+        scratch_ptr[dev] = p;
+    }
+    return scratch_ptr[dev];
+}
 
 int32_t default_tile(int op, int32_t bs = 4)
 {
@@ -87,7 +114,7 @@ const char *psk_status_string(int status)
         case PSK_ERR_NULL: return "a required pointer is NULL";
         case PSK_ERR_SIZE: return "invalid size argument";
         case PSK_ERR_TILE: return "unsupported position-tile size";
-        case PSK_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case PSK_ERR_WORKSPACE: return "workspace missing, misaligned or too small (or the problem exceeds the built-in scratch memory)";
         case PSK_ERR_UNSUPPORTED: return "unsupported operation, variant or phase mask";
         case PSK_ERR_HIP: return "HIP runtime error at kernel launch";
         case PSK_ERR_ALIGNMENT: return "operand not 16-byte aligned";
@@ -217,6 +244,32 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
     }
     if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, 1, 1, tile, pos, ws, y, s);
     return hip_status(e);
+}
+
+size_t psk_static_scratch_bytes(void) { return PSK_STATIC_SCRATCH_BYTES; }
+
+int psk_spmv_csr_static(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                        const float *vals, const float *x, float *y, int32_t tile, int32_t col_passes, void *stream)
+{
+    if (col_passes < 0 || col_passes > PSK_MAX_COL_PASSES) return PSK_ERR_SIZE;
+    if (tile == 0) tile = col_passes > 1 ? 1024 : default_tile(PSK_OP_SPMV_CSR);
+    if (!tile_ok(PSK_OP_SPMV_CSR, tile)) return PSK_ERR_TILE;
+    if (nnz >= 0 && nnz <= kMaxI32 &&
+        psk_workspace_bytes(PSK_OP_SPMV_CSR, rows, nnz, 1, 1, tile) > (size_t)PSK_STATIC_SCRATCH_BYTES)
+        return PSK_ERR_WORKSPACE;               // more tiles than the built-in scratch memory has room for
+    // validate before touching the runtime, with a stand-in workspace address that is never dereferenced
+    Workspace ws;
+    int st = check_common(PSK_OP_SPMV_CSR, rows, cols, nnz, pos, crd, vals, 1, 1, &tile, PSK_PHASE_ALL,
+                          reinterpret_cast<void *>(uintptr_t(256)), PSK_STATIC_SCRATCH_BYTES, &ws);
+    if (st != PSK_OK) return st;
+    if ((rows > 0 && !y) || (nnz > 0 && !x)) return PSK_ERR_NULL;
+    hipError_t e = hipSuccess;
+    void *base = static_scratch(&e);
+    if (!base) return PSK_ERR_HIP;
+    // every part of the scratch memory that a product reads is written earlier in the same product (table by
+    // the partition, carry records and column ranges by the tile kernel), so nothing needs clearing
+    return psk_spmv_csr(rows, cols, nnz, pos, crd, vals, x, y, tile, col_passes, PSK_PHASE_ALL, base,
+                        PSK_STATIC_SCRATCH_BYTES, stream);
 }
 
 int psk_spmv_csr_f64(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
