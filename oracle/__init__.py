@@ -64,6 +64,12 @@ def _lib():
         lib.oracle_partition.restype = None
         lib.oracle_validate_csr.argtypes = [i64, i64, i64, p, p]
         lib.oracle_validate_csr.restype = ci
+        lib.oracle_slab_count.argtypes = [i64, i64, i64, p, p, i64, i64, p]
+        lib.oracle_slab_count.restype = ci
+        lib.oracle_slab_build.argtypes = [i64, i64, i64, p, p, p, i64, i64, p, p, p, p, p, p, p]
+        lib.oracle_slab_build.restype = ci
+        lib.oracle_spmv_slab.argtypes = [i64, i64, i64, i64, i64, p, p, p, p, p, p, p, p, p, p]
+        lib.oracle_spmv_slab.restype = None
         _h = lib
     return _h
 
@@ -235,3 +241,44 @@ def within_tolerance(got, ref, mag, rel: float = 1e-5, floor: float = 1e-30):
     bad = ~(err <= bound)  # NaN counts as failure
     worst = float(np.max(err / bound)) if err.size else 0.0
     return (not bool(bad.any())), worst
+
+
+class Slab:
+    """The column-slab hierarchy of a CSR matrix (see oracle.c): arrays svals, scol (uint16), srow, chunk_pair,
+    slab_chunk, qpos, qidx and the sizes nslots, npairs, nq, nslabs."""
+
+
+def slab_build(rows: int, cols: int, pos, crd, vals, W: int = 32736, CH: int = 512) -> Slab:
+    pos, crd, vals = _i32(pos), _i32(crd), _f32(vals)
+    nnz = int(crd.size)
+    sizes = np.zeros(4, dtype=np.int64)
+    if _lib().oracle_slab_count(rows, cols, nnz, pos.ctypes.data, crd.ctypes.data, W, CH, sizes.ctypes.data) != 0:
+        raise MemoryError("oracle_slab_count")
+    S = Slab()
+    S.rows, S.cols, S.nnz, S.W, S.CH = rows, cols, nnz, W, CH
+    S.nslots, S.npairs, S.nq, S.nslabs = (int(v) for v in sizes)
+    S.svals = np.empty(S.nslots, dtype=np.float32)
+    S.scol = np.empty(S.nslots, dtype=np.uint16)
+    S.srow = np.empty(S.nslots, dtype=np.int32)
+    S.chunk_pair = np.empty(S.nslots // CH + 1, dtype=np.int32)
+    S.slab_chunk = np.empty(S.nslabs + 1, dtype=np.int32)
+    S.qpos = np.empty(rows + 1, dtype=np.int32)
+    S.qidx = np.empty(S.nq, dtype=np.int32)
+    if _lib().oracle_slab_build(rows, cols, nnz, pos.ctypes.data, crd.ctypes.data, vals.ctypes.data, W, CH,
+                                S.svals.ctypes.data, S.scol.ctypes.data, S.srow.ctypes.data, S.chunk_pair.ctypes.data,
+                                S.slab_chunk.ctypes.data, S.qpos.ctypes.data, S.qidx.ctypes.data) != 0:
+        raise MemoryError("oracle_slab_build")
+    return S
+
+
+def spmv_slab(S: Slab, x):
+    """y and mag (float64, one per row) evaluated over the slab structure: P per pair, then the pairs of each row."""
+    x = _f32(x)
+    P = np.empty(max(S.npairs, 1), dtype=np.float64)
+    Pm = np.empty(max(S.npairs, 1), dtype=np.float64)
+    y = np.empty(S.rows, dtype=np.float64)
+    mag = np.empty(S.rows, dtype=np.float64)
+    _lib().oracle_spmv_slab(S.rows, S.cols, S.nslots, S.W, S.CH, S.svals.ctypes.data, S.scol.ctypes.data,
+                            S.slab_chunk.ctypes.data, S.qpos.ctypes.data, S.qidx.ctypes.data, x.ctypes.data,
+                            P.ctypes.data, Pm.ctypes.data, y.ctypes.data, mag.ctypes.data)
+    return y, mag

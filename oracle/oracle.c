@@ -301,3 +301,164 @@ int oracle_validate_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *
         if (crd[p] < 0 || crd[p] >= cols) return 4;
     return 0;
 }
+
+/*
+ * The column-slab hierarchy of a CSR matrix and the SpMV evaluated over it.
+ *
+ * Section 8.6 obtains locality by tiling a dense-operand loop (split, then reorder); Section 3 allows
+ * the position cut at any level of any coordinate hierarchy.  Here the column loop j is split by a fixed
+ * slab width W, jo = j / W is moved outermost and the matrix is STORED in that order: a three-level
+ * hierarchy (jo dense, i compressed, ji compressed).  Its leaf positions ("slots") are the stored
+ * entries sorted by (jo, original position), i.e. a stable bucketing of the CSR positions by slab.
+ * Every slab is padded with empty slots to a multiple of CH, so that chunks of CH slots never cross a
+ * slab.  A "pair" is a maximal run of slots of one row inside one chunk; the product is evaluated as
+ *     P(pair) = sum over the pair's slots of value * x(jo*W + ji)       (x of one slab at a time)
+ *     y(i)    = sum of P over the pairs of row i
+ * and the pairs of a row are listed by a CSR-like structure (qpos, qidx) in the order in which their
+ * first slots occur in the original CSR.
+ *
+ *   svals[N], scol[N]: value and 15-bit in-slab column of each slot, bit 15 of scol = the slot is the
+ *                      last of its pair; pad slots have value 0, column 0 and form pairs of their own
+ *                      that no row lists;
+ *   srow[N]:           row of each slot, -1 for pad slots (only needed while building);
+ *   chunk_pair[N/CH + 1]: index of the pair that owns the first slot of each chunk; last = npairs;
+ *   slab_chunk[S + 1]: first chunk of each slab; last = N/CH;
+ *   qpos[rows + 1], qidx[nq]: the pairs of each row.
+ * oracle_slab_count gives N, npairs and nq (array sizes); oracle_slab_build fills the arrays.
+ * W must be at most 32768 (15 bits).
+ */
+static int64_t slab_layout(int64_t cols, int64_t nnz, const int32_t *crd, int64_t W, int64_t CH,
+                           int64_t *base /* S + 1 */)
+{
+    int64_t S = (cols + W - 1) / W;
+    for (int64_t s = 0; s <= S; ++s) base[s] = 0;
+    for (int64_t p = 0; p < nnz; ++p) base[crd[p] / W + 1] += 1;           /* count of slab s at base[s+1] */
+    for (int64_t s = 0; s < S; ++s) {
+        int64_t padded = (base[s + 1] + CH - 1) / CH * CH;
+        base[s + 1] = base[s] + padded;
+    }
+    return base[S];
+}
+
+/* Fills slot_row (row of each slot, -1 = pad) and slot_src (CSR position of each slot, -1 = pad). */
+static void slab_slots(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd, int64_t W,
+                       int64_t CH, const int64_t *base, int64_t N, int32_t *slot_row, int64_t *slot_src,
+                       int64_t *fill /* S scratch */)
+{
+    int64_t S = (cols + W - 1) / W;
+    (void)CH;
+    for (int64_t j = 0; j < N; ++j) { slot_row[j] = -1; slot_src[j] = -1; }
+    for (int64_t s = 0; s < S; ++s) fill[s] = 0;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t p = pos[i]; p < pos[i + 1]; ++p) {
+            int64_t s = crd[p] / W;
+            int64_t j = base[s] + fill[s]++;
+            slot_row[j] = (int32_t)i;
+            slot_src[j] = p;
+        }
+    (void)nnz;
+}
+
+static int slab_is_start(const int32_t *slot_row, int64_t CH, int64_t j)
+{
+    return j % CH == 0 || slot_row[j] != slot_row[j - 1];
+}
+
+#include <stdlib.h>
+
+/* sizes[0] = N (slots), sizes[1] = npairs, sizes[2] = nq (pairs listed by rows), sizes[3] = S.  Returns 0,
+ * or -1 when memory runs out. */
+int oracle_slab_count(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd, int64_t W,
+                      int64_t CH, int64_t *sizes)
+{
+    int64_t S = (cols + W - 1) / W;
+    int64_t *base = (int64_t *)malloc((size_t)(S + 1) * sizeof(int64_t));
+    int64_t *fill = (int64_t *)malloc((size_t)(S + 1) * sizeof(int64_t));
+    if (!base || !fill) { free(base); free(fill); return -1; }
+    int64_t N = slab_layout(cols, nnz, crd, W, CH, base);
+    int32_t *slot_row = (int32_t *)malloc((size_t)(N + 1) * sizeof(int32_t));
+    int64_t *slot_src = (int64_t *)malloc((size_t)(N + 1) * sizeof(int64_t));
+    if (!slot_row || !slot_src) { free(base); free(fill); free(slot_row); free(slot_src); return -1; }
+    slab_slots(rows, cols, nnz, pos, crd, W, CH, base, N, slot_row, slot_src, fill);
+    int64_t npairs = 0, nq = 0;
+    for (int64_t j = 0; j < N; ++j)
+        if (slab_is_start(slot_row, CH, j)) { ++npairs; if (slot_row[j] >= 0) ++nq; }
+    sizes[0] = N; sizes[1] = npairs; sizes[2] = nq; sizes[3] = S;
+    free(base); free(fill); free(slot_row); free(slot_src);
+    return 0;
+}
+
+int oracle_slab_build(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                      const float *vals, int64_t W, int64_t CH, float *svals, uint16_t *scol, int32_t *srow,
+                      int32_t *chunk_pair, int32_t *slab_chunk, int32_t *qpos, int32_t *qidx)
+{
+    int64_t S = (cols + W - 1) / W;
+    int64_t *base = (int64_t *)malloc((size_t)(S + 1) * sizeof(int64_t));
+    int64_t *fill = (int64_t *)malloc((size_t)(S + 1) * sizeof(int64_t));
+    if (!base || !fill) { free(base); free(fill); return -1; }
+    int64_t N = slab_layout(cols, nnz, crd, W, CH, base);
+    int64_t *slot_src = (int64_t *)malloc((size_t)(N + 1) * sizeof(int64_t));
+    int32_t *pair_of = (int32_t *)malloc((size_t)(N + 1) * sizeof(int32_t));
+    int64_t *slot_of = (int64_t *)malloc((size_t)(nnz + 1) * sizeof(int64_t));
+    if (!slot_src || !pair_of || !slot_of) { free(base); free(fill); free(slot_src); free(pair_of); free(slot_of); return -1; }
+    slab_slots(rows, cols, nnz, pos, crd, W, CH, base, N, srow, slot_src, fill);
+    for (int64_t s = 0; s <= S; ++s) slab_chunk[s] = (int32_t)(base[s] / CH);
+    /* slots: value, in-slab column; pairs numbered in slot order */
+    int64_t npairs = 0;
+    for (int64_t j = 0; j < N; ++j) {
+        if (slab_is_start(srow, CH, j)) ++npairs;
+        pair_of[j] = (int32_t)(npairs - 1);
+        int64_t p = slot_src[j];
+        svals[j] = p >= 0 ? vals[p] : 0.0f;
+        scol[j] = p >= 0 ? (uint16_t)(crd[p] % W) : 0;
+        if (p >= 0) slot_of[p] = j;
+        if (j % CH == 0) chunk_pair[j / CH] = pair_of[j];
+    }
+    chunk_pair[N / CH] = (int32_t)npairs;
+    for (int64_t j = 0; j < N; ++j)
+        if (j == N - 1 || slab_is_start(srow, CH, j + 1)) scol[j] |= 0x8000u;
+    /* the pairs of each row, in the order their first slots occur in the CSR */
+    int64_t nq = 0;
+    for (int64_t i = 0; i < rows; ++i) {
+        qpos[i] = (int32_t)nq;
+        for (int64_t p = pos[i]; p < pos[i + 1]; ++p) {
+            int64_t j = slot_of[p];
+            if (slab_is_start(srow, CH, j)) qidx[nq++] = pair_of[j];
+        }
+    }
+    qpos[rows] = (int32_t)nq;
+    free(base); free(fill); free(slot_src); free(pair_of); free(slot_of);
+    return 0;
+}
+
+/* The SpMV evaluated over the structure, step by step as described above, in fp64: first P per pair, then
+ * y per row (and mag = sum |value * x|).  P has npairs doubles (scratch).  Used to pin that the structure
+ * represents the same matrix: its result must equal the CSR definition up to the order of the sums. */
+void oracle_spmv_slab(int64_t rows, int64_t cols, int64_t N, int64_t W, int64_t CH, const float *svals,
+                      const uint16_t *scol, const int32_t *slab_chunk, const int32_t *qpos, const int32_t *qidx,
+                      const float *x, double *P, double *Pmag, double *y, double *mag)
+{
+    int64_t S = (cols + W - 1) / W;
+    int64_t pair = 0;
+    for (int64_t s = 0; s < S; ++s)
+        for (int64_t j = (int64_t)slab_chunk[s] * CH; j < (int64_t)slab_chunk[s + 1] * CH; ++j) {
+            double acc = 0.0, m = 0.0;
+            for (;; ++j) {
+                int64_t col = s * W + (scol[j] & 0x7fff);      /* pad slots: column 0 of the slab, value 0 */
+                double t = (double)svals[j] * (double)x[col];
+                acc += t;
+                m += fabs(t);
+                if (scol[j] & 0x8000u) break;
+            }
+            P[pair] = acc;
+            Pmag[pair] = m;
+            ++pair;
+        }
+    (void)N;
+    for (int64_t i = 0; i < rows; ++i) {
+        double acc = 0.0, m = 0.0;
+        for (int64_t q = qpos[i]; q < qpos[i + 1]; ++q) { acc += P[qidx[q]]; m += Pmag[qidx[q]]; }
+        y[i] = acc;
+        if (mag) mag[i] = m;
+    }
+}
