@@ -365,6 +365,81 @@ int psk_spmm_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t
                           const int32_t *crd, const float *vals, const float *B, int32_t k,
                           int64_t ldb, float *C, int64_t ldc, void *stream);
 
+/*
+ * ---- y = A x over a column-slab copy of A (an analysis step, then products) ----
+ *
+ * Section 8.6 of the paper obtains locality by tiling: split a loop and move its outer part outward;
+ * Section 3 lets the position cut be taken in any coordinate hierarchy.  Here the column loop j is split
+ * by slabs of PSK_SLAB_COLS columns, jo = j / PSK_SLAB_COLS moves outermost and A is stored once in that
+ * order: three levels (jo dense, i compressed, ji compressed) whose leaf positions ("slots") are the CSR
+ * positions bucketed stably by slab.  The leaf position space is divided into equal pieces as in
+ * psk_spmv_csr_divide, but a piece needs one slab of x only, which a workgroup keeps in on-chip memory, so
+ * the gathers of x never leave the compute unit.  Meant for matrices whose columns are scattered over an x
+ * that exceeds the caches (where a gather costs a cache-line request per entry); for banded matrices
+ * psk_spmv_csr is the better choice.
+ *
+ * Structure (psk_slab; the arrays live in the caller's `mem`, the struct itself is host memory):
+ *   - every slab is padded with empty slots (value 0, column 0) to a multiple of PSK_SLAB_CHUNK slots;
+ *     nslots = all slots, nchunks = nslots / PSK_SLAB_CHUNK; slab_chunk[s] = first chunk of slab s
+ *     (nslabs + 1 entries);
+ *   - a pair is a maximal run of slots of one row inside one chunk; svals[j] / scol[j] hold a slot's value
+ *     and its column inside the slab (low 15 bits), bit 15 of scol[j] is set on the last slot of a pair;
+ *     chunk_pair[c] = index of the pair of chunk c's first slot (nchunks + 1 entries, last = npairs);
+ *   - qpos[rows + 1], qidx[nq]: the pairs of each row, in the order of their first slots in the CSR;
+ *     qtile_row: the position cut (psk_partition_csr) of (qpos, nq) with tiles of `tile` pairs.
+ * Product: step 1 writes P[pair] = sum of value * x over the pair's slots; step 2 is y = (qpos, qidx) * P
+ * with unit values through the tile kernel, carries and fix-up of psk_spmv_csr.  Deterministic; same
+ * result bar as psk_spmv_csr.  Columns inside a row need not be sorted or distinct.
+ *
+ * Limits: cols <= 8192 * PSK_SLAB_COLS, nnz + 511 * nslabs < 2^31, nslabs * ceil(nnz / 2048) <= 2^30
+ * (PSK_ERR_UNSUPPORTED / PSK_ERR_SIZE otherwise).
+ */
+#define PSK_SLAB_COLS 32736
+#define PSK_SLAB_CHUNK 512
+typedef struct psk_slab {
+    int64_t rows, cols, nnz;
+    int64_t nslabs, nslots, nchunks, npairs, nq;
+    int32_t slab_cols, chunk, tile, reserved;
+    const float *svals;          /* [nslots]  device */
+    const uint16_t *scol;        /* [nslots]  device */
+    const int32_t *chunk_pair;   /* [nchunks + 1] device */
+    const int32_t *slab_chunk;   /* [nslabs + 1]  device */
+    const int32_t *qpos;         /* [rows + 1]    device */
+    const int32_t *qidx;         /* [nq]          device */
+    const int32_t *qtile_row;    /* [ceil(nq / tile) + 1] device */
+} psk_slab;
+
+/* Bytes of device memory for the structure of a rows x cols matrix with nnz entries (an upper bound: the
+ * exact size depends on how the entries fall into slabs and chunks; about 10 bytes per entry + 4 per row);
+ * 0 when the sizes are outside the limits above. */
+size_t psk_slab_mem_bytes(int64_t rows, int64_t cols, int64_t nnz);
+/* Bytes of scratch memory psk_slab_build_csr needs (about 20 bytes per entry); free to reuse afterwards. */
+size_t psk_slab_build_workspace_bytes(int64_t rows, int64_t cols, int64_t nnz);
+/* Bytes of workspace a product over S needs (the pair sums and the carry records); 0 if S is NULL. */
+size_t psk_slab_spmv_workspace_bytes(const psk_slab *S);
+
+/*
+ * The analysis step: builds the structure from a CSR matrix, entirely on the device (a histogram of the
+ * slabs per block of 2048 positions, prefix sums, a stable scatter, pair flags and their prefix sums, the
+ * row lists and their position cut).  `mem` (psk_slab_mem_bytes, 256-byte aligned) receives the arrays and
+ * must stay allocated while *out is used; `workspace` (psk_slab_build_workspace_bytes, 256-byte aligned) is
+ * scratch.  *out (HOST pointer) receives the sizes and the device pointers.  pos, crd, vals: as for
+ * psk_spmv_csr (same unchecked preconditions).  This call SYNCHRONISES `stream` (it reads three counts
+ * back).  The structure depends only on A: build once, multiply many times.
+ */
+int psk_slab_build_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                       const float *vals, void *mem, size_t mem_bytes, void *workspace, size_t workspace_bytes,
+                       psk_slab *out, void *stream);
+
+/*
+ * y = A x over the structure: x has S->cols entries, y S->rows entries (assigned, rows without entries
+ * become +0).  `workspace`: psk_slab_spmv_workspace_bytes(S), 256-byte aligned; products that may overlap in
+ * time need separate workspaces, the structure itself is only read.  Enqueues three kernels on `stream`
+ * (pair sums, row sums, carry fix-up) and returns; allocates nothing, never synchronises.
+ */
+int psk_spmv_slab(const psk_slab *S, const float *x, float *y, void *workspace, size_t workspace_bytes,
+                  void *stream);
+
 #ifdef __cplusplus
 }
 #endif

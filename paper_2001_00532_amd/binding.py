@@ -28,7 +28,19 @@ EXPORTS = [
     "psk_spmv_csr_rowsplit", "psk_spmm_csr_rowsplit", "psk_spmv_csr_atomics", "psk_mttkrp_csf3",
     "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64", "psk_spmv_dcsr", "psk_spmv_csr_divide", "psk_suggest_schedule_csr", "psk_default_tile_bcsr", "psk_validate_csr",
     "psk_spmv_csr_static", "psk_static_scratch_bytes",
+    "psk_slab_mem_bytes", "psk_slab_build_workspace_bytes", "psk_slab_spmv_workspace_bytes", "psk_slab_build_csr",
+    "psk_spmv_slab",
 ]
+
+
+PSK_SLAB_COLS, PSK_SLAB_CHUNK = 32736, 512
+
+
+class psk_slab(ctypes.Structure):
+    """Mirror of the C struct psk_slab (host memory; the pointers are device addresses)."""
+    _fields_ = [(n, ctypes.c_int64) for n in ("rows", "cols", "nnz", "nslabs", "nslots", "nchunks", "npairs", "nq")] + \
+               [(n, ctypes.c_int32) for n in ("slab_cols", "chunk", "tile", "reserved")] + \
+               [(n, ctypes.c_void_p) for n in ("svals", "scol", "chunk_pair", "slab_chunk", "qpos", "qidx", "qtile_row")]
 
 
 class PskError(RuntimeError):
@@ -61,6 +73,14 @@ def lib() -> ctypes.CDLL:
         L.psk_spmv_csr_static.argtypes = [i64, i64, i64, p, p, p, p, p, i32, i32, p]
         L.psk_spmv_csr_static.restype = ci
         L.psk_static_scratch_bytes.argtypes, L.psk_static_scratch_bytes.restype = [], sz
+        L.psk_slab_mem_bytes.argtypes, L.psk_slab_mem_bytes.restype = [i64, i64, i64], sz
+        L.psk_slab_build_workspace_bytes.argtypes, L.psk_slab_build_workspace_bytes.restype = [i64, i64, i64], sz
+        L.psk_slab_spmv_workspace_bytes.argtypes = [ctypes.POINTER(psk_slab)]
+        L.psk_slab_spmv_workspace_bytes.restype = sz
+        L.psk_slab_build_csr.argtypes = [i64, i64, i64, p, p, p, p, sz, p, sz, ctypes.POINTER(psk_slab), p]
+        L.psk_slab_build_csr.restype = ci
+        L.psk_spmv_slab.argtypes = [ctypes.POINTER(psk_slab), p, p, p, sz, p]
+        L.psk_spmv_slab.restype = ci
         L.psk_spmm_csr.argtypes = [i64, i64, i64, p, p, p, p, i32, i64, p, i64, i32, ci, p, sz, p]
         L.psk_spmm_csr.restype = ci
         L.psk_spmv_bcsr.argtypes = [i64, i64, i64, i32, p, p, p, p, p, i32, ci, p, sz, p]
@@ -367,3 +387,60 @@ def psk_spmm_csr_rowsplit(rows, cols, nnz, pos, crd, vals, B, C, stream=None):
                                      int(B.stride(0)), _ptr(C, torch.float32), int(C.stride(0)), _stream(stream))
     _check(st, "psk_spmm_csr_rowsplit")
     return C
+
+
+class Slab:
+    """A built column-slab structure: the C struct (`desc`) plus the device memory that holds its arrays."""
+
+    def __init__(self, desc, mem):
+        self.desc, self.mem = desc, mem
+
+    def array(self, name):
+        """Device view of one array of the structure (for inspection and tests)."""
+        d = self.desc
+        dtype, n = {"svals": (torch.float32, d.nslots), "scol": (torch.int16, d.nslots),
+                    "chunk_pair": (torch.int32, d.nchunks + 1), "slab_chunk": (torch.int32, d.nslabs + 1),
+                    "qpos": (torch.int32, d.rows + 1), "qidx": (torch.int32, d.nq),
+                    "qtile_row": (torch.int32, psk_num_tiles(d.nq, d.tile) + 1)}[name]
+        off = int(getattr(d, name)) - self.mem.data_ptr()
+        size = n * torch.empty((), dtype=dtype).element_size()
+        return self.mem[off:off + size].view(dtype)
+
+
+def psk_slab_mem_bytes(rows, cols, nnz) -> int:
+    return int(lib().psk_slab_mem_bytes(int(rows), int(cols), int(nnz)))
+
+
+def psk_slab_build_workspace_bytes(rows, cols, nnz) -> int:
+    return int(lib().psk_slab_build_workspace_bytes(int(rows), int(cols), int(nnz)))
+
+
+def psk_slab_build_csr(rows, cols, nnz, pos, crd, vals, mem=None, ws=None, stream=None) -> Slab:
+    """Builds the column-slab structure of a CSR matrix on the device (synchronises the stream)."""
+    nm, nw = psk_slab_mem_bytes(rows, cols, nnz), psk_slab_build_workspace_bytes(rows, cols, nnz)
+    if nm == 0 or nw == 0:
+        raise PskError(5, "psk_slab_build_csr (sizes outside the limits of the slab structure)")
+    if mem is None:
+        mem = _alloc_bytes(nm, pos.device, stream)
+    if ws is None:
+        ws = _alloc_bytes(nw, pos.device, stream)
+    desc = psk_slab()
+    st = lib().psk_slab_build_csr(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
+                                  _ptr(vals, torch.float32), _ptr(mem), mem.numel(), _ptr(ws), ws.numel(),
+                                  ctypes.byref(desc), _stream(stream))
+    _check(st, "psk_slab_build_csr")
+    return Slab(desc, mem)
+
+
+def psk_slab_spmv_workspace(S: Slab, device="cuda", stream=None):
+    n = int(lib().psk_slab_spmv_workspace_bytes(ctypes.byref(S.desc)))
+    return _alloc_bytes(max(n, 256), device, stream)
+
+
+def psk_spmv_slab(S: Slab, x, y, ws=None, stream=None):
+    if ws is None:
+        ws = psk_slab_spmv_workspace(S, x.device if x is not None else y.device, stream)
+    st = lib().psk_spmv_slab(ctypes.byref(S.desc), _ptr(x, torch.float32), _ptr(y, torch.float32), _ptr(ws), ws.numel(),
+                             _stream(stream))
+    _check(st, "psk_spmv_slab")
+    return y

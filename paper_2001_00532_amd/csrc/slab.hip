@@ -1,0 +1,514 @@
+// Column-slab hierarchy of a CSR matrix: the analysis step that builds it and the first step of the
+// SpMV over it.
+//
+// Why: on this chip a 4-byte gather of x that misses the 32 KB L1 costs one 64-byte request slot of the
+// L1's miss path whatever the table's size, and a row-ordered CSR with scattered columns misses almost
+// always.  Section 8.6 of the paper gets locality by tiling (split a loop, move the outer part outward);
+// Section 3 lets the position cut be taken in any coordinate hierarchy.  Here the column loop j is split
+// by a slab of PSK_SLAB_COLS columns, jo = j / PSK_SLAB_COLS moves outermost and A is STORED in that
+// order once (three levels: jo dense, i compressed, ji compressed).  The position space of the leaf
+// level is then cut into equal pieces as before, but a piece now needs only one slab of x, which a
+// workgroup keeps in on-chip memory (128 KB of the CU's 160 KB): gathers become LDS reads.
+//
+// Structure (all built here, on the device; the CPU oracle builds the same arrays from the definition):
+//   slots   = the stored entries sorted by (slab, CSR position): a stable bucketing; every slab is
+//             padded to a multiple of PSK_SLAB_CHUNK slots so that a chunk never crosses a slab;
+//   pair    = a maximal run of slots of one row inside one chunk; scol bit 15 marks a pair's last slot;
+//   step 1  : P[pair] = sum of value * x over the pair's slots            (k_slab_pairs, this file)
+//   step 2  : y[i] = sum of P over the pairs of row i, listed by (qpos, qidx): the ordinary position-cut
+//             SpMV kernel with unit values (k_spmv_pos, VARIANT 6).
+// A chunk is one wave's unit of work: no sum crosses a chunk, so step 1 needs no communication between
+// waves, no carries and no barrier except when a workgroup moves on to the next slab.
+#include "psk_dev.h"
+#include "psk_internal.h"
+
+namespace psk {
+
+constexpr int SLAB_W = kSlabCols;
+constexpr int SLAB_CH = kSlabChunk;
+constexpr int BUILD_BT = kSlabBuildBlock;     // CSR positions per block of the bucketing kernels
+
+// ------------------------------------------------------------------ DPP scans over the 64 lanes of a wave
+template <int CTRL, int ROWMASK>
+__device__ __forceinline__ int dpp_i(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, ROWMASK, 0xF, false); }
+template <int CTRL, int ROWMASK>
+__device__ __forceinline__ float dpp_f(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROWMASK, 0xF, false));
+}
+// row_shr 1, 2, 4, 8 scan each row of 16 lanes; row_bcast15 hands lane 15 of rows 0 and 2 to rows 1 and 3,
+// row_bcast31 hands lane 31 to rows 2 and 3.  Lanes without a source receive 0.
+__device__ __forceinline__ int wave_scan_add(int v)
+{
+    v += dpp_i<0x111, 0xF>(v);
+    v += dpp_i<0x112, 0xF>(v);
+    v += dpp_i<0x114, 0xF>(v);
+    v += dpp_i<0x118, 0xF>(v);
+    v += dpp_i<0x142, 0xA>(v);
+    v += dpp_i<0x143, 0xC>(v);
+    return v;
+}
+// Inclusive segmented sum: a lane with f != 0 starts afresh (takes nothing from the lanes below it).
+__device__ __forceinline__ float wave_segscan(float v, int f)
+{
+#define PSK_SEG_STEP(CTRL, MASK)                       \
+    {                                                  \
+        const float pv = dpp_f<CTRL, MASK>(v);         \
+        const int pf = dpp_i<CTRL, MASK>(f);           \
+        v = f ? v : v + pv;                            \
+        f |= pf;                                       \
+    }
+    PSK_SEG_STEP(0x111, 0xF) PSK_SEG_STEP(0x112, 0xF) PSK_SEG_STEP(0x114, 0xF) PSK_SEG_STEP(0x118, 0xF)
+    PSK_SEG_STEP(0x142, 0xA) PSK_SEG_STEP(0x143, 0xC)
+#undef PSK_SEG_STEP
+    return v;
+}
+
+// ------------------------------------------------------------------ step 1 of the product
+// Persistent workgroups: workgroup b owns the chunks [b*cpw, (b+1)*cpw) (the position space DIVIDED into
+// equal pieces, Section 5), walks them slab by slab, loads the slab's part of x into LDS once and lets its
+// 16 waves take the chunks of that slab round-robin.  A lane owns 8 consecutive slots (two 16-byte loads of
+// values, one of columns); the next chunk's loads are issued before the current one is processed.
+// Inside a chunk: lane-serial sums, then a segmented DPP scan hands each lane the open sum of the lanes
+// below it; a pair's sum is stored by the lane that holds its last slot, at chunk_pair[c] + (number of
+// pair ends before it in the chunk).
+__global__ __launch_bounds__(1024) void k_slab_pairs(const float *__restrict__ svals,
+                                                     const unsigned short *__restrict__ scol,
+                                                     const int *__restrict__ chunk_pair,
+                                                     const int *__restrict__ slab_chunk,
+                                                     const float *__restrict__ x, float *__restrict__ P, int cols,
+                                                     int nslabs, int nchunks, int cpw)
+{
+    constexpr int WAVES = 16;
+    __shared__ float xs[SLAB_W];
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
+    int c0 = blockIdx.x * cpw;
+    const int c1 = min(c0 + cpw, nchunks);
+    if (c0 >= c1) return;
+    int s;      // slab of chunk c0: max { s : slab_chunk[s] <= c0 }
+    {
+        int lo = 0, hi = nslabs;
+        while (lo < hi) {
+            const int mid = lo + ((hi - lo + 1) >> 1);
+            if (slab_chunk[mid] <= c0) lo = mid; else hi = mid - 1;
+        }
+        s = lo;
+    }
+    while (c0 < c1) {
+        while (slab_chunk[s + 1] <= c0) ++s;            // skips empty slabs; c0 < nchunks = slab_chunk[nslabs]
+        const int ce = min(c1, slab_chunk[s + 1]);
+        __syncthreads();                                  // the previous slab's window is no longer read
+        const long long xb = (long long)s * SLAB_W;
+        const int wlen = (int)min((long long)SLAB_W, (long long)cols - xb);
+        const bool x16 = (reinterpret_cast<uintptr_t>(x + xb) & 15) == 0;
+        for (int i = tid * 4; i < wlen; i += 4096) {
+            if (x16 && i + 4 <= wlen) {
+                *reinterpret_cast<v4f *>(&xs[i]) = *reinterpret_cast<const v4f *>(x + xb + i);
+            } else {
+                for (int j = i; j < i + 4 && j < wlen; ++j) xs[j] = x[xb + j];
+            }
+        }
+        __syncthreads();
+        int c = c0 + wave;
+        v4f va = {0, 0, 0, 0}, vb = {0, 0, 0, 0};
+        v4i cc = {0, 0, 0, 0};
+        int pb = 0;
+        if (c < ce) {
+            const long long b = (long long)c * SLAB_CH + lane * 8;
+            va = ld_stream(reinterpret_cast<const v4f *>(svals + b));
+            vb = ld_stream(reinterpret_cast<const v4f *>(svals + b + 4));
+            cc = ld_stream(reinterpret_cast<const v4i *>(scol + b));
+            pb = chunk_pair[c];
+        }
+        for (; c < ce; c += WAVES) {
+            const v4f a0 = va, a1 = vb;
+            const v4i q = cc;
+            const int pbase = pb;
+            const int cn = c + WAVES;
+            if (cn < ce) {
+                const long long b = (long long)cn * SLAB_CH + lane * 8;
+                va = ld_stream(reinterpret_cast<const v4f *>(svals + b));
+                vb = ld_stream(reinterpret_cast<const v4f *>(svals + b + 4));
+                cc = ld_stream(reinterpret_cast<const v4i *>(scol + b));
+                pb = chunk_pair[cn];
+            }
+            const unsigned w[4] = {(unsigned)q.x, (unsigned)q.y, (unsigned)q.z, (unsigned)q.w};
+            const float v[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+            float p[8];
+            int e[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const unsigned h = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu);
+                e[j] = (int)(h >> 15);
+                p[j] = v[j] * xs[h & 0x7fffu];
+            }
+            int cnt = 0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) cnt += e[j];
+            const int first = pbase + wave_scan_add(cnt) - cnt;     // index of this lane's first pair end
+            int rank = first;
+            float run = 0.0f, head = 0.0f;
+            bool seen = false;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                run += p[j];
+                if (e[j]) {
+                    if (!seen) { head = run; seen = true; }
+                    else { ++rank; P[rank] = run; }           // a pair that lies inside this lane
+                    run = 0.0f;
+                }
+            }
+            // `run` is the lane's open sum; the lane below hands over the open sum of all lanes below
+            const float open = wave_segscan(run, seen ? 1 : 0);
+            const float carry = __shfl_up(open, 1, WAVE);
+            if (seen) P[first] = (lane == 0) ? head : carry + head;
+        }
+        c0 = ce;
+        ++s;
+    }
+}
+
+hipError_t launch_slab_pairs(const float *svals, const uint16_t *scol, const int32_t *chunk_pair,
+                             const int32_t *slab_chunk, const float *x, float *P, int32_t cols, int32_t nslabs,
+                             int32_t nchunks, int32_t nwg, hipStream_t s)
+{
+    if (nchunks <= 0) return hipSuccess;
+    if (nwg < 1) nwg = 1;
+    const int cpw = (nchunks + nwg - 1) / nwg;
+    const int grid = (nchunks + cpw - 1) / cpw;
+    PSK_LAUNCH(k_slab_pairs, dim3(grid), dim3(1024), 0, s, svals, scol, chunk_pair, slab_chunk, x, P, cols, nslabs,
+               nchunks, cpw);
+    return take_launch_status();
+}
+
+// ------------------------------------------------------------------ prefix sums over int32 arrays
+// Three kernels: sums of blocks of 4096, a single-workgroup scan of those sums, then every block scans its
+// own elements on top of its offset.  In place (out == in) is allowed.
+constexpr int SCAN_EPT = 16, SCAN_BLOCK = 256 * SCAN_EPT;
+
+__device__ __forceinline__ int block_scan_256(int v, int *s_w, int *total)
+{
+    // inclusive scan of one value per thread over 256 threads; s_w has 4 ints
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+    const int inc = wave_scan_add(v);
+    if (lane == WAVE - 1) s_w[wave] = inc;
+    __syncthreads();
+    int off = 0;
+    for (int w = 0; w < wave; ++w) off += s_w[w];
+    *total = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+    __syncthreads();
+    return inc + off;
+}
+
+__global__ __launch_bounds__(256) void k_scan_reduce(const int *__restrict__ in, long long n, int *__restrict__ bsum)
+{
+    __shared__ int s_w[4];
+    const long long base = (long long)blockIdx.x * SCAN_BLOCK + threadIdx.x * SCAN_EPT;
+    int t = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_EPT; ++i) t += base + i < n ? in[base + i] : 0;
+    int total;
+    block_scan_256(t, s_w, &total);
+    if (threadIdx.x == 0) bsum[blockIdx.x] = total;
+}
+
+// exclusive scan of bsum[0 .. nb) in place, by one workgroup of 256 threads
+__global__ __launch_bounds__(256) void k_scan_spine(int *__restrict__ bsum, long long nb)
+{
+    __shared__ int s_w[4];
+    int carry = 0;
+    for (long long b0 = 0; b0 < nb; b0 += 256) {
+        const long long i = b0 + threadIdx.x;
+        const int v = i < nb ? bsum[i] : 0;
+        int total;
+        const int inc = block_scan_256(v, s_w, &total);
+        if (i < nb) bsum[i] = carry + inc - v;
+        carry += total;
+    }
+}
+
+template <bool INCLUSIVE>
+__global__ __launch_bounds__(256) void k_scan_apply(const int *__restrict__ in, int *__restrict__ out, long long n,
+                                                    const int *__restrict__ bsum)
+{
+    __shared__ int s_w[4];
+    const long long base = (long long)blockIdx.x * SCAN_BLOCK + threadIdx.x * SCAN_EPT;
+    int v[SCAN_EPT];
+    int t = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_EPT; ++i) { v[i] = base + i < n ? in[base + i] : 0; t += v[i]; }
+    int total;
+    const int inc = block_scan_256(t, s_w, &total);
+    int run = bsum[blockIdx.x] + inc - t;
+#pragma unroll
+    for (int i = 0; i < SCAN_EPT; ++i) {
+        if (INCLUSIVE) run += v[i];
+        if (base + i < n) out[base + i] = run;
+        if (!INCLUSIVE) run += v[i];
+    }
+}
+
+size_t scan_tmp_ints(int64_t n) { return (size_t)((n + SCAN_BLOCK - 1) / SCAN_BLOCK) + 1; }
+
+static void launch_scan(const int32_t *in, int32_t *out, int64_t n, int32_t *bsum, bool inclusive, hipStream_t s)
+{
+    if (n <= 0) return;
+    const long long nb = (n + SCAN_BLOCK - 1) / SCAN_BLOCK;
+    PSK_LAUNCH(k_scan_reduce, dim3((unsigned)nb), dim3(256), 0, s, in, (long long)n, bsum);
+    PSK_LAUNCH(k_scan_spine, dim3(1), dim3(256), 0, s, bsum, nb);
+    if (inclusive) PSK_LAUNCH(k_scan_apply<true>, dim3((unsigned)nb), dim3(256), 0, s, in, out, (long long)n, bsum);
+    else PSK_LAUNCH(k_scan_apply<false>, dim3((unsigned)nb), dim3(256), 0, s, in, out, (long long)n, bsum);
+}
+
+// ------------------------------------------------------------------ the analysis step: CSR -> slab hierarchy
+// H[s * nblk + b] = number of positions of block b (BUILD_BT consecutive CSR positions) that fall into slab s.
+__global__ __launch_bounds__(256) void k_slab_hist(int nnz, const int *__restrict__ crd, int nslabs, int nblk,
+                                                   int *__restrict__ H)
+{
+    extern __shared__ int hist[];
+    for (int s = threadIdx.x; s < nslabs; s += 256) hist[s] = 0;
+    __syncthreads();
+    const int b = blockIdx.x;
+    const long long p0 = (long long)b * BUILD_BT;
+    for (int i = threadIdx.x; i < BUILD_BT; i += 256)
+        if (p0 + i < nnz) atomicAdd(&hist[crd[p0 + i] / SLAB_W], 1);
+    __syncthreads();
+    for (int s = threadIdx.x; s < nslabs; s += 256) H[(long long)s * nblk + b] = hist[s];
+}
+
+// E = exclusive scan of H (E[nslabs * nblk] = nnz).  One workgroup: slab s holds E[(s+1)*nblk] - E[s*nblk]
+// positions, padded to a multiple of the chunk; slab_chunk = exclusive scan of the padded sizes in chunks.
+// meta[0] = number of slots.
+__global__ __launch_bounds__(256) void k_slab_bases(const int *__restrict__ E, int nslabs, int nblk,
+                                                    int *__restrict__ slab_chunk, int *__restrict__ meta)
+{
+    __shared__ int s_w[4];
+    int carry = 0;
+    for (int s0 = 0; s0 < nslabs; s0 += 256) {
+        const int s = s0 + threadIdx.x;
+        int chunks = 0;
+        if (s < nslabs) {
+            const int cnt = E[(long long)(s + 1) * nblk] - E[(long long)s * nblk];
+            chunks = (cnt + SLAB_CH - 1) / SLAB_CH;
+        }
+        int total;
+        const int inc = block_scan_256(chunks, s_w, &total);
+        if (s < nslabs) slab_chunk[s] = carry + inc - chunks;
+        carry += total;
+    }
+    if (threadIdx.x == 0) {
+        slab_chunk[nslabs] = carry;
+        meta[0] = carry * SLAB_CH;
+    }
+}
+
+// The pad slots of slab s (fewer than a chunk): value 0, column 0, no row, no source position.
+__global__ __launch_bounds__(64) void k_slab_pads(const int *__restrict__ E, int nblk, const int *__restrict__ slab_chunk,
+                                                  float *__restrict__ svals, unsigned short *__restrict__ scol,
+                                                  int *__restrict__ srow, int *__restrict__ src)
+{
+    const int s = blockIdx.x;
+    const int cnt = E[(long long)(s + 1) * nblk] - E[(long long)s * nblk];
+    const long long lo = (long long)slab_chunk[s] * SLAB_CH + cnt, hi = (long long)slab_chunk[s + 1] * SLAB_CH;
+    for (long long j = lo + threadIdx.x; j < hi; j += 64) {
+        svals[j] = 0.0f;
+        scol[j] = 0;
+        srow[j] = -1;
+        src[j] = -1;
+    }
+}
+
+// Stable bucketing.  One wave per block of BUILD_BT CSR positions, taken 64 at a time in order; off[s] is the
+// slot the block's next position of slab s goes to.  The lanes of one step that share a slab are ranked by
+// lane number (ballot), so the order of the CSR is kept inside every slab.  The row of a position is the
+// largest r with pos[r] <= p, searched between the rows of the block's first and last position
+// (tile_row = the position cut of pos with tiles of BUILD_BT).
+__global__ __launch_bounds__(64) void k_slab_scatter(int rows, int nnz, const int *__restrict__ pos,
+                                                     const int *__restrict__ crd, const float *__restrict__ vals,
+                                                     const int *__restrict__ tile_row, const int *__restrict__ E,
+                                                     const int *__restrict__ slab_chunk, int nslabs, int nblk,
+                                                     float *__restrict__ svals, unsigned short *__restrict__ scol,
+                                                     int *__restrict__ srow, int *__restrict__ src)
+{
+    extern __shared__ int off[];
+    const int b = blockIdx.x, lane = threadIdx.x;
+    for (int s = lane; s < nslabs; s += WAVE)
+        off[s] = slab_chunk[s] * SLAB_CH + (E[(long long)s * nblk + b] - E[(long long)s * nblk]);
+    __syncthreads();
+    const long long p0 = (long long)b * BUILD_BT;
+    const int r_lo = tile_row[b], r_hi = tile_row[b + 1];
+    for (int it = 0; it < BUILD_BT / WAVE; ++it) {
+        const long long pl = p0 + it * WAVE + lane;
+        const bool valid = pl < nnz;
+        const int p = valid ? (int)pl : 0;
+        int c = 0, s = -1, r = 0;
+        float v = 0.0f;
+        if (valid) {
+            c = crd[p];
+            v = vals[p];
+            s = c / SLAB_W;
+            int lo = r_lo, hi = r_hi;
+            while (lo < hi) {
+                const int mid = lo + ((hi - lo + 1) >> 1);
+                if (pos[mid] <= p) lo = mid; else hi = mid - 1;
+            }
+            r = lo;
+        }
+        int dst = -1;
+        unsigned long long todo = __ballot(valid);
+        while (todo) {
+            const int leader = __ffsll((long long)todo) - 1;
+            const int sl = __shfl(s, leader, WAVE);
+            const unsigned long long same = __ballot(valid && s == sl);
+            if (valid && s == sl) dst = off[sl] + __popcll(same & ((1ull << lane) - 1ull));
+            __syncthreads();                                  // one wave: orders the LDS read before the update
+            if (lane == leader) off[sl] += __popcll(same);
+            __syncthreads();
+            todo &= ~same;
+        }
+        if (valid) {
+            svals[dst] = v;
+            scol[dst] = (unsigned short)(c - s * SLAB_W);
+            srow[dst] = r;
+            src[dst] = p;
+        }
+    }
+}
+
+// F[j] = 1 when slot j starts a pair (first slot of a chunk, or another row than the slot before), for
+// j < nslots = meta[0]; 0 beyond (the array is scanned over its whole allocated length).
+__global__ __launch_bounds__(256) void k_slab_starts(const int *__restrict__ meta, const int *__restrict__ srow,
+                                                     long long nmax, int *__restrict__ F)
+{
+    const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (j >= nmax) return;
+    const int n = meta[0];
+    int f = 0;
+    if (j < n) f = (j % SLAB_CH == 0 || srow[j] != srow[j - 1]) ? 1 : 0;
+    F[j] = f;
+}
+
+// I = inclusive scan of F: slot j belongs to pair I[j] - 1.  Sets the end-of-pair bit, the chunk table, and
+// marks the CSR position of every real pair's first slot (mark[p] = 1, pair_at[p] = pair) for the row lists.
+// meta[1] = number of pairs.
+__global__ __launch_bounds__(256) void k_slab_finish(const int *__restrict__ meta_in, const int *__restrict__ I,
+                                                     const int *__restrict__ srow, const int *__restrict__ src,
+                                                     unsigned short *__restrict__ scol, int *__restrict__ chunk_pair,
+                                                     int *__restrict__ mark, int *__restrict__ pair_at,
+                                                     int *__restrict__ meta)
+{
+    const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
+    const int n = meta_in[0];
+    if (j >= n) return;
+    const int mine = I[j];
+    const bool start = j == 0 || I[j - 1] != mine;
+    const bool end = j == n - 1 || I[j + 1] != mine;
+    if (end) scol[j] = (unsigned short)(scol[j] | 0x8000u);
+    if (j % SLAB_CH == 0) chunk_pair[j / SLAB_CH] = mine - 1;
+    if (j == n - 1) {
+        chunk_pair[n / SLAB_CH] = mine;
+        meta[1] = mine;
+    }
+    if (start && srow[j] >= 0) {
+        mark[src[j]] = 1;
+        pair_at[src[j]] = mine - 1;
+    }
+}
+
+// R = exclusive scan of mark over nnz + 1 entries: R[p] = number of pairs whose first slot comes from a CSR
+// position below p.  Rows list their pairs in that order: qpos[r] = R[pos[r]], qidx[R[p]] = pair_at[p].
+// meta[2] = number of listed pairs.
+__global__ __launch_bounds__(256) void k_slab_rows(int rows, int nnz, const int *__restrict__ pos,
+                                                   const int *__restrict__ R, const int *__restrict__ pair_at,
+                                                   int *__restrict__ qpos, int *__restrict__ qidx,
+                                                   int *__restrict__ meta)
+{
+    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (g < nnz) {
+        const int a = R[g];
+        if (R[g + 1] != a) qidx[a] = pair_at[g];
+    }
+    if (g <= rows) qpos[g] = R[pos[g]];
+    if (g == 0) meta[2] = R[nnz];
+}
+
+__global__ __launch_bounds__(256) void k_fill_int(int *__restrict__ p, long long n, int v)
+{
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+hipError_t launch_fill_int(int32_t *p, int64_t n, int32_t v, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    PSK_LAUNCH(k_fill_int, dim3((unsigned)blocks), dim3(256), 0, s, p, (long long)n, v);
+    return take_launch_status();
+}
+
+SlabBuildSpace carve_slab_build(void *base, int64_t rows, int64_t cols, int64_t nnz)
+{
+    (void)rows;
+    SlabBuildSpace w;
+    const int64_t S = (cols + SLAB_W - 1) / SLAB_W;
+    const int64_t nblk = (nnz + BUILD_BT - 1) / BUILD_BT;
+    const int64_t nmax = slab_max_slots(cols, nnz);
+    char *p = static_cast<char *>(base);
+    size_t o = 0;
+    auto take = [&](size_t bytes) { char *q = p + o; o += align256(bytes); return q; };
+    w.meta = reinterpret_cast<int32_t *>(take(256));
+    w.tile_row = reinterpret_cast<int32_t *>(take((size_t)(nblk + 1) * 4));
+    w.H = reinterpret_cast<int32_t *>(take((size_t)(S * nblk + 1) * 4));
+    w.srow = reinterpret_cast<int32_t *>(take((size_t)(nmax + 1) * 4));
+    w.src = reinterpret_cast<int32_t *>(take((size_t)(nmax + 1) * 4));
+    w.F = reinterpret_cast<int32_t *>(take((size_t)(nmax + 1) * 4));
+    w.mark = reinterpret_cast<int32_t *>(take((size_t)(nnz + 1) * 4));
+    w.pair_at = reinterpret_cast<int32_t *>(take((size_t)(nnz + 1) * 4));
+    size_t tmp = scan_tmp_ints(S * nblk + 1);
+    if (scan_tmp_ints(nmax + 1) > tmp) tmp = scan_tmp_ints(nmax + 1);
+    if (scan_tmp_ints(nnz + 1) > tmp) tmp = scan_tmp_ints(nnz + 1);
+    w.scan_tmp = reinterpret_cast<int32_t *>(take(tmp * 4));
+    w.bytes = o;
+    return w;
+}
+
+// Enqueues the whole analysis on `s`.  When it has run, meta[0..2] = {slots, pairs, listed pairs}.
+hipError_t launch_slab_build(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                             const float *vals, const SlabBuildSpace &w, float *svals, uint16_t *scol,
+                             int32_t *chunk_pair, int32_t *slab_chunk, int32_t *qpos, int32_t *qidx, hipStream_t s)
+{
+    const int S = (int)(((int64_t)cols + SLAB_W - 1) / SLAB_W);
+    const int nblk = (int)(((int64_t)nnz + BUILD_BT - 1) / BUILD_BT);
+    const int64_t nmax = slab_max_slots(cols, nnz);
+    unsigned short *scol_d = reinterpret_cast<unsigned short *>(scol);
+    hipError_t e = launch_partition(rows, nnz, pos, BUILD_BT, 0, w.tile_row, s);
+    if (e != hipSuccess) return e;
+    const size_t lds = (size_t)S * 4;
+    PSK_LAUNCH(k_slab_hist, dim3(nblk), dim3(256), (unsigned)lds, s, nnz, crd, S, nblk, w.H);
+    PSK_LAUNCH(k_fill_int, dim3(1), dim3(64), 0, s, w.H + (long long)S * nblk, 1ll, 0);      // the scan's total slot
+    launch_scan(w.H, w.H, (int64_t)S * nblk + 1, w.scan_tmp, false, s);
+    PSK_LAUNCH(k_slab_bases, dim3(1), dim3(256), 0, s, w.H, S, nblk, slab_chunk, w.meta);
+    PSK_LAUNCH(k_slab_pads, dim3(S), dim3(64), 0, s, w.H, nblk, slab_chunk, svals, scol_d, w.srow, w.src);
+    PSK_LAUNCH(k_slab_scatter, dim3(nblk), dim3(64), (unsigned)lds, s, rows, nnz, pos, crd, vals, w.tile_row, w.H,
+               slab_chunk, S, nblk, svals, scol_d, w.srow, w.src);
+    PSK_LAUNCH(k_slab_starts, dim3((unsigned)((nmax + 1 + 255) / 256)), dim3(256), 0, s, w.meta, w.srow,
+               (long long)(nmax + 1), w.F);
+    launch_scan(w.F, w.F, nmax + 1, w.scan_tmp, true, s);
+    {
+        int64_t blocks = ((int64_t)nnz + 1 + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        PSK_LAUNCH(k_fill_int, dim3((unsigned)blocks), dim3(256), 0, s, w.mark, (long long)nnz + 1, 0);
+    }
+    PSK_LAUNCH(k_slab_finish, dim3((unsigned)((nmax + 255) / 256)), dim3(256), 0, s, w.meta, w.F, w.srow, w.src, scol_d,
+               chunk_pair, w.mark, w.pair_at, w.meta);
+    launch_scan(w.mark, w.mark, (int64_t)nnz + 1, w.scan_tmp, false, s);
+    const int64_t span = ((int64_t)nnz > (int64_t)rows + 1 ? (int64_t)nnz : (int64_t)rows + 1);
+    PSK_LAUNCH(k_slab_rows, dim3((unsigned)((span + 255) / 256)), dim3(256), 0, s, rows, nnz, pos, w.mark, w.pair_at,
+               qpos, qidx, w.meta);
+    return take_launch_status();
+}
+
+}  // namespace psk

@@ -67,6 +67,8 @@ __device__ __forceinline__ void run_select(const RunPlan &p, v4f_u wA, v4f_u wB,
 // 3: one pass without the per-thread temporary and without the unrolled load loop (the ablation of
 //    Section 8.3): each thread walks its positions in a rolled loop, one load -> gather -> multiply -> LDS
 //    store after the other.
+// 6: one pass with unit values: vals is not read (the second step of the product over the column-slab
+//    hierarchy, where the "matrix" only lists which partial sums belong to a row).
 template <int THREADS, int NPT, int MODE, int VARIANT>
 __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nnz, const int *__restrict__ pos,
                                                       const int *__restrict__ crd,
@@ -85,6 +87,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
     constexpr bool VEC = MODE != 0;
     constexpr bool WIN = VARIANT == 1 || VARIANT == 5, ATOM = VARIANT == 2, NOTEMP = VARIANT == 3;
     constexpr bool ROWMAP = VARIANT == 4 || VARIANT == 5;
+    constexpr bool ONES = VARIANT == 6;
     static_assert(NPT % 4 == 0, "NPT must be a multiple of 4");
     __shared__ float sprod[skewed_size<1>(T)];
     __shared__ int slong[MAXLONG * 3];
@@ -129,13 +132,14 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
             for (int g = 0; g < NPT / 4; ++g) {
                 const int off = t0 + (g * THREADS + tid) * 4;
                 cv[g] = ld_stream(reinterpret_cast<const v4i *>(crd + off));
-                vv[g] = ld_stream(reinterpret_cast<const v4f *>(vals + off));
+                if (ONES) vv[g] = v4f{1.0f, 1.0f, 1.0f, 1.0f};
+                else vv[g] = ld_stream(reinterpret_cast<const v4f *>(vals + off));
             }
         } else {
 #pragma unroll
             for (int g = 0; g < NPT; ++g) {
                 cs[g] = ld_stream(crd + t0 + g * THREADS + tid);
-                vs[g] = ld_stream(vals + t0 + g * THREADS + tid);
+                vs[g] = ONES ? 1.0f : ld_stream(vals + t0 + g * THREADS + tid);
             }
         }
     }
@@ -211,7 +215,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
             float pr = 0.0f;
             if (i < cnt) {
                 const int c = crd[t0 + i];
-                if (!WIN || (c >= clo && c < chi)) pr = vals[t0 + i] * x[c];
+                if (!WIN || (c >= clo && c < chi)) pr = ONES ? x[c] : vals[t0 + i] * x[c];
             }
             prod[g] = pr;
         }
@@ -353,6 +357,23 @@ static void launch_pos(int mode, int grid, hipStream_t s, int rows, int cols, in
     else if (mode == 1) { if (variant == 2) PSK_GO(1, 2); else if (variant == 1) PSK_GO(1, 1); else PSK_GO(1, 0); }
     else { if (variant == 2) PSK_GO(0, 2); else if (variant == 1) PSK_GO(0, 1); else PSK_GO(0, 0); }
 #undef PSK_GO
+}
+
+hipError_t launch_spmv_csr_ones(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                                const float *x, float *y, const Workspace &w, hipStream_t s)
+{
+    const int ntiles = (int)(((int64_t)nnz + 2047) / 2048);
+    if (ntiles == 0) return hipSuccess;
+    const int grid = xcd_grid(ntiles);
+    const float *none = nullptr;
+    const int *nomap = nullptr;
+    if ((reinterpret_cast<uintptr_t>(crd) & 15) == 0)
+        PSK_LAUNCH((k_spmv_pos<256, 8, 1, 6>), dim3(grid), dim3(256), 0, s, rows, cols, nnz, pos, crd, none, x, y,
+                   w.tile_row, w.carry_row, w.carry_val, ntiles, 0, cols, 0, nomap, w.tile_cols);
+    else
+        PSK_LAUNCH((k_spmv_pos<256, 8, 0, 6>), dim3(grid), dim3(256), 0, s, rows, cols, nnz, pos, crd, none, x, y,
+                   w.tile_row, w.carry_row, w.carry_val, ntiles, 0, cols, 0, nomap, w.tile_cols);
+    return take_launch_status();
 }
 
 hipError_t launch_spmv_csr_main(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
