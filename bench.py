@@ -43,22 +43,28 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
-# scaled by the copy-kernel calibration; the summaries are under profiles/.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {
-    # (workload, tile, col_passes): bytes per launch of the tile kernel
-    ("powerlaw", 1024, 2): 629236071,      # profiles/k_spmv_pos_powerlaw_2passes.txt
-    ("powerlaw", 2048, 1): 3558251794,     # profiles/k_spmv_pos_powerlaw_1pass.txt
-    ("uniform28", 1024, 2): 697080350,     # profiles/k_spmv_pos_uniform28.txt
-    ("stencil", 2048, 1): 929627715,       # profiles/k_spmv_pos_stencil.txt
-    ("spmm", 512, 1): 8775506057,          # profiles/k_spmm_pos_csr_spmm_k128.txt
-    ("bcsr_spmv", 512, 1): 191721313,      # profiles/k_spmv_bcsr4_bcsr_spmv.txt
-    ("bcsr_spmm", 64, 1): 2411752120,      # profiles/k_spmm_pos_bcsr_spmm_n64.txt
-    ("powerlaw_f64", 1024, 3): 1260169750,  # profiles/k_spmv_pos_f64_powerlaw.txt (per pass)
-    ("stencil_f64", 1024, 1): 1405422169,   # profiles/k_spmv_pos_f64_stencil.txt
-    ("dcsr", 2048, 1): 1606172701 + 268435456 + 20685,   # profiles/k_spmv_pos_dcsr_hypersparse.txt: tile kernel + zero-fill of y
-    ("mttkrp", 2048, 1): 11818681536,      # profiles/k_mttkrp_pos_mttkrp_j64.txt (L2 <-> fabric, j = 64)
-}
+def profile_traffic(workload, tile, col_passes, path="csr"):
+    """HBM-side bytes per product of the timed kernels, read from the rocprofv3 summaries under profiles/
+    (two --pmc runs, FETCH_SIZE and WRITE_SIZE, scaled by the copy-kernel calibration).  A summary carries a line
+        bench-key: workload=W path=P tile=T col_passes=Q traffic_bytes=N
+    for the configuration it was measured on.  Returns (bytes, file name) or (None, note) when no summary
+    matches the configuration that is being run."""
+    import glob
+    import re
+
+    here = os.path.dirname(os.path.abspath(__file__))
+    want = {"workload": workload, "path": path, "tile": str(tile), "col_passes": str(col_passes)}
+    for f in sorted(glob.glob(os.path.join(here, "profiles", "*.txt"))):
+        for line in open(f, errors="replace"):
+            if not line.startswith("bench-key:"):
+                continue
+            kv = dict(re.findall(r"(\w+)=(\S+)", line))
+            if all(kv.get(k) == v for k, v in want.items()) and "traffic_bytes" in kv:
+                return int(kv["traffic_bytes"]), os.path.basename(f)
+    return None, "no rocprofv3 summary under profiles/ for workload=%s path=%s tile=%s col_passes=%s" % (
+        workload, path, tile, col_passes)
+
+
 
 WORKLOADS = {
     "uniform10": (1, "csr_spmv"),
@@ -208,7 +214,7 @@ def bench_mttkrp(args, torch, psk, wl):
     # the roofline is priced on those compulsory bytes.  What the kernel is bound by is the rate at which
     # L2 misses on D rows are served (no-reuse bytes / time, reported beside it).
     achieved = comp / (main_avg * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get(("mttkrp", tile, 1)) if J == 64 else None
+    traffic, traffic_src = profile_traffic("mttkrp", tile, 1) if J == 64 else (None, "measured for j = 64 only")
     rec = {
         "metric": "SpMV/SpMM GFLOP/s and achieved HBM GB/s (% of MI355X peak), 1 GPU",
         "value": round(fl / (wall / args.steps) / 1e9, 3), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -222,7 +228,7 @@ def bench_mttkrp(args, torch, psk, wl):
                              "all": round(statistics.median(all_ms) * 1e3, 2)},
         "roofline": {"bound": "hbm", "kernel": "k_mttkrp_pos", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "algorithmic_bytes": comp, "no_reuse_bytes": noreuse,
+                     "traffic_source": traffic_src, "algorithmic_bytes": comp, "no_reuse_bytes": noreuse,
                      "no_reuse_GBs": round(noreuse / (main_avg * 1e-3) / 1e9, 2),
                      "avg_launch_us": round(main_avg * 1e3, 2), "launches_per_step": 1,
                      "byte_model": "every operand once (factor matrices are cache resident); no_reuse_* counts one "
@@ -295,6 +301,8 @@ def bench_dcsr(args, torch, psk, wl):
     all_ms = time_phase(psk.PSK_PHASE_ALL)
     main_avg = sum(main_ms) / len(main_ms)
     achieved = comp / (main_avg * 1e-3) / 1e9
+    dcsr_traffic, dcsr_traffic_src = (profile_traffic("dcsr", tile, passes) if args.cut == "positions"
+                                      else (None, "not measured for the row-level cut"))
     rec = {
         "metric": "SpMV/SpMM GFLOP/s and achieved HBM GB/s (% of MI355X peak), 1 GPU",
         "value": round(fl / (wall / args.steps) / 1e9, 3), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -311,7 +319,7 @@ def bench_dcsr(args, torch, psk, wl):
         "roofline": {"bound": "hbm", "kernel": "k_fill_zero + " + ("k_spmv_pos" if args.cut == "positions" else "k_spmv_wave_per_row"),
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(("dcsr", tile, passes)) if args.cut == "positions" else None,
+                     "traffic": dcsr_traffic, "traffic_source": dcsr_traffic_src,
                      "algorithmic_bytes": comp,
                      "avg_launch_us": round(main_avg * 1e3, 2), "launches_per_step": 2,
                      "byte_model": "A once + x once + y once (the zero-fill of y is part of the main phase)"},
@@ -349,6 +357,10 @@ def main():
                     help="bcsr_spmv / bcsr_spmm: block edge (the 10^6 x 10^6 matrix with 32 entries per row is re-blocked)")
     ap.add_argument("--f64", action="store_true", help="CSR SpMV workloads: fp64 values, vector and result")
     ap.add_argument("--rank", type=int, default=64, help="mttkrp: number of columns j of the factor matrices")
+    ap.add_argument("--path", choices=["auto", "csr", "slab"], default="auto",
+                    help="CSR SpMV workloads: multiply from the CSR arrays (position cut per call) or from the "
+                         "column-slab copy of A built once by the analysis step; auto = slab when psk_analyze_csr "
+                         "finds the columns scattered over an x larger than the caches, else csr")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--baselines", action="store_true", help="also time the row-split kernels")
     args = ap.parse_args()
@@ -444,18 +456,42 @@ def main():
             col_passes = 1
             if psk.psk_analyze_csr(A.rows, A.cols, A.nnz, sets[0]["pos"], sets[0]["crd"], stream=stream) > 1:
                 col_passes = int(min(4, -(-(8 * A.cols) // (6 << 20))))
+    path = "csr"
+    analysis = None
     if kind == "csr_spmv" and not f64:
-        col_passes = args.col_passes or psk.psk_analyze_csr(A.rows, A.cols, A.nnz, sets[0]["pos"], sets[0]["crd"],
-                                                            stream=stream)
+        suggested = psk.psk_analyze_csr(A.rows, A.cols, A.nnz, sets[0]["pos"], sets[0]["crd"], stream=stream)
+        path = args.path if args.path != "auto" else ("slab" if suggested > 1 and not args.col_passes else "csr")
+        col_passes = args.col_passes or suggested
         if col_passes > 1 and not tile_given:
             tile = 1024      # what tile = 0 selects inside the library when column passes are on
     for s in sets:
         s["ws"] = psk.workspace(op, A.rows, A.nnz, k=k, bs=A.bs, tile=tile, device=dev)
+    csr_tile, csr_passes = tile, col_passes
+    if path == "slab":
+        # the analysis step: once per matrix, outside the timed region like the column-pass probe; its time is
+        # reported beside the product's so that the number of products that repay it can be read off
+        build_ms = []
+        for i, s in enumerate(sets):
+            torch.cuda.synchronize()
+            t_b = time.perf_counter()
+            s["slab"] = psk.psk_slab_build_csr(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], stream=stream)
+            torch.cuda.synchronize()
+            build_ms.append((time.perf_counter() - t_b) * 1e3)
+            s["slab_ws"] = psk.psk_slab_spmv_workspace(s["slab"], dev)
+        d0 = sets[0]["slab"].desc
+        analysis = {"call": "psk_slab_build_csr", "ms_median": round(statistics.median(build_ms), 3),
+                    "ms_first": round(build_ms[0], 3), "builds": len(build_ms),
+                    "slabs": int(d0.nslabs), "slots": int(d0.nslots), "pairs": int(d0.npairs),
+                    "listed_pairs": int(d0.nq), "structure_bytes": int(6 * d0.nslots + 4 * (d0.nchunks + 1) + 4 * (d0.nslabs + 1)
+                                                                   + 4 * (A.rows + 1) + 4 * d0.nq)}
+        tile, col_passes = int(d0.tile), 1
 
     def step(s, phases=psk.PSK_PHASE_ALL):
         if f64:
             psk.psk_spmv_csr_f64(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"], tile=tile,
                                  col_passes=col_passes, phases=phases, ws=s["ws"], stream=stream)
+        elif kind == "csr_spmv" and path == "slab":
+            psk.psk_spmv_slab(s["slab"], s["dense"], s["out"], phases=phases, ws=s["slab_ws"], stream=stream)
         elif kind == "csr_spmv":
             psk.psk_spmv_csr(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"], tile=tile,
                              col_passes=col_passes, phases=phases, ws=s["ws"], stream=stream)
@@ -504,9 +540,9 @@ def main():
     main_avg = sum(main_ms) / len(main_ms)
     kernel_bytes = noreuse_bytes if kind.endswith("spmm") else comp_bytes
     achieved = kernel_bytes / (main_avg * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload + ("_f64" if f64 else ""), tile, col_passes))
-    if traffic is not None:
-        traffic *= col_passes           # like `achieved`: all launches of the tile kernel in one product
+    traffic, traffic_src = profile_traffic(args.workload + ("_f64" if f64 else ""), tile, col_passes, path)
+    if kind.startswith("bcsr") and A.bs != 4 or (kind.endswith("spmm") and k != cfg.get("k", 1)):
+        traffic, traffic_src = None, "measured for the configuration's block size and width only"
 
     rec = {
         "metric": "SpMV/SpMM GFLOP/s and achieved HBM GB/s (% of MI355X peak), 1 GPU",
@@ -522,12 +558,14 @@ def main():
         "dtype": "f64" if f64 else "f32",
         "data": "synthetic",
         "config": {
-            "workload": "%s: %s, %d x %d%s, nnz %d (max row %d, mean %.2f), tile %d, col_passes %d, k %d, %d operand copies rotated"
-                        % (args.workload, kind, A.rows * A.bs, A.cols * A.bs, " in %dx%d blocks" % (A.bs, A.bs) if A.bs > 1 else "",
+            "workload": "%s: %s%s, %d x %d%s, nnz %d (max row %d, mean %.2f), tile %d, col_passes %d, k %d, %d operand copies rotated"
+                        % (args.workload, kind, " over the column-slab copy of A (built once by psk_slab_build_csr)" if path == "slab" else "",
+                           A.rows * A.bs, A.cols * A.bs, " in %dx%d blocks" % (A.bs, A.bs) if A.bs > 1 else "",
                            A.nnz * A.bs * A.bs, int(L.max()) if L.size else 0, float(L.mean()) if L.size else 0.0,
                            tile, col_passes, k, copies),
             "rows": A.rows * A.bs, "cols": A.cols * A.bs, "nnz": A.nnz * A.bs * A.bs, "k": k, "tile": tile,
             "col_passes": col_passes,
+            "path": path,
             "seed": wl.BASE_SEED + cfg_no,
             "input_hash": input_hash(A.pos, A.crd, vals_h, dense_h),
         },
@@ -543,20 +581,44 @@ def main():
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "k_spmv_pos_f64" if f64 else {"csr_spmv": "k_spmv_pos", "csr_spmm": "k_spmm_pos<1,*>", "bcsr_spmv": "k_spmv_bcsr4",
-                       "bcsr_spmm": "k_spmm_pos<4,*>"}[kind],
+            "kernel": "k_spmv_pos_f64" if f64 else ("k_slab_pairs + k_spmv_pos<256,8,*,6>" if path == "slab" else
+                       {"csr_spmv": "k_spmv_pos", "csr_spmm": "k_spmm_pos<1,*>", "bcsr_spmv": "k_spmv_bcsr4",
+                        "bcsr_spmm": "k_spmm_pos<4,*>"}[kind]),
             "achieved": round(achieved, 2),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
             "traffic": traffic,
+            "traffic_source": traffic_src,
             "algorithmic_bytes": kernel_bytes,
-            "avg_launch_us": round(main_avg * 1e3 / col_passes, 2),
-            "launches_per_step": col_passes,
+            "avg_launch_us": round(main_avg * 1e3 / (2 if path == "slab" else col_passes), 2),
+            "launches_per_step": 2 if path == "slab" else col_passes,
             "byte_model": ("one dense row per stored position (no reuse)" if kind.endswith("spmm")
                            else "A once + dense operand once + output once"),
         },
     }
+
+    if path == "slab":
+        # the same product from the CSR arrays (position cut, tile kernel, fix-up in every call), for comparison
+        ts = []
+        for i in range(24):
+            s_ = sets[i % copies]
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            psk.psk_spmv_csr(A.rows, A.cols, A.nnz, s_["pos"], s_["crd"], s_["vals"], s_["dense"], s_["out"], tile=csr_tile,
+                             col_passes=csr_passes, ws=s_["ws"], stream=stream)
+            e1.record(stream)
+            e1.synchronize()
+            if i >= 8:
+                ts.append(e0.elapsed_time(e1))
+        csr_us = statistics.median(ts) * 1e3
+        slab_us = statistics.median(all_ms) * 1e3
+        analysis["repaid_after_products"] = (int(np.ceil(analysis["ms_median"] * 1e3 / (csr_us - slab_us)))
+                                             if csr_us > slab_us else None)
+        rec["analysis"] = analysis
+        rec["csr_path"] = {"call": "psk_spmv_csr", "tile": csr_tile, "col_passes": csr_passes,
+                           "us_median": round(csr_us, 2), "gflops": round(fl / (csr_us * 1e-6) / 1e9, 3),
+                           "frac_of_hbm_peak_whole_call": round(comp_bytes / (csr_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
 
     if args.baselines and kind == "csr_spmv" and not f64:
         base = {}

@@ -435,10 +435,12 @@ int psk_slab_build_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *p
  * y = A x over the structure: x has S->cols entries, y S->rows entries (assigned, rows without entries
  * become +0).  `workspace`: psk_slab_spmv_workspace_bytes(S), 256-byte aligned; products that may overlap in
  * time need separate workspaces, the structure itself is only read.  Enqueues three kernels on `stream`
- * (pair sums, row sums, carry fix-up) and returns; allocates nothing, never synchronises.
+ * (pair sums, row sums, carry fix-up) and returns; allocates nothing, never synchronises.  `phases`:
+ * PSK_PHASE_MAIN = the two sum kernels, PSK_PHASE_FIXUP = the fix-up (PSK_PHASE_ALL for a product;
+ * PSK_PHASE_PARTITION does nothing: the cut of the row lists is part of the structure).
  */
-int psk_spmv_slab(const psk_slab *S, const float *x, float *y, void *workspace, size_t workspace_bytes,
-                  void *stream);
+int psk_spmv_slab(const psk_slab *S, const float *x, float *y, int phases, void *workspace,
+                  size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -79,7 +79,7 @@ def lib() -> ctypes.CDLL:
         L.psk_slab_spmv_workspace_bytes.restype = sz
         L.psk_slab_build_csr.argtypes = [i64, i64, i64, p, p, p, p, sz, p, sz, ctypes.POINTER(psk_slab), p]
         L.psk_slab_build_csr.restype = ci
-        L.psk_spmv_slab.argtypes = [ctypes.POINTER(psk_slab), p, p, p, sz, p]
+        L.psk_spmv_slab.argtypes = [ctypes.POINTER(psk_slab), p, p, ci, p, sz, p]
         L.psk_spmv_slab.restype = ci
         L.psk_spmm_csr.argtypes = [i64, i64, i64, p, p, p, p, i32, i64, p, i64, i32, ci, p, sz, p]
         L.psk_spmm_csr.restype = ci
@@ -437,10 +437,10 @@ def psk_slab_spmv_workspace(S: Slab, device="cuda", stream=None):
     return _alloc_bytes(max(n, 256), device, stream)
 
 
-def psk_spmv_slab(S: Slab, x, y, ws=None, stream=None):
+def psk_spmv_slab(S: Slab, x, y, phases=PSK_PHASE_ALL, ws=None, stream=None):
     if ws is None:
         ws = psk_slab_spmv_workspace(S, x.device if x is not None else y.device, stream)
-    st = lib().psk_spmv_slab(ctypes.byref(S.desc), _ptr(x, torch.float32), _ptr(y, torch.float32), _ptr(ws), ws.numel(),
+    st = lib().psk_spmv_slab(ctypes.byref(S.desc), _ptr(x, torch.float32), _ptr(y, torch.float32), int(phases), _ptr(ws), ws.numel(),
                              _stream(stream))
     _check(st, "psk_spmv_slab")
     return y

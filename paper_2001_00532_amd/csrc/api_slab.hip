@@ -121,15 +121,17 @@ int psk_slab_build_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *p
     return hip_status(e);
 }
 
-int psk_spmv_slab(const psk_slab *S, const float *x, float *y, void *workspace, size_t workspace_bytes, void *stream)
+int psk_spmv_slab(const psk_slab *S, const float *x, float *y, int phases, void *workspace, size_t workspace_bytes,
+                  void *stream)
 {
     if (!S) return PSK_ERR_NULL;
+    if (phases <= 0 || (phases & ~PSK_PHASE_ALL)) return PSK_ERR_UNSUPPORTED;
     if (S->rows < 0 || S->cols < 0 || S->nnz < 0 || S->npairs < 0 || S->nq < 0 || S->nchunks < 0 ||
         S->slab_cols != kSlabCols || S->chunk != kSlabChunk || S->tile != kSlabTile)
         return PSK_ERR_SIZE;
     if ((S->rows > 0 && !y) || (S->nnz > 0 && !x)) return PSK_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (S->nnz == 0) return hip_status(launch_fill_zero(y, S->rows, s));
+    if (S->nnz == 0) return hip_status((phases & PSK_PHASE_MAIN) ? launch_fill_zero(y, S->rows, s) : hipSuccess);
     if (!S->svals || !S->scol || !S->chunk_pair || !S->slab_chunk || !S->qpos || !S->qidx || !S->qtile_row)
         return PSK_ERR_NULL;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) ||
@@ -146,14 +148,17 @@ int psk_spmv_slab(const psk_slab *S, const float *x, float *y, void *workspace, 
         int v = 0;
         if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
     }
-    hipError_t e = launch_slab_pairs(S->svals, S->scol, S->chunk_pair, S->slab_chunk, x, P, (int32_t)S->cols,
-                                     (int32_t)S->nslabs, (int32_t)S->nchunks, cus, s);
-    // step 2: rows add up their pairs (position cut of the row lists, carries, fix-up)
-    if (e == hipSuccess) {
-        if (ntiles == 0) e = launch_fill_zero(y, S->rows, s);
-        else e = launch_spmv_csr_ones((int32_t)S->rows, (int32_t)S->npairs, (int32_t)S->nq, S->qpos, S->qidx, P, y, ws, s);
+    hipError_t e = hipSuccess;
+    if (phases & PSK_PHASE_MAIN) {
+        e = launch_slab_pairs(S->svals, S->scol, S->chunk_pair, S->slab_chunk, x, P, (int32_t)S->cols,
+                              (int32_t)S->nslabs, (int32_t)S->nchunks, cus, s);
+        // step 2: rows add up their pairs (position cut of the row lists, carries)
+        if (e == hipSuccess) {
+            if (ntiles == 0) e = launch_fill_zero(y, S->rows, s);
+            else e = launch_spmv_csr_ones((int32_t)S->rows, (int32_t)S->npairs, (int32_t)S->nq, S->qpos, S->qidx, P, y, ws, s);
+        }
     }
-    if (e == hipSuccess) e = launch_carry_fixup(ntiles, 1, 1, 1, kSlabTile, S->qpos, ws, y, s);
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, 1, 1, kSlabTile, S->qpos, ws, y, s);
     return hip_status(e);
 }
 

@@ -69,9 +69,12 @@ __device__ __forceinline__ float wave_segscan(float v, int f)
 // equal pieces, Section 5), walks them slab by slab, loads the slab's part of x into LDS once and lets its
 // 16 waves take the chunks of that slab round-robin.  A lane owns 8 consecutive slots (two 16-byte loads of
 // values, one of columns); the next chunk's loads are issued before the current one is processed.
-// Inside a chunk: lane-serial sums, then a segmented DPP scan hands each lane the open sum of the lanes
-// below it; a pair's sum is stored by the lane that holds its last slot, at chunk_pair[c] + (number of
-// pair ends before it in the chunk).
+// Inside a chunk (no branches): the lane walks its 8 slots with a running sum that restarts after a pair
+// end and writes every running sum to LDS -- to the pair's place in the chunk (number of pair ends before
+// it) when the slot ends a pair, to a dummy word otherwise; a segmented DPP scan then hands each lane the
+// open sum of the lanes below it, which is added to the lane's first pair.  The chunk's pair sums, now
+// compact in LDS, leave with full-width coalesced stores to P[chunk_pair[c] ...].
+// LDS: 127.9 KB of x + 2 KB of pair sums per wave + the dummy words = the CU's 160 KB.
 __global__ __launch_bounds__(1024) void k_slab_pairs(const float *__restrict__ svals,
                                                      const unsigned short *__restrict__ scol,
                                                      const int *__restrict__ chunk_pair,
@@ -81,8 +84,11 @@ __global__ __launch_bounds__(1024) void k_slab_pairs(const float *__restrict__ s
 {
     constexpr int WAVES = 16;
     __shared__ float xs[SLAB_W];
+    __shared__ float stage[WAVES * SLAB_CH + 16];
     const int tid = threadIdx.x, lane = tid & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
+    float *st = stage + wave * SLAB_CH;
+    const int dummy = (WAVES - wave) * SLAB_CH + (lane & 15);      // index, relative to st, of a word nobody reads
     int c0 = blockIdx.x * cpw;
     const int c1 = min(c0 + cpw, nchunks);
     if (c0 >= c1) return;
@@ -114,55 +120,50 @@ __global__ __launch_bounds__(1024) void k_slab_pairs(const float *__restrict__ s
         v4f va = {0, 0, 0, 0}, vb = {0, 0, 0, 0};
         v4i cc = {0, 0, 0, 0};
         int pb = 0;
-        if (c < ce) {
-            const long long b = (long long)c * SLAB_CH + lane * 8;
+        auto issue = [&](int ci) {
+            const long long b = (long long)ci * SLAB_CH + lane * 8;
             va = ld_stream(reinterpret_cast<const v4f *>(svals + b));
             vb = ld_stream(reinterpret_cast<const v4f *>(svals + b + 4));
             cc = ld_stream(reinterpret_cast<const v4i *>(scol + b));
-            pb = chunk_pair[c];
-        }
+            // lanes 0 and 1 fetch the chunk's first pair and the next chunk's: a vector load on purpose, a scalar
+            // load would share its counter with the LDS reads and make each of them wait for its round trip
+            pb = chunk_pair[ci + (lane & 1)];
+        };
+        if (c < ce) issue(c);
         for (; c < ce; c += WAVES) {
             const v4f a0 = va, a1 = vb;
             const v4i q = cc;
-            const int pbase = pb;
-            const int cn = c + WAVES;
-            if (cn < ce) {
-                const long long b = (long long)cn * SLAB_CH + lane * 8;
-                va = ld_stream(reinterpret_cast<const v4f *>(svals + b));
-                vb = ld_stream(reinterpret_cast<const v4f *>(svals + b + 4));
-                cc = ld_stream(reinterpret_cast<const v4i *>(scol + b));
-                pb = chunk_pair[cn];
-            }
-            const unsigned w[4] = {(unsigned)q.x, (unsigned)q.y, (unsigned)q.z, (unsigned)q.w};
+            const int pbase = rl(pb, 0), np = rl(pb, 1) - pbase;
+            if (c + WAVES < ce) issue(c + WAVES);
+            const unsigned w0 = (unsigned)q.x, w1 = (unsigned)q.y, w2 = (unsigned)q.z, w3 = (unsigned)q.w;
+            // bit j = slot j of this lane ends a pair (bit 15 of its 16-bit column word)
+            const unsigned ends = ((w0 >> 15) & 1u) | ((w0 >> 30) & 2u) | ((w1 >> 13) & 4u) | ((w1 >> 28) & 8u) |
+                                  ((w2 >> 11) & 16u) | ((w2 >> 26) & 32u) | ((w3 >> 9) & 64u) | ((w3 >> 24) & 128u);
+            const unsigned w[4] = {w0, w1, w2, w3};
             const float v[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
             float p[8];
-            int e[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const unsigned h = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu);
-                e[j] = (int)(h >> 15);
+                const unsigned h = (j & 1) ? (w[j >> 1] >> 16) : w[j >> 1];
                 p[j] = v[j] * xs[h & 0x7fffu];
             }
-            int cnt = 0;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) cnt += e[j];
-            const int first = pbase + wave_scan_add(cnt) - cnt;     // index of this lane's first pair end
-            int rank = first;
-            float run = 0.0f, head = 0.0f;
-            bool seen = false;
+            const int cnt = __popc(ends);
+            const int first = wave_scan_add(cnt) - cnt;         // place of this lane's first pair end in the chunk
+            float run = 0.0f;
+            int place = first;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
+                const bool e = (ends >> j) & 1u;
                 run += p[j];
-                if (e[j]) {
-                    if (!seen) { head = run; seen = true; }
-                    else { ++rank; P[rank] = run; }           // a pair that lies inside this lane
-                    run = 0.0f;
-                }
+                st[e ? place : dummy] = run;
+                run = e ? 0.0f : run;
+                place += e ? 1 : 0;
             }
-            // `run` is the lane's open sum; the lane below hands over the open sum of all lanes below
-            const float open = wave_segscan(run, seen ? 1 : 0);
+            // `run` is the lane's open sum; the lane below hands over the open sum of all lanes below it
+            const float open = wave_segscan(run, cnt ? 1 : 0);
             const float carry = __shfl_up(open, 1, WAVE);
-            if (seen) P[first] = (lane == 0) ? head : carry + head;
+            if (cnt && lane) st[first] += carry;                // head + carry (a chunk's first slot starts a pair)
+            for (int k = lane; k < np; k += WAVE) P[pbase + k] = st[k];
         }
         c0 = ce;
         ++s;

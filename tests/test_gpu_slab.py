@@ -155,4 +155,4 @@ def test_slab_rejects_bad_arguments():
     assert L.psk_slab_build_csr(4, 4, 4, None, one, one, one, 1 << 30, one, 1 << 30, ctypes.byref(d), None) == 1
     assert L.psk_slab_build_csr(4, 4, 4, one, one, one, one, 16, one, 1 << 30, ctypes.byref(d), None) == 4
     assert L.psk_slab_build_csr(-1, 4, 4, one, one, one, one, 1 << 30, one, 1 << 30, ctypes.byref(d), None) == 2
-    assert L.psk_spmv_slab(None, one, one, one, 1 << 30, None) == 1
+    assert L.psk_spmv_slab(None, one, one, 7, one, 1 << 30, None) == 1
