@@ -31,6 +31,11 @@ Workloads (names of the evaluated configurations):
                       (Section 8.4; --skew-base, default 1.00256)
   copy                not a product: a plain device copy of 1 GiB, the calibration kernel for the
                       rocprofv3 FETCH_SIZE / WRITE_SIZE counters and the practical HBM ceiling
+  stream_read         not a product: 1 GiB read once with 16-byte non-temporal loads (the read-only ceiling)
+  gather              not a product: 2^26 gathers of 4-byte words at seeded uniform random indices from a table
+                      of --table-mb MB (default 8) in global memory: the cost of one gather of x
+  gather_lds          not a product: the same gathers from a table of 32736 floats that each workgroup holds
+                      in on-chip memory (the column-slab kernel's way of reading x)
 """
 import argparse
 import json
@@ -80,6 +85,9 @@ WORKLOADS = {
     "fewlong": (0, "csr_spmv"),
     "expskew": (0, "csr_spmv"),
     "copy": (0, "copy"),
+    "stream_read": (0, "calibration"),
+    "gather": (0, "calibration"),
+    "gather_lds": (0, "calibration"),
 }
 
 
@@ -155,6 +163,53 @@ def bench_copy(args, torch):
                       "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
                       "ms_per_step": round(avg, 6), "bytes_read": 4 * n, "bytes_written": 4 * n,
                       "config": {"workload": "copy: 2^28 fp32 elements, torch copy kernel"}}))
+
+
+def bench_calibration(args, torch, psk):
+    """The machine rates the design is argued with, from the library's calibration kernels."""
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream()
+    rng = np.random.default_rng(200100532)
+    if args.workload == "stream_read":
+        bufs = [torch.ones(1 << 28, device=dev) for _ in range(2)]          # two buffers of 1 GiB, alternated
+        sink = torch.zeros(64, device=dev)
+        work, unit, per = 4.0 * (1 << 28), "GB/s", "bytes"
+        what = "stream_read: 2^28 fp32 read once per launch with 16-byte non-temporal loads"
+        run = lambda i: psk.psk_calibrate_stream_read(bufs[i % 2], sink, stream=stream)
+    elif args.workload == "gather":
+        n = 1 << 26
+        elems = max(1024, int(args.table_mb * (1 << 20) / 4))
+        table = torch.zeros(elems, device=dev)
+        idx = [torch.from_numpy(rng.integers(0, elems, size=n, dtype=np.int32)).to(dev) for _ in range(2)]
+        out = torch.empty(n // 8, device=dev)
+        work, unit, per = float(n), "Ggather/s", "gathers"
+        what = "gather: 2^26 uniform random 4-byte gathers from a table of %.2f MB in global memory" % (elems * 4 / 2 ** 20)
+        run = lambda i: psk.psk_calibrate_gather(table, idx[i % 2], out, stream=stream)
+    else:
+        n = 1 << 26
+        elems = 32736
+        table = torch.zeros(elems, device=dev)
+        idx = [torch.from_numpy(rng.integers(0, elems, size=n, dtype=np.int16)).to(dev) for _ in range(2)]
+        out = torch.empty(256 * 1024, device=dev)
+        work, unit, per = float(n), "Ggather/s", "gathers"
+        what = "gather_lds: 2^26 uniform random gathers from a table of 32736 floats held in LDS by each workgroup"
+        run = lambda i: psk.psk_calibrate_gather_lds(table, idx[i % 2], out, stream=stream)
+    for i in range(args.warmup):
+        run(i)
+    torch.cuda.synchronize()
+    ts = []
+    for i in range(args.steps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        run(i)
+        e1.record(stream)
+        e1.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    med = statistics.median(ts)
+    print(json.dumps({"metric": "calibration: %s per second" % per, "value": round(work / (med * 1e-3) / 1e9, 3), "unit": unit,
+                      "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(med, 6),
+                      "ms_min": round(min(ts), 6), "ps_per_item": round(med * 1e9 / work, 3),
+                      "config": {"workload": what}}))
 
 
 def bench_mttkrp(args, torch, psk, wl):
@@ -356,6 +411,7 @@ def main():
     ap.add_argument("--bs", type=int, default=4, choices=[2, 4, 8],
                     help="bcsr_spmv / bcsr_spmm: block edge (the 10^6 x 10^6 matrix with 32 entries per row is re-blocked)")
     ap.add_argument("--f64", action="store_true", help="CSR SpMV workloads: fp64 values, vector and result")
+    ap.add_argument("--table-mb", type=float, default=8.0, help="gather: size of the table in MB")
     ap.add_argument("--rank", type=int, default=64, help="mttkrp: number of columns j of the factor matrices")
     ap.add_argument("--path", choices=["auto", "csr", "slab"], default="auto",
                     help="CSR SpMV workloads: multiply from the CSR arrays (position cut per call) or from the "
@@ -381,6 +437,8 @@ def main():
     cfg_no, kind = WORKLOADS[args.workload]
     if kind == "copy":
         return bench_copy(args, torch)
+    if kind == "calibration":
+        return bench_calibration(args, torch, psk)
     if kind == "mttkrp":
         return bench_mttkrp(args, torch, psk, wl)
     if kind == "dcsr":

@@ -442,6 +442,27 @@ int psk_slab_build_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *p
 int psk_spmv_slab(const psk_slab *S, const float *x, float *y, int phases, void *workspace,
                   size_t workspace_bytes, void *stream);
 
+/*
+ * ---- calibration kernels (no product; they reproduce the machine rates the design is argued with) ----
+ *
+ * psk_calibrate_stream_read: reads `bytes` bytes at `src` (16-byte aligned) once with 16-byte non-temporal
+ *   loads; nothing is written (`sink` needs one float).  Rate = bytes / kernel time: the practical ceiling
+ *   of a read-only stream.
+ * psk_calibrate_gather: out[i/8] (n/8 floats) receives sums of table[idx[i]], n gathers of 4-byte words
+ *   with 16-byte loads of the int32 indices (0 <= idx < table_elems, caller's contract), 2048 gathers per
+ *   workgroup: the CSR tile kernel's access pattern without values and row logic.  n must be a positive
+ *   multiple of 2048, idx 16-byte aligned.  Time / n = cost of one gather for that table size.
+ * psk_calibrate_gather_lds: the same number of gathers from a table of at most PSK_SLAB_COLS floats that
+ *   every workgroup first copies into on-chip memory; 16-bit indices (idx < table_elems), n a positive
+ *   multiple of 8192, out has 1024 floats per workgroup (at most 256 workgroups).
+ * All three only enqueue one kernel on `stream`.
+ */
+int psk_calibrate_stream_read(const void *src, size_t bytes, float *sink, void *stream);
+int psk_calibrate_gather(const float *table, int64_t table_elems, const int32_t *idx, int64_t n, float *out,
+                         void *stream);
+int psk_calibrate_gather_lds(const float *table, int32_t table_elems, const uint16_t *idx, int64_t n, float *out,
+                             void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,7 +29,7 @@ EXPORTS = [
     "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64", "psk_spmv_dcsr", "psk_spmv_csr_divide", "psk_suggest_schedule_csr", "psk_default_tile_bcsr", "psk_validate_csr",
     "psk_spmv_csr_static", "psk_static_scratch_bytes",
     "psk_slab_mem_bytes", "psk_slab_build_workspace_bytes", "psk_slab_spmv_workspace_bytes", "psk_slab_build_csr",
-    "psk_spmv_slab",
+    "psk_spmv_slab", "psk_calibrate_stream_read", "psk_calibrate_gather", "psk_calibrate_gather_lds",
 ]
 
 
@@ -81,6 +81,9 @@ def lib() -> ctypes.CDLL:
         L.psk_slab_build_csr.restype = ci
         L.psk_spmv_slab.argtypes = [ctypes.POINTER(psk_slab), p, p, ci, p, sz, p]
         L.psk_spmv_slab.restype = ci
+        L.psk_calibrate_stream_read.argtypes, L.psk_calibrate_stream_read.restype = [p, sz, p, p], ci
+        L.psk_calibrate_gather.argtypes, L.psk_calibrate_gather.restype = [p, i64, p, i64, p, p], ci
+        L.psk_calibrate_gather_lds.argtypes, L.psk_calibrate_gather_lds.restype = [p, i32, p, i64, p, p], ci
         L.psk_spmm_csr.argtypes = [i64, i64, i64, p, p, p, p, i32, i64, p, i64, i32, ci, p, sz, p]
         L.psk_spmm_csr.restype = ci
         L.psk_spmv_bcsr.argtypes = [i64, i64, i64, i32, p, p, p, p, p, i32, ci, p, sz, p]
@@ -444,3 +447,20 @@ def psk_spmv_slab(S: Slab, x, y, phases=PSK_PHASE_ALL, ws=None, stream=None):
                              _stream(stream))
     _check(st, "psk_spmv_slab")
     return y
+
+
+def psk_calibrate_stream_read(src, sink, stream=None):
+    st = lib().psk_calibrate_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink, torch.float32), _stream(stream))
+    _check(st, "psk_calibrate_stream_read")
+
+
+def psk_calibrate_gather(table, idx, out, stream=None):
+    st = lib().psk_calibrate_gather(_ptr(table, torch.float32), table.numel(), _ptr(idx, torch.int32), idx.numel(),
+                                    _ptr(out, torch.float32), _stream(stream))
+    _check(st, "psk_calibrate_gather")
+
+
+def psk_calibrate_gather_lds(table, idx, out, stream=None):
+    st = lib().psk_calibrate_gather_lds(_ptr(table, torch.float32), table.numel(), _ptr(idx, torch.int16), idx.numel(),
+                                        _ptr(out, torch.float32), _stream(stream))
+    _check(st, "psk_calibrate_gather_lds")

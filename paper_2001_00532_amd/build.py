@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libpsk.so")
 OBJDIR = os.path.join(HERE, "_build")
 
-SOURCES = ["api.hip", "partition.hip", "spmv_csr.hip", "spmm.hip", "spmv_bcsr.hip", "mttkrp.hip", "spmv_csr_f64.hip", "spmv_csr_divide.hip", "spmv_bcsr_g.hip", "spmm_narrow.hip", "slab.hip", "api_slab.hip"]
+SOURCES = ["api.hip", "partition.hip", "spmv_csr.hip", "spmm.hip", "spmv_bcsr.hip", "mttkrp.hip", "spmv_csr_f64.hip", "spmv_csr_divide.hip", "spmv_bcsr_g.hip", "spmm_narrow.hip", "slab.hip", "api_slab.hip", "calibrate.hip"]
 HEADERS = ["psk_dev.h", "psk_internal.h", os.path.join("..", "..", "include", "psk.h")]
 
 FLAGS = [
