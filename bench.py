@@ -165,6 +165,71 @@ def bench_copy(args, torch):
                       "config": {"workload": "copy: 2^28 fp32 elements, torch copy kernel"}}))
 
 
+def cu_trace_report(args, torch, psk, A, s, tile, col_passes, path, stream):
+    """Per-CU busy time from the instrumented build: every workgroup records start, end (100 MHz wall clock) and
+    the compute unit it ran on; a CU's busy time is the length of the union of its workgroups' intervals."""
+    SLAB_REC = 1024            # PSK_CU_TRACE_SLAB_RECORDS: the slab pair kernel's records come first
+    nrec = SLAB_REC + max(A.rows // 4 + 8, A.nnz // 256 + 64, A.rows // 256 + 8)
+    trace = torch.zeros(3 * nrec, dtype=torch.int64, device="cuda:0")
+    psk.psk_cu_trace_set(trace)
+    ws1 = psk.workspace(psk.PSK_OP_SPMV_CSR, A.rows, A.nnz, tile=2048, device="cuda:0")
+    variants = [
+        ("position cut, tile 2048, one pass (k_spmv_pos)",
+         lambda ph: psk.psk_spmv_csr(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"], tile=2048,
+                                     col_passes=1, phases=ph, ws=ws1, stream=stream)),
+        ("row split, wave per row (k_spmv_wave_per_row)",
+         lambda ph: psk.psk_spmv_csr_rowsplit(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"],
+                                              variant=1, stream=stream)),
+        ("row split, thread per row (k_spmv_thread_per_row)",
+         lambda ph: psk.psk_spmv_csr_rowsplit(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"],
+                                              variant=0, stream=stream)),
+    ]
+    if path == "slab":
+        variants.insert(0, ("column-slab path, pair sums (k_slab_pairs) + row sums (k_spmv_pos, unit values)",
+                            lambda ph: psk.psk_spmv_slab(s["slab"], s["dense"], s["out"], phases=ph, ws=s["slab_ws"], stream=stream)))
+    out = []
+    for name, fn in variants:
+        fn(psk.PSK_PHASE_PARTITION | psk.PSK_PHASE_MAIN)           # warm-up, and the table for the traced launch
+        torch.cuda.synchronize()
+        trace.zero_()
+        torch.cuda.synchronize()
+        fn(psk.PSK_PHASE_MAIN)
+        torch.cuda.synchronize()
+        t = trace.cpu().numpy().reshape(-1, 3)
+        if name.startswith("column-slab"):
+            pair_part = t[:SLAB_REC]
+            pair_part = pair_part[pair_part[:, 1] > 0]
+            pair_span = float((pair_part[:, 1].max() - pair_part[:, 0].min()) * 0.01)
+        t = t[t[:, 1] > 0]
+        t0, t1, hw = t[:, 0], t[:, 1], t[:, 2]
+        cu = ((hw >> 32) & 0xF) * 1024 + ((hw >> 13) & 7) * 32 + ((hw >> 12) & 1) * 16 + ((hw >> 8) & 0xF)
+        busy = []
+        for k in np.unique(cu):
+            m = cu == k
+            a, b = t0[m], t1[m]
+            o = np.argsort(a)
+            a, b = a[o], b[o]
+            end = np.maximum.accumulate(b)
+            gap = np.maximum(0, a[1:] - end[:-1])                  # idle time between consecutive intervals
+            busy.append((end[-1] - a[0] - gap.sum()) * 0.01)       # ticks of 10 ns -> us
+        busy = np.array(busy)
+        dur = (t1 - t0) * 0.01
+        out.append({"schedule": name, "workgroups": int(len(t)), "compute_units": int(len(busy)),
+                    "span_us": round(float((t1.max() - t0.min()) * 0.01), 1),
+                    "cu_busy_us": {"mean": round(float(busy.mean()), 1), "max": round(float(busy.max()), 1),
+                                   "min": round(float(busy.min()), 1)},
+                    "max_over_mean": round(float(busy.max() / busy.mean()), 3),
+                    "workgroup_us": {"median": round(float(np.median(dur)), 2), "p99": round(float(np.percentile(dur, 99)), 2),
+                                     "max": round(float(dur.max()), 2)}})
+        if name.startswith("column-slab"):
+            out[-1]["pair_kernel_workgroups"] = int(len(pair_part))
+            out[-1]["pair_kernel_span_us"] = round(pair_span, 1)
+    psk.psk_cu_trace_set(None)
+    print(json.dumps({"metric": "per-CU busy time of the SpMV schedules (instrumented build; ratios, not absolute times)",
+                      "config": {"workload": "%s: %d x %d, nnz %d" % (args.workload, A.rows, A.cols, A.nnz)},
+                      "schedules": out}))
+
+
 def bench_calibration(args, torch, psk):
     """The machine rates the design is argued with, from the library's calibration kernels."""
     dev = torch.device("cuda:0")
@@ -417,6 +482,9 @@ def main():
                     help="CSR SpMV workloads: multiply from the CSR arrays (position cut per call) or from the "
                          "column-slab copy of A built once by the analysis step; auto = slab when psk_analyze_csr "
                          "finds the columns scattered over an x larger than the caches, else csr")
+    ap.add_argument("--cu-trace", action="store_true",
+                    help="CSR SpMV workloads: load the instrumented build (libpsk_trace.so) and report the busy time of "
+                         "every compute unit (max / mean) for the position cut, the slab path and the two row-split kernels")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--baselines", action="store_true", help="also time the row-split kernels")
     args = ap.parse_args()
@@ -432,6 +500,8 @@ def main():
     if not torch.cuda.is_available():
         sys.stderr.write("bench.py: no GPU visible\n")
         sys.exit(1)
+    if args.cu_trace:
+        psk.use_instrumented_library()
     psk.lib()   # fail loudly when the HIP library is missing
 
     cfg_no, kind = WORKLOADS[args.workload]
@@ -562,6 +632,12 @@ def main():
         else:
             psk.psk_spmm_bcsr(A.rows, A.cols, A.nnz, A.bs, s["pos"], s["crd"], s["vals"], s["dense"], s["out"],
                               tile=tile, phases=phases, ws=s["ws"], stream=stream)
+
+    if args.cu_trace:
+        if kind != "csr_spmv" or f64:
+            sys.stderr.write("bench.py: --cu-trace applies to the fp32 CSR SpMV workloads\n")
+            sys.exit(2)
+        return cu_trace_report(args, torch, psk, A, sets[0], tile, col_passes, path, stream)
 
     # ---- warm-up, then exactly K timed steps bracketed by synchronize
     for i in range(args.warmup):

@@ -443,6 +443,24 @@ int psk_spmv_slab(const psk_slab *S, const float *x, float *y, int phases, void 
                   size_t workspace_bytes, void *stream);
 
 /*
+ * ---- per-CU load balance (instrumented build only) ----
+ *
+ * The library can be built a second time with -DPSK_CU_TRACE (libpsk_trace.so, python -m paper_2001_00532_amd.build
+ * makes both).  In that build every workgroup of the CSR SpMV tile kernel, of the two row-split kernels and of the
+ * slab pair kernel writes a record of three 64-bit words: its start and its end on the 100 MHz wall clock, and
+ * (HW_ID & 0xffff) | (XCC_ID << 32), i.e. the compute unit it ran on.  Workgroup b of the slab pair kernel writes
+ * record b (b < PSK_CU_TRACE_SLAB_RECORDS), workgroup b of the other kernels record PSK_CU_TRACE_SLAB_RECORDS + b, so
+ * that a product over the slab structure, which launches both kinds, can be traced in one go.  The host forms the busy
+ * time of each compute unit from them (Section 3 of the paper: equal position tiles give static load balance; the
+ * trace shows it per CU, position cut against row split).  records = NULL switches tracing off.  The records must be
+ * zeroed by the caller before each traced launch (the end time is written with an atomic max); workgroups beyond
+ * nrecords are not recorded.  Synchronous (it copies the pointer to the device).  The tracing costs time: use
+ * ratios, not absolute times.  The plain build returns PSK_ERR_UNSUPPORTED.
+ */
+#define PSK_CU_TRACE_SLAB_RECORDS 1024
+int psk_cu_trace_set(void *records, size_t nrecords);
+
+/*
  * ---- calibration kernels (no product; they reproduce the machine rates the design is argued with) ----
  *
  * psk_calibrate_stream_read: reads `bytes` bytes at `src` (16-byte aligned) once with 16-byte non-temporal

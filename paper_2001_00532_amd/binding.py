@@ -13,6 +13,7 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpsk.so")
+TRACE_LIB_PATH = os.path.join(_HERE, "libpsk_trace.so")
 
 PSK_OK = 0
 PSK_OP_SPMV_CSR, PSK_OP_SPMM_CSR, PSK_OP_SPMV_BCSR, PSK_OP_SPMM_BCSR, PSK_OP_MTTKRP_CSF3 = 0, 1, 2, 3, 4
@@ -29,7 +30,7 @@ EXPORTS = [
     "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64", "psk_spmv_dcsr", "psk_spmv_csr_divide", "psk_suggest_schedule_csr", "psk_default_tile_bcsr", "psk_validate_csr",
     "psk_spmv_csr_static", "psk_static_scratch_bytes",
     "psk_slab_mem_bytes", "psk_slab_build_workspace_bytes", "psk_slab_spmv_workspace_bytes", "psk_slab_build_csr",
-    "psk_spmv_slab", "psk_calibrate_stream_read", "psk_calibrate_gather", "psk_calibrate_gather_lds",
+    "psk_spmv_slab", "psk_cu_trace_set", "psk_calibrate_stream_read", "psk_calibrate_gather", "psk_calibrate_gather_lds",
 ]
 
 
@@ -50,15 +51,25 @@ class PskError(RuntimeError):
 
 
 _lib = None
+_lib_path = LIB_PATH
+
+
+def use_instrumented_library() -> None:
+    """Selects libpsk_trace.so (the build with per-workgroup records, see psk_cu_trace_set) instead of libpsk.so.
+    Must be called before the first operation of the process."""
+    global _lib_path
+    if _lib is not None:
+        raise RuntimeError("the library is already loaded")
+    _lib_path = TRACE_LIB_PATH
 
 
 def lib() -> ctypes.CDLL:
     """The loaded library.  Raises if it has not been built (python -m paper_2001_00532_amd.build)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise RuntimeError("libpsk.so is not built; run `python -m paper_2001_00532_amd.build`")
-        L = ctypes.CDLL(LIB_PATH)
+        if not os.path.exists(_lib_path):
+            raise RuntimeError("%s is not built; run `python -m paper_2001_00532_amd.build`" % os.path.basename(_lib_path))
+        L = ctypes.CDLL(_lib_path)
         i64, i32, p, ci, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
         L.psk_status_string.argtypes, L.psk_status_string.restype = [ci], ctypes.c_char_p
         L.psk_version.argtypes, L.psk_version.restype = [], ci
@@ -81,6 +92,7 @@ def lib() -> ctypes.CDLL:
         L.psk_slab_build_csr.restype = ci
         L.psk_spmv_slab.argtypes = [ctypes.POINTER(psk_slab), p, p, ci, p, sz, p]
         L.psk_spmv_slab.restype = ci
+        L.psk_cu_trace_set.argtypes, L.psk_cu_trace_set.restype = [p, sz], ci
         L.psk_calibrate_stream_read.argtypes, L.psk_calibrate_stream_read.restype = [p, sz, p, p], ci
         L.psk_calibrate_gather.argtypes, L.psk_calibrate_gather.restype = [p, i64, p, i64, p, p], ci
         L.psk_calibrate_gather_lds.argtypes, L.psk_calibrate_gather_lds.restype = [p, i32, p, i64, p, p], ci
@@ -464,3 +476,11 @@ def psk_calibrate_gather_lds(table, idx, out, stream=None):
     st = lib().psk_calibrate_gather_lds(_ptr(table, torch.float32), table.numel(), _ptr(idx, torch.int16), idx.numel(),
                                         _ptr(out, torch.float32), _stream(stream))
     _check(st, "psk_calibrate_gather_lds")
+
+
+def psk_cu_trace_set(records) -> None:
+    """records: int64 device tensor with 3 entries per workgroup, more than 1024 records (None switches tracing off).
+    Instrumented build only."""
+    n = 0 if records is None else records.numel() // 3
+    st = lib().psk_cu_trace_set(_ptr(records, torch.int64) if records is not None else None, n)
+    _check(st, "psk_cu_trace_set")

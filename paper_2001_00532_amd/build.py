@@ -14,6 +14,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libpsk.so")
 OBJDIR = os.path.join(HERE, "_build")
+# the instrumented build (-DPSK_CU_TRACE: per-workgroup start/end/CU records, see psk_cu_trace_set)
+OUT_TRACE = os.path.join(HERE, "libpsk_trace.so")
+OBJDIR_TRACE = os.path.join(HERE, "_build_trace")
 
 SOURCES = ["api.hip", "partition.hip", "spmv_csr.hip", "spmm.hip", "spmv_bcsr.hip", "mttkrp.hip", "spmv_csr_f64.hip", "spmv_csr_divide.hip", "spmv_bcsr_g.hip", "spmm_narrow.hip", "slab.hip", "api_slab.hip", "calibrate.hip"]
 HEADERS = ["psk_dev.h", "psk_internal.h", os.path.join("..", "..", "include", "psk.h")]
@@ -33,9 +36,9 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJDIR, os.path.splitext(src)[0] + ".o")
-    cmd = [hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(src: str, objdir: str = OBJDIR, extra=()) -> str:
+    obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
+    cmd = [hipcc(), *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
@@ -54,16 +57,26 @@ def stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
+def _link(objs, out: str) -> None:
+    cmd = [hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", out + ".tmp", *objs]
+    subprocess.check_call(cmd)
+    os.replace(out + ".tmp", out)
+
+
 def build(force: bool = True) -> str:
-    """Compile every kernel file and link libpsk.so.  With force=False only when sources are newer."""
-    if not force and not stale():
+    """Compile every kernel file and link libpsk.so and the instrumented libpsk_trace.so.  With force=False only
+    when sources are newer."""
+    if not force and not stale() and os.path.exists(OUT_TRACE) and os.path.getmtime(OUT_TRACE) >= os.path.getmtime(OUT):
         return OUT
     os.makedirs(OBJDIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", OUT + ".tmp", *objs]
-    subprocess.check_call(cmd)
-    os.replace(OUT + ".tmp", OUT)
+    os.makedirs(OBJDIR_TRACE, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        plain = [ex.submit(_compile, s) for s in SOURCES]
+        traced = [ex.submit(_compile, s, OBJDIR_TRACE, ("-DPSK_CU_TRACE",)) for s in SOURCES]
+        objs = [f.result() for f in plain]
+        objs_t = [f.result() for f in traced]
+    _link(objs, OUT)
+    _link(objs_t, OUT_TRACE)
     return OUT
 
 

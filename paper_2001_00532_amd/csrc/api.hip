@@ -246,6 +246,25 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
     return hip_status(e);
 }
 
+int psk_cu_trace_set(void *records, size_t nrecords)
+{
+#ifdef PSK_CU_TRACE
+    if (nrecords > 0xffffffffu) return PSK_ERR_SIZE;
+    // the slab pair kernel (persistent, at most PSK_CU_TRACE_SLAB_RECORDS workgroups) records into the first part
+    // of the buffer, the CSR kernels behind it, so that a slab product (both kinds of kernel) can be traced at once
+    if (records && nrecords <= PSK_CU_TRACE_SLAB_RECORDS) return PSK_ERR_SIZE;
+    unsigned long long *base = static_cast<unsigned long long *>(records);
+    const unsigned n = records ? (unsigned)(nrecords - PSK_CU_TRACE_SLAB_RECORDS) : 0u;
+    if (cu_trace_set_slab(base, records ? PSK_CU_TRACE_SLAB_RECORDS : 0u) != hipSuccess) return PSK_ERR_HIP;
+    if (cu_trace_set_spmv_csr(records ? base + 3ull * PSK_CU_TRACE_SLAB_RECORDS : nullptr, n) != hipSuccess) return PSK_ERR_HIP;
+    return PSK_OK;
+#else
+    (void)records;
+    (void)nrecords;
+    return PSK_ERR_UNSUPPORTED;     // this is the plain build; the instrumented one is libpsk_trace.so
+#endif
+}
+
 size_t psk_static_scratch_bytes(void) { return PSK_STATIC_SCRATCH_BYTES; }
 
 int psk_spmv_csr_static(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,

@@ -86,6 +86,41 @@ __device__ __forceinline__ void st_vec(float *p, const float (&s)[VEC])
     __builtin_nontemporal_store(v, reinterpret_cast<V *>(p));
 }
 
+// ---- per-workgroup trace (only in the instrumented build, -DPSK_CU_TRACE): every workgroup of a traced kernel
+// records its start and end on the 100 MHz wall clock and the compute unit it ran on (HW_ID: cu, sh, se;
+// XCC_ID: die) into a caller-supplied buffer of 3 x 64 bits per workgroup, from which the host forms each
+// CU's busy time.  Each translation unit has its own copy of the pointer; psk_cu_trace_set sets them all.
+#ifdef PSK_CU_TRACE
+static __device__ unsigned long long *g_cu_trace = nullptr;
+static __device__ unsigned g_cu_trace_records = 0;
+struct WorkgroupTrace {
+    unsigned long long t0;
+    __device__ WorkgroupTrace() : t0(wall_clock64()) {}
+    __device__ ~WorkgroupTrace()
+    {
+        if ((threadIdx.x & (WAVE - 1)) == 0 && g_cu_trace && blockIdx.x < g_cu_trace_records) {
+            unsigned long long *r = g_cu_trace + 3ull * blockIdx.x;
+            atomicMax(r + 1, (unsigned long long)wall_clock64());      // a workgroup ends with its last wave
+            if (threadIdx.x == 0) {
+                const unsigned hw = __builtin_amdgcn_s_getreg((15 << 11) | (0 << 6) | 4);     // HW_ID[15:0]
+                const unsigned xcc = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20);    // XCC_ID[3:0]
+                r[0] = t0;
+                r[2] = (unsigned long long)hw | ((unsigned long long)xcc << 32);
+            }
+        }
+    }
+};
+inline hipError_t cu_trace_set_here(void *buf, unsigned records)
+{
+    hipError_t e = hipMemcpyToSymbol(HIP_SYMBOL(g_cu_trace), &buf, sizeof(buf));
+    if (e == hipSuccess) e = hipMemcpyToSymbol(HIP_SYMBOL(g_cu_trace_records), &records, sizeof(records));
+    return e;
+}
+#define PSK_TRACE_WORKGROUP() WorkgroupTrace psk_trace_guard_
+#else
+#define PSK_TRACE_WORKGROUP() do { } while (0)
+#endif
+
 __device__ __forceinline__ int   rl(int v, int lane)   { return __builtin_amdgcn_readlane(v, lane); }
 __device__ __forceinline__ float rl(float v, int lane) { return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane)); }
 

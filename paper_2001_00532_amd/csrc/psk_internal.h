@@ -163,6 +163,11 @@ hipError_t launch_fill_int(int32_t *p, int64_t n, int32_t v, hipStream_t s);
 hipError_t launch_spmv_csr_ones(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
                                 const float *x, float *y, const Workspace &w, hipStream_t s);
 
+#ifdef PSK_CU_TRACE
+hipError_t cu_trace_set_spmv_csr(void *buf, unsigned records);
+hipError_t cu_trace_set_slab(void *buf, unsigned records);
+#endif
+
 // MTTKRP on a three-level hierarchy
 bool mttkrp_tile_ok(int32_t tile);
 hipError_t launch_partition_csf3(int32_t nslices, int32_t nfibers, int32_t nnz, const int32_t *pos_k,

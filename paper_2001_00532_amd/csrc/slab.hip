@@ -92,6 +92,7 @@ __global__ __launch_bounds__(1024) void k_slab_pairs(const float *__restrict__ s
     int c0 = blockIdx.x * cpw;
     const int c1 = min(c0 + cpw, nchunks);
     if (c0 >= c1) return;
+    PSK_TRACE_WORKGROUP();
     int s;      // slab of chunk c0: max { s : slab_chunk[s] <= c0 }
     {
         int lo = 0, hi = nslabs;
@@ -511,5 +512,9 @@ hipError_t launch_slab_build(int32_t rows, int32_t cols, int32_t nnz, const int3
                qpos, qidx, w.meta);
     return take_launch_status();
 }
+
+#ifdef PSK_CU_TRACE
+hipError_t cu_trace_set_slab(void *buf, unsigned records) { return cu_trace_set_here(buf, records); }
+#endif
 
 }  // namespace psk

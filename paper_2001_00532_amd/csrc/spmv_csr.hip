@@ -96,6 +96,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
 
     const int t = xcd_tile(blockIdx.x, ntiles);
     if (t < 0) return;
+    PSK_TRACE_WORKGROUP();
     const int tid = threadIdx.x, lane = tid & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);   // tells the compiler it is uniform
     const int t0 = t * T;
@@ -414,6 +415,7 @@ __global__ __launch_bounds__(256) void k_spmv_thread_per_row(int rows, const int
                                                              const float *__restrict__ x,
                                                              float *__restrict__ y)
 {
+    PSK_TRACE_WORKGROUP();
     const int r = blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= rows) return;
     float s = 0.0f;
@@ -430,6 +432,7 @@ __global__ __launch_bounds__(256) void k_spmv_wave_per_row(int rows, const int *
                                                            float *__restrict__ y,
                                                            const int *__restrict__ rowmap)
 {
+    PSK_TRACE_WORKGROUP();
     const int lane = threadIdx.x & (WAVE - 1);
     const int r = blockIdx.x * (256 / WAVE) + threadIdx.x / WAVE;
     if (r >= rows) return;
@@ -452,5 +455,9 @@ hipError_t launch_spmv_rowsplit(int32_t rows, const int32_t *pos, const int32_t 
                            rowmap);
     return take_launch_status();
 }
+
+#ifdef PSK_CU_TRACE
+hipError_t cu_trace_set_spmv_csr(void *buf, unsigned records) { return cu_trace_set_here(buf, records); }
+#endif
 
 }  // namespace psk
