@@ -732,6 +732,15 @@ def main():
         },
     }
 
+    if kind == "csr_spmv" and not f64 and path == "csr" and not tile_given and col_passes <= 1 and 0 < A.nnz <= 16384:
+        # a problem of one tile: the library takes it as one launch of one workgroup; what counts is time per call
+        rec["roofline"]["launches_per_step"] = 1
+        rec["roofline"]["kernel"] = "k_spmv_pos<1024,16,*,7> (the whole matrix as one tile)"
+        rec["latency"] = {"launches_per_product": 1,
+                          "us_per_call_back_to_back": round(ms_per_step * 1e3, 2),
+                          "us_per_call_isolated_with_events": round(statistics.median(all_ms) * 1e3, 2),
+                          "note": "launch-latency bound: 94 KB of operands; the roofline fraction is not meaningful here"}
+
     if path == "slab":
         # the same product from the CSR arrays (position cut, tile kernel, fix-up in every call), for comparison
         ts = []

@@ -140,7 +140,9 @@ int psk_partition_csr(int64_t rows, int64_t nnz, const int32_t *pos, int32_t til
  * the tile, one carry record per tile for a row that began in an earlier tile
  * (instead of the schedule's atomics), carries added by a second small kernel.
  * x has cols entries, y rows entries.  tile in {0, 256, 512, 1024, 2048, 4096}; 0 means 2048, or
- * 1024 when col_passes > 1 (psk_workspace_bytes with tile = 0 covers both).
+ * 1024 when col_passes > 1 (psk_workspace_bytes with tile = 0 covers both).  With tile = 0, col_passes <= 1
+ * and nnz <= 16384 the whole matrix is taken as one tile by one workgroup: one launch (in PSK_PHASE_MAIN),
+ * no table, no carries; such problems are bound by launch latency.
  *
  * col_passes (0 or 1 = off, at most PSK_MAX_COL_PASSES): the main step is run that many times, pass q
  * gathering only the columns of the q-th equal slice of [0, cols) and adding to what the earlier passes

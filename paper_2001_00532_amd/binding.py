@@ -149,6 +149,13 @@ def _stream(stream=None):
     return ctypes.c_void_p(s.cuda_stream)
 
 
+def _temporary_ws_ok(phases: int, what: str):
+    """A workspace made for one call holds no table: the main and fix-up steps on their own would read garbage
+    row numbers (and run out of bounds), so a partial product must bring the workspace the table was built in."""
+    if int(phases) & PSK_PHASE_PARTITION == 0:
+        raise ValueError("%s: phases without PSK_PHASE_PARTITION need the workspace (ws=...) that holds the table" % what)
+
+
 def _check(status: int, what: str):
     if status != PSK_OK:
         raise PskError(status, what)
@@ -249,6 +256,7 @@ def psk_suggest_schedule_csr(rows, nnz, pos, ws=None, stream=None) -> int:
 def psk_spmv_csr(rows, cols, nnz, pos, crd, vals, x, y, tile=0, col_passes=1, phases=PSK_PHASE_ALL, ws=None,
                  stream=None):
     if ws is None:
+        _temporary_ws_ok(phases, "psk_spmv_csr")
         ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmv_csr(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                             _ptr(vals, torch.float32), _ptr(x, torch.float32), _ptr(y, torch.float32), int(tile),
@@ -273,6 +281,7 @@ def psk_spmv_csr_static(rows, cols, nnz, pos, crd, vals, x, y, tile=0, col_passe
 def psk_spmm_csr(rows, cols, nnz, pos, crd, vals, B, C, tile=0, phases=PSK_PHASE_ALL, ws=None, stream=None):
     k = B.shape[1]
     if ws is None:
+        _temporary_ws_ok(phases, "psk_spmm_csr")
         ws = workspace(PSK_OP_SPMM_CSR, rows, nnz, k=k, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmm_csr(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                             _ptr(vals, torch.float32), _ptr(B, torch.float32), int(k), int(B.stride(0)),
@@ -285,6 +294,7 @@ def psk_spmm_csr(rows, cols, nnz, pos, crd, vals, B, C, tile=0, phases=PSK_PHASE
 def psk_spmv_bcsr(brows, bcols, nblocks, bs, pos, crd, vals, x, y, tile=0, phases=PSK_PHASE_ALL, ws=None,
                   stream=None):
     if ws is None:
+        _temporary_ws_ok(phases, "psk_spmv_bcsr")
         ws = workspace(PSK_OP_SPMV_BCSR, brows, nblocks, bs=bs, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmv_bcsr(int(brows), int(bcols), int(nblocks), int(bs), _ptr(pos, torch.int32),
                              _ptr(crd, torch.int32), _ptr(vals, torch.float32), _ptr(x, torch.float32),
@@ -297,6 +307,7 @@ def psk_spmm_bcsr(brows, bcols, nblocks, bs, pos, crd, vals, B, C, tile=0, phase
                   stream=None):
     k = B.shape[1]
     if ws is None:
+        _temporary_ws_ok(phases, "psk_spmm_bcsr")
         ws = workspace(PSK_OP_SPMM_BCSR, brows, nblocks, k=k, bs=bs, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmm_bcsr(int(brows), int(bcols), int(nblocks), int(bs), _ptr(pos, torch.int32),
                              _ptr(crd, torch.int32), _ptr(vals, torch.float32), _ptr(B, torch.float32), int(k),
@@ -323,6 +334,7 @@ def psk_mttkrp_csf3(dims, crd_i, pos_k, crd_k, pos_l, crd_l, vals, C, D, A, tile
     """A (dims[0] x j) = MTTKRP of the three-level tensor with C (dims[1] x j) and D (dims[2] x j)."""
     nslices, nfibers, nnz, j = pos_k.numel() - 1, pos_l.numel() - 1, crd_l.numel(), C.shape[1]
     if ws is None:
+        _temporary_ws_ok(phases, "psk_mttkrp_csf3")
         ws = workspace(PSK_OP_MTTKRP_CSF3, nslices, nnz, k=j, tile=tile, device=pos_k.device, stream=stream)
     st = lib().psk_mttkrp_csf3(int(dims[0]), int(dims[1]), int(dims[2]), nslices, nfibers, nnz,
                                _ptr(crd_i, torch.int32), _ptr(pos_k, torch.int32), _ptr(crd_k, torch.int32),
@@ -336,6 +348,7 @@ def psk_mttkrp_csf3(dims, crd_i, pos_k, crd_k, pos_l, crd_l, vals, C, D, A, tile
 
 def psk_spmv_csr_atomics(rows, cols, nnz, pos, crd, vals, x, y, tile=0, phases=PSK_PHASE_ALL, ws=None, stream=None):
     if ws is None:
+        _temporary_ws_ok(phases, "psk_spmv_csr_atomics")
         ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmv_csr_atomics(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                                     _ptr(vals, torch.float32), _ptr(x, torch.float32), _ptr(y, torch.float32),
@@ -347,6 +360,7 @@ def psk_spmv_csr_atomics(rows, cols, nnz, pos, crd, vals, x, y, tile=0, phases=P
 def psk_spmv_csr_f64(rows, cols, nnz, pos, crd, vals, x, y, tile=0, col_passes=1, phases=PSK_PHASE_ALL, ws=None,
                      stream=None):
     if ws is None:
+        _temporary_ws_ok(phases, "psk_spmv_csr_f64")
         ws = workspace(PSK_OP_SPMV_CSR_F64, rows, nnz, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmv_csr_f64(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                                 _ptr(vals, torch.float64), _ptr(x, torch.float64), _ptr(y, torch.float64),
@@ -358,6 +372,8 @@ def psk_spmv_csr_f64(rows, cols, nnz, pos, crd, vals, x, y, tile=0, col_passes=1
 def psk_spmv_dcsr(rows, cols, nnz, crd_i, pos, crd, vals, x, y, cut=PSK_CUT_POSITIONS, tile=0, col_passes=1,
                   phases=PSK_PHASE_ALL, ws=None, stream=None):
     nstored = int(crd_i.numel())
+    if ws is None and cut == PSK_CUT_POSITIONS:
+        _temporary_ws_ok(phases, "psk_spmv_dcsr")
     if ws is None:
         ws = workspace(PSK_OP_SPMV_CSR, nstored, nnz, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmv_dcsr(int(rows), int(cols), nstored, int(nnz), _ptr(crd_i, torch.int32), _ptr(pos, torch.int32),
@@ -370,6 +386,8 @@ def psk_spmv_dcsr(rows, cols, nnz, crd_i, pos, crd, vals, x, y, cut=PSK_CUT_POSI
 
 def psk_spmv_csr_divide(rows, cols, nnz, pos, crd, vals, x, y, parts=0, phases=PSK_PHASE_ALL, ws=None, stream=None):
     if ws is None:
+        if int(phases) & 6 != 6:      # no table here, but main and fix-up share the carry records
+            raise ValueError("psk_spmv_csr_divide: main and fix-up on their own need a workspace that outlives the call")
         ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=2048, device=pos.device, stream=stream)
     st = lib().psk_spmv_csr_divide(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                                    _ptr(vals, torch.float32), _ptr(x, torch.float32), _ptr(y, torch.float32),
@@ -380,6 +398,7 @@ def psk_spmv_csr_divide(rows, cols, nnz, pos, crd, vals, x, y, parts=0, phases=P
 
 def psk_spmv_csr_notemp(rows, cols, nnz, pos, crd, vals, x, y, tile=0, phases=PSK_PHASE_ALL, ws=None, stream=None):
     if ws is None:
+        _temporary_ws_ok(phases, "psk_spmv_csr_notemp")
         ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=tile, device=pos.device, stream=stream)
     st = lib().psk_spmv_csr_notemp(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
                                    _ptr(vals, torch.float32), _ptr(x, torch.float32), _ptr(y, torch.float32),
@@ -454,6 +473,8 @@ def psk_slab_spmv_workspace(S: Slab, device="cuda", stream=None):
 
 def psk_spmv_slab(S: Slab, x, y, phases=PSK_PHASE_ALL, ws=None, stream=None):
     if ws is None:
+        if int(phases) != PSK_PHASE_ALL:
+            raise ValueError("psk_spmv_slab: a partial product needs the workspace (ws=...) of the earlier steps")
         ws = psk_slab_spmv_workspace(S, x.device if x is not None else y.device, stream)
     st = lib().psk_spmv_slab(ctypes.byref(S.desc), _ptr(x, torch.float32), _ptr(y, torch.float32), int(phases), _ptr(ws), ws.numel(),
                              _stream(stream))

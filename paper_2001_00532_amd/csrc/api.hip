@@ -228,6 +228,9 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
                  void *workspace, size_t workspace_bytes, void *stream)
 {
     if (col_passes < 0 || col_passes > PSK_MAX_COL_PASSES) return PSK_ERR_SIZE;
+    // a matrix of a few thousand entries is bound by launch latency: with the default tile it is taken as ONE tile
+    // by one workgroup -- no table, no carries, one launch instead of three
+    const bool single = tile == 0 && col_passes <= 1 && nnz > 0 && nnz <= kSingleTile;
     if (tile == 0 && col_passes > 1) tile = 1024;   // gather-bound passes prefer the smaller tile (measured)
     Workspace ws;
     int st = check_common(PSK_OP_SPMV_CSR, rows, cols, nnz, pos, crd, vals, 1, 1, &tile, phases, workspace,
@@ -235,6 +238,10 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
     if (st != PSK_OK) return st;
     if ((rows > 0 && !y) || (nnz > 0 && !x)) return PSK_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (single) {
+        if (!(phases & PSK_PHASE_MAIN)) return PSK_OK;
+        return hip_status(launch_spmv_csr_single((int32_t)rows, (int32_t)cols, (int32_t)nnz, pos, crd, vals, x, y, s));
+    }
     const int32_t ntiles = (int32_t)psk_num_tiles(nnz, tile);
     hipError_t e = hipSuccess;
     if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, 0, ws.tile_row, s);

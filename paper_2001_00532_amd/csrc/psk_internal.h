@@ -88,6 +88,10 @@ bool spmv_csr_tile_ok(int32_t tile);
 hipError_t launch_spmv_csr_main(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
                                 const float *vals, const float *x, float *y, int32_t tile, int32_t col_passes,
                                 const Workspace &w, hipStream_t s, const int32_t *rowmap = nullptr);
+// the whole matrix as one tile of one workgroup (nnz <= kSingleTile): no table, no carries
+constexpr int32_t kSingleTile = 16384;
+hipError_t launch_spmv_csr_single(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                                  const float *vals, const float *x, float *y, hipStream_t s);
 // rowmap (optional, both launchers): row r of the hierarchy is row rowmap[r] of y (DCSR)
 hipError_t launch_spmv_rowsplit(int32_t rows, const int32_t *pos, const int32_t *crd, const float *vals,
                                 const float *x, float *y, int variant, hipStream_t s,

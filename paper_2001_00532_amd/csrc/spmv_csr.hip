@@ -67,6 +67,8 @@ __device__ __forceinline__ void run_select(const RunPlan &p, v4f_u wA, v4f_u wB,
 // 3: one pass without the per-thread temporary and without the unrolled load loop (the ablation of
 //    Section 8.3): each thread walks its positions in a rolled loop, one load -> gather -> multiply -> LDS
 //    store after the other.
+// 7: the whole matrix is one tile (nnz <= T): no table, no carries, no fix-up -- one launch per product for
+//    problems of a few thousand entries, which are bound by launch latency.
 // 6: one pass with unit values: vals is not read (the second step of the product over the column-slab
 //    hierarchy, where the "matrix" only lists which partial sums belong to a row).
 template <int THREADS, int NPT, int MODE, int VARIANT>
@@ -88,13 +90,14 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
     constexpr bool WIN = VARIANT == 1 || VARIANT == 5, ATOM = VARIANT == 2, NOTEMP = VARIANT == 3;
     constexpr bool ROWMAP = VARIANT == 4 || VARIANT == 5;
     constexpr bool ONES = VARIANT == 6;
+    constexpr bool SINGLE = VARIANT == 7;
     static_assert(NPT % 4 == 0, "NPT must be a multiple of 4");
     __shared__ float sprod[skewed_size<1>(T)];
     __shared__ int slong[MAXLONG * 3];
     __shared__ int nlong;
     __shared__ float swave[NW];
 
-    const int t = xcd_tile(blockIdx.x, ntiles);
+    const int t = SINGLE ? (blockIdx.x == 0 ? 0 : -1) : xcd_tile(blockIdx.x, ntiles);
     if (t < 0) return;
     PSK_TRACE_WORKGROUP();
     const int tid = threadIdx.x, lane = tid & (WAVE - 1);
@@ -118,7 +121,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
     // Issue order matters more than anything else here: the tile's row bounds hang off a chain of
     // dependent loads (tile_row -> pos), so that chain is started first and runs underneath the
     // streaming loads and the gather instead of after them.
-    const int r0 = tile_row[t], r1 = tile_row[t + 1];
+    const int r0 = SINGLE ? 0 : tile_row[t], r1 = SINGLE ? rows : tile_row[t + 1];
 
     // ---- 1. stream + gather + multiply
     float prod[NPT];
@@ -258,7 +261,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
 
     const bool has_carry = (t > 0) && (p_r0 < t0);
     const int rend = (p_r1 == t1) ? r1 : r1 + 1;   // last tile: r1 = rows and pos[rows] = nnz = t1
-    if (tid == 0 && !has_carry && !ATOM) carry_row[t] = -1;
+    if (tid == 0 && !has_carry && !ATOM && !SINGLE) carry_row[t] = -1;
     // a later column pass adds to what the first one stored (same lane, same order: deterministic)
     auto emit = [&](int r, float v) {
         if (ATOM) {
@@ -358,6 +361,24 @@ static void launch_pos(int mode, int grid, hipStream_t s, int rows, int cols, in
     else if (mode == 1) { if (variant == 2) PSK_GO(1, 2); else if (variant == 1) PSK_GO(1, 1); else PSK_GO(1, 0); }
     else { if (variant == 2) PSK_GO(0, 2); else if (variant == 1) PSK_GO(0, 1); else PSK_GO(0, 0); }
 #undef PSK_GO
+}
+
+// nnz <= kSingleTile: the whole product in one launch of one workgroup
+hipError_t launch_spmv_csr_single(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                                  const float *vals, const float *x, float *y, hipStream_t s)
+{
+    if (nnz <= 0 || nnz > kSingleTile) return hipErrorInvalidValue;
+    const int *notable = nullptr;
+    int *nocarry = nullptr;
+    float *nocarryval = nullptr;
+    const bool aligned = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
+    if (aligned)
+        PSK_LAUNCH((k_spmv_pos<1024, 16, 1, 7>), dim3(1), dim3(1024), 0, s, rows, cols, nnz, pos, crd, vals, x, y, notable,
+                   nocarry, nocarryval, 1, 0, cols, 0, notable, nocarry);
+    else
+        PSK_LAUNCH((k_spmv_pos<1024, 16, 0, 7>), dim3(1), dim3(1024), 0, s, rows, cols, nnz, pos, crd, vals, x, y, notable,
+                   nocarry, nocarryval, 1, 0, cols, 0, notable, nocarry);
+    return take_launch_status();
 }
 
 hipError_t launch_spmv_csr_ones(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,

@@ -123,3 +123,17 @@ def test_binding_refuses_host_tensors():
     t = torch.zeros(4, dtype=torch.int32)
     with pytest.raises(ValueError):
         psk.psk_partition_csr(t, 0, 4)
+
+
+def test_binding_refuses_partial_products_on_a_temporary_workspace():
+    """Main or fix-up without the partition step read the table from the workspace: a workspace made for the call
+    holds garbage row numbers, so the binding refuses before anything reaches the library."""
+    for fn, args in ((psk.psk_spmv_csr, (4, 4, 4, None, None, None, None, None)),
+                     (psk.psk_spmv_bcsr, (4, 4, 4, 4, None, None, None, None, None)),
+                     (psk.psk_spmv_csr_notemp, (4, 4, 4, None, None, None, None, None))):
+        with pytest.raises(ValueError):
+            fn(*args, phases=psk.PSK_PHASE_MAIN)
+        with pytest.raises(ValueError):
+            fn(*args, phases=psk.PSK_PHASE_MAIN | psk.PSK_PHASE_FIXUP)
+    with pytest.raises(ValueError):
+        psk.psk_spmv_csr_divide(4, 4, 4, None, None, None, None, None, phases=psk.PSK_PHASE_MAIN)
