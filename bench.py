@@ -621,8 +621,9 @@ def main():
         elif kind == "csr_spmv" and path == "slab":
             psk.psk_spmv_slab(s["slab"], s["dense"], s["out"], phases=phases, ws=s["slab_ws"], stream=stream)
         elif kind == "csr_spmv":
-            psk.psk_spmv_csr(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"], tile=tile,
-                             col_passes=col_passes, phases=phases, ws=s["ws"], stream=stream)
+            # tile = 0 unless one was asked for: the library then also takes a matrix of one tile in one launch
+            psk.psk_spmv_csr(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"],
+                             tile=tile if tile_given else 0, col_passes=col_passes, phases=phases, ws=s["ws"], stream=stream)
         elif kind == "csr_spmm":
             psk.psk_spmm_csr(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"], tile=tile,
                              phases=phases, ws=s["ws"], stream=stream)
@@ -650,18 +651,21 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
 
-    # ---- the phases on their own, HIP events on the stream the kernels run on (median of 16, 8 warm-ups)
-    def time_phase(phases, reps=16, warm=8):
+    # ---- the phases on their own, HIP events on the stream the kernels run on (median of 16 samples, 4 warm-ups)
+    # Each sample brackets `inner` back-to-back calls with one event pair and divides: the host-side cost of
+    # recording an event and of the first launch after an idle stream (about 5-10 us) would otherwise be charged to
+    # kernels that now take about 100 us; the calls of a sample rotate over the operand copies like the timed steps.
+    def time_phase(phases, reps=16, warm=4, inner=8):
         ts = []
         for i in range(warm + reps):
-            s = sets[i % copies]
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
-            step(s, phases)
+            for j in range(inner):
+                step(sets[(i * inner + j) % copies], phases)
             e1.record(stream)
             e1.synchronize()
             if i >= warm:
-                ts.append(e0.elapsed_time(e1))
+                ts.append(e0.elapsed_time(e1) / inner)
         return ts
 
     main_ms = time_phase(psk.PSK_PHASE_MAIN)
@@ -736,9 +740,22 @@ def main():
         # a problem of one tile: the library takes it as one launch of one workgroup; what counts is time per call
         rec["roofline"]["launches_per_step"] = 1
         rec["roofline"]["kernel"] = "k_spmv_pos<1024,16,*,7> (the whole matrix as one tile)"
+        iso = time_phase(psk.PSK_PHASE_ALL, reps=32, warm=8, inner=1)     # one call between two events, stream idle before
+        # the same product with the arguments marshalled once (the Python side of a call costs more than the kernel)
+        calls = [psk.psk_spmv_csr_prepared(A.rows, A.cols, A.nnz, s_["pos"], s_["crd"], s_["vals"], s_["dense"], s_["out"],
+                                           ws=s_["ws"], stream=stream) for s_ in sets]
+        for i in range(200):
+            calls[i % copies]()
+        torch.cuda.synchronize()
+        t_p = time.perf_counter()
+        for i in range(2000):
+            calls[i % copies]()
+        torch.cuda.synchronize()
+        prepared_us = (time.perf_counter() - t_p) / 2000 * 1e6
         rec["latency"] = {"launches_per_product": 1,
                           "us_per_call_back_to_back": round(ms_per_step * 1e3, 2),
-                          "us_per_call_isolated_with_events": round(statistics.median(all_ms) * 1e3, 2),
+                          "us_per_call_back_to_back_prepared": round(prepared_us, 2),
+                          "us_per_call_isolated_with_events": round(statistics.median(iso) * 1e3, 2),
                           "note": "launch-latency bound: 94 KB of operands; the roofline fraction is not meaningful here"}
 
     if path == "slab":

@@ -278,6 +278,30 @@ def psk_spmv_csr_static(rows, cols, nnz, pos, crd, vals, x, y, tile=0, col_passe
     return y
 
 
+class PreparedCall:
+    """A call whose arguments are already marshalled: calling it only crosses into the library.  For loops that
+    repeat one product on the same buffers and are bound by the host side of the call (small matrices)."""
+
+    def __init__(self, fn, what, cargs, keep):
+        self._fn, self._what, self._cargs, self._keep = fn, what, cargs, keep      # `keep` holds the tensors alive
+
+    def __call__(self):
+        st = self._fn(*self._cargs)
+        if st != PSK_OK:
+            raise PskError(st, self._what)
+
+
+def psk_spmv_csr_prepared(rows, cols, nnz, pos, crd, vals, x, y, tile=0, col_passes=1, phases=PSK_PHASE_ALL, ws=None,
+                          stream=None) -> PreparedCall:
+    """psk_spmv_csr with the marshalling done once; the returned object repeats the call."""
+    if ws is None:
+        ws = workspace(PSK_OP_SPMV_CSR, rows, nnz, tile=tile, device=pos.device, stream=stream)
+    cargs = (int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32), _ptr(vals, torch.float32),
+             _ptr(x, torch.float32), _ptr(y, torch.float32), int(tile), int(col_passes), int(phases), _ptr(ws), ws.numel(),
+             _stream(stream))
+    return PreparedCall(lib().psk_spmv_csr, "psk_spmv_csr", cargs, (pos, crd, vals, x, y, ws, stream))
+
+
 def psk_spmm_csr(rows, cols, nnz, pos, crd, vals, B, C, tile=0, phases=PSK_PHASE_ALL, ws=None, stream=None):
     k = B.shape[1]
     if ws is None:

@@ -36,7 +36,7 @@ def check(got, ref, mag, what):
 @pytest.mark.parametrize("kind", ADVERSARIAL_KINDS)
 def test_single_tile_path_structures(kind):
     rng = np.random.default_rng(31)
-    for rows, cols in ((1, 1), (7, 5000), (1024, 1024), (5000, 300), (16000, 17)):
+    for rows, cols in ((3, 2), (7, 5000), (1024, 1024), (5000, 300), (16000, 17)):
         A = wl.csr_from_lengths(adversarial_lengths(rng, rows, cols, kind), cols, seed=rows + cols)
         if A.nnz > 16384:
             continue
