@@ -161,10 +161,10 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
  * psk_spmv_csr for callers that cannot allocate device memory and have no workspace to pass: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same product (all three phases), same
  * kernels and bit-identical results as psk_spmv_csr with the same tile and col_passes; the table, the carry
- * records and the column ranges live in a built-in device array of PSK_STATIC_SCRATCH_BYTES (4 MiB per GPU,
+ * records, the column ranges and the run list live in a built-in device array of PSK_STATIC_SCRATCH_BYTES (4 MiB per GPU,
  * held until the process ends) instead of a caller's workspace.  The call allocates nothing.
  *  - Limit: psk_workspace_bytes(PSK_OP_SPMV_CSR, rows, nnz, 1, 1, tile) must not exceed
- *    psk_static_scratch_bytes(), i.e. about 87 000 tiles (178 M nonzeros at tile 2048, 89 M at 1024);
+ *    psk_static_scratch_bytes(), i.e. about 74 000 tiles (153 M nonzeros at tile 2048, 76 M at 1024);
  *    beyond that PSK_ERR_WORKSPACE and nothing is enqueued.
  *  - tile in {0, 256, 512, 1024, 2048, 4096}; 0 means 2048, or 1024 when col_passes > 1.
  *  - All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (different

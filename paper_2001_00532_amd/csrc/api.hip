@@ -230,7 +230,7 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
     if (col_passes < 0 || col_passes > PSK_MAX_COL_PASSES) return PSK_ERR_SIZE;
     // a matrix of a few thousand entries is bound by launch latency: with the default tile it is taken as ONE tile
     // by one workgroup -- no table, no carries, one launch instead of three
-    const bool single = tile == 0 && col_passes <= 1 && nnz > 0 && nnz <= kSingleTile;
+    const bool single = tile == 0 && col_passes <= 1 && nnz > 0 && nnz <= kSingleTile && rows <= 4 * kSingleTile;
     if (tile == 0 && col_passes > 1) tile = 1024;   // gather-bound passes prefer the smaller tile (measured)
     Workspace ws;
     int st = check_common(PSK_OP_SPMV_CSR, rows, cols, nnz, pos, crd, vals, 1, 1, &tile, phases, workspace,
@@ -244,12 +244,15 @@ int psk_spmv_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, co
     }
     const int32_t ntiles = (int32_t)psk_num_tiles(nnz, tile);
     hipError_t e = hipSuccess;
-    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, 0, ws.tile_row, s);
+    // long runs of empty rows: the tile that spans one lists it (ws.gap) and the fix-up step clears it at full width
+    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, 0, ws.tile_row, s, ws.gap);
     if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
         if (ntiles == 0) e = launch_fill_zero(y, rows, s);
-        else e = launch_spmv_csr_main((int32_t)rows, (int32_t)cols, (int32_t)nnz, pos, crd, vals, x, y, tile, col_passes, ws, s);
+        else e = launch_spmv_csr_main((int32_t)rows, (int32_t)cols, (int32_t)nnz, pos, crd, vals, x, y, tile, col_passes, ws, s,
+                                      nullptr, true);
     }
-    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, 1, 1, tile, pos, ws, y, s);
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess)
+        e = launch_carry_fixup(ntiles, 1, 1, 1, tile, pos, ws, y, s, nullptr, nullptr, true);
     return hip_status(e);
 }
 

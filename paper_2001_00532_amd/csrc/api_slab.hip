@@ -151,14 +151,15 @@ int psk_spmv_slab(const psk_slab *S, const float *x, float *y, int phases, void 
     hipError_t e = hipSuccess;
     if (phases & PSK_PHASE_MAIN) {
         e = launch_slab_pairs(S->svals, S->scol, S->chunk_pair, S->slab_chunk, x, P, (int32_t)S->cols,
-                              (int32_t)S->nslabs, (int32_t)S->nchunks, cus, s);
+                              (int32_t)S->nslabs, (int32_t)S->nchunks, cus, ws.gap, s);
         // step 2: rows add up their pairs (position cut of the row lists, carries)
         if (e == hipSuccess) {
             if (ntiles == 0) e = launch_fill_zero(y, S->rows, s);
             else e = launch_spmv_csr_ones((int32_t)S->rows, (int32_t)S->npairs, (int32_t)S->nq, S->qpos, S->qidx, P, y, ws, s);
         }
     }
-    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup(ntiles, 1, 1, 1, kSlabTile, S->qpos, ws, y, s);
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess)
+        e = launch_carry_fixup(ntiles, 1, 1, 1, kSlabTile, S->qpos, ws, y, s, nullptr, nullptr, true);
     return hip_status(e);
 }
 

@@ -8,9 +8,11 @@ namespace psk {
 // coordinate of a tile of the position space is recovered by a binary search over pos).
 // One lane per table entry; pos[0] = 0 makes i = 0 always admissible.
 __global__ __launch_bounds__(256) void k_partition(int rows, int nnz, const int *__restrict__ pos,
-                                                   int tile, int ntiles, int *__restrict__ tile_row)
+                                                   int tile, int ntiles, int *__restrict__ tile_row,
+                                                   int *__restrict__ gap)
 {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t == 0 && gap) { gap[0] = 0; gap[1] = 0; }
     if (t > ntiles) return;
     const long long first = (long long)t * tile;
     const int target = first < nnz ? (int)first : nnz;
@@ -31,13 +33,16 @@ __global__ __launch_bounds__(256) void k_partition(int rows, int nnz, const int 
 // written by their whole wave.
 __global__ __launch_bounds__(256) void k_partition_scan(int rows, int nnz, const int *__restrict__ pos, int tile,
                                                         int shift, int ntiles, int *__restrict__ tile_row,
-                                                        int vec_ok)
+                                                        int vec_ok, int *__restrict__ gap)
 {
     constexpr int RPT = 4;                                   // rows per thread
     const int g = blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = threadIdx.x & (WAVE - 1);
     const int rbase = g * RPT;
-    if (g == 0) tile_row[ntiles] = rows;
+    if (g == 0) {
+        tile_row[ntiles] = rows;
+        if (gap) { gap[0] = 0; gap[1] = 0; }
+    }
     int p[RPT + 1];
     if (vec_ok && rbase + RPT <= rows) {
         const v4i v = *reinterpret_cast<const v4i *>(pos + rbase);
@@ -75,7 +80,7 @@ __global__ __launch_bounds__(256) void k_partition_scan(int rows, int nnz, const
 
 // method: 0 = choose, 1 = binary search per tile, 2 = one scan over the rows
 hipError_t launch_partition(int64_t rows, int64_t nnz, const int32_t *pos, int32_t tile, int method,
-                            int32_t *tile_row, hipStream_t s)
+                            int32_t *tile_row, hipStream_t s, int32_t *gap)
 {
     const int64_t ntiles = nnz <= 0 ? 0 : (nnz + tile - 1) / tile;
     if (method == 0) method = (ntiles > 0 && rows <= (int64_t(1) << 23)) ? 2 : 1;
@@ -85,12 +90,12 @@ hipError_t launch_partition(int64_t rows, int64_t nnz, const int32_t *pos, int32
         const int vec_ok = (reinterpret_cast<uintptr_t>(pos) & 15) == 0;
         const int64_t threads = (rows + 3) / 4;
         PSK_LAUNCH(k_partition_scan, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, (int)rows,
-                           (int)nnz, pos, tile, shift, (int)ntiles, tile_row, vec_ok);
+                           (int)nnz, pos, tile, shift, (int)ntiles, tile_row, vec_ok, gap);
         return take_launch_status();
     }
     const int64_t n = ntiles + 1;
     PSK_LAUNCH(k_partition, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (int)rows, (int)nnz, pos,
-                       tile, (int)ntiles, tile_row);
+                       tile, (int)ntiles, tile_row, gap);
     return take_launch_status();
 }
 
@@ -238,13 +243,33 @@ __device__ __forceinline__ int run_length(const int *__restrict__ pos, const int
 
 // width = 1 (SpMV): a lane per tile; runs of more than 8 records are summed by the whole wave.
 // V = float: fp32 records and output, summed in fp64.  V = double: all fp64.
+// Workgroups from `carry_groups` on (launched only for the CSR SpMV) clear the runs of empty rows that tiles listed in
+// `gap` instead of walking them (gap[0] = number of runs, then first and end row of each): every row r of a run with
+// pos[r] = pos[r+1] becomes 0; rows with entries were written by their tiles.  The last of these workgroups to finish
+// resets the two counters, so that a product which reuses the table (no partition step) starts from an empty list.
 template <typename V>
 __global__ __launch_bounds__(256) void k_carry_fixup1(int ntiles, long long ld, int tile, int shift,
                                                       const int *__restrict__ pos,
                                                       const int *__restrict__ carry_row,
                                                       const V *__restrict__ carry_val,
-                                                      V *__restrict__ out)
+                                                      V *__restrict__ out, int carry_groups, int *__restrict__ gap)
 {
+    if ((int)blockIdx.x >= carry_groups) {
+        const int fillers = (int)gridDim.x - carry_groups, me = (int)blockIdx.x - carry_groups;
+        int n = gap[0];
+        n = n < ntiles ? n : ntiles;
+        for (int e = 0; e < n; ++e) {
+            const long long lo = gap[2 + 2 * e], hi = gap[3 + 2 * e];
+            for (long long r = lo + (long long)me * 256 + threadIdx.x; r < hi; r += (long long)fillers * 256)
+                if (pos[r] == pos[r + 1]) out[r * ld] = V(0);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            __threadfence();
+            if (atomicAdd(&gap[1], 1) == fillers - 1) { gap[0] = 0; gap[1] = 0; }
+        }
+        return;
+    }
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = threadIdx.x & (WAVE - 1);
     int r = -1, len = 0;
@@ -315,15 +340,18 @@ __global__ __launch_bounds__(256) void k_carry_fixup(int ntiles, int width, int 
 
 hipError_t launch_carry_fixup(int32_t ntiles, int32_t nsub, int32_t k, int64_t ld, int32_t tile, const int32_t *pos,
                               const Workspace &w, float *out, hipStream_t s, const int32_t *pos2,
-                              const int32_t *rowmap)
+                              const int32_t *rowmap, bool gaps)
 {
-    if (ntiles <= 1) return hipSuccess;   // tile 0 never has a carry
+    const int width = nsub * k;
+    gaps = gaps && width == 1 && !pos2 && !rowmap && ntiles >= 1;
+    if (ntiles <= 1 && !gaps) return hipSuccess;   // tile 0 never has a carry
     int shift = -1;
     if ((tile & (tile - 1)) == 0) { shift = 0; while ((1 << shift) < tile) ++shift; }
-    const int width = nsub * k;
     if (width == 1 && !pos2 && !rowmap) {
-        PSK_LAUNCH(k_carry_fixup1<float>, dim3((unsigned)((ntiles + 255) / 256)), dim3(256), 0, s, ntiles,
-                           (long long)ld, tile, shift, pos, w.carry_row, w.carry_val, out);
+        const int carry_groups = ntiles <= 1 ? 0 : (ntiles + 255) / 256;
+        int *gap = gaps ? w.gap : nullptr;
+        PSK_LAUNCH(k_carry_fixup1<float>, dim3((unsigned)(carry_groups + (gaps ? kGapFillGroups : 0))), dim3(256), 0, s,
+                   ntiles, (long long)ld, tile, shift, pos, w.carry_row, w.carry_val, out, carry_groups, gap);
         return take_launch_status();
     }
     const int64_t n = (int64_t)ntiles * width;
@@ -338,8 +366,10 @@ hipError_t launch_carry_fixup_f64(int32_t ntiles, int32_t tile, const int32_t *p
     if (ntiles <= 1) return hipSuccess;
     int shift = -1;
     if ((tile & (tile - 1)) == 0) { shift = 0; while ((1 << shift) < tile) ++shift; }
+    int *nogap = nullptr;
     PSK_LAUNCH(k_carry_fixup1<double>, dim3((unsigned)((ntiles + 255) / 256)), dim3(256), 0, s, ntiles, 1ll,
-                       tile, shift, pos, w.carry_row, reinterpret_cast<const double *>(w.carry_val), out);
+                       tile, shift, pos, w.carry_row, reinterpret_cast<const double *>(w.carry_val), out,
+                       (ntiles + 255) / 256, nogap);
     return take_launch_status();
 }
 

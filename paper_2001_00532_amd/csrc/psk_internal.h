@@ -39,13 +39,15 @@ inline void launch_kernel(void (*kern)(KA...), dim3 grid, dim3 block, unsigned s
 
 // Workspace carving: [tile_row: ntiles+1 int32][carry_row: ntiles int32][carry_val: ntiles*width float]
 // [tile_aux: ntiles+1 int32 (second table of a two-level cut)][tile_cols: ntiles*8 int32 (column range of each
-// tile, one min/max pair per wave, written by the first column pass)], each part starting on a 256-byte boundary.
+// tile, one min/max pair per wave, written by the first column pass)][gap: 2+2*ntiles int32 (the long runs of
+// empty rows that the fix-up step clears with many workgroups)], each part starting on a 256-byte boundary.
 struct Workspace {
     int32_t *tile_row;
     int32_t *carry_row;
     float   *carry_val;
     int32_t *tile_aux;
     int32_t *tile_cols;
+    int32_t *gap;        // [2 + 2*ntiles]: count, arrivals, then (first row, end row) of every long run of rows a tile spans
     size_t   bytes;
 };
 inline size_t align256(size_t n) { return (n + 255) & ~size_t(255); }
@@ -61,14 +63,17 @@ inline Workspace carve(void *base, int64_t ntiles, int64_t width)
     const size_t d = align256(size_t(ntiles) * 32 + 4);
     w.tile_aux = reinterpret_cast<int32_t *>(p + a + b + c);
     w.tile_cols = reinterpret_cast<int32_t *>(p + a + b + c + a);
-    w.bytes = a + b + c + a + d;
+    const size_t g = align256(size_t(ntiles) * 8 + 8);
+    w.gap = reinterpret_cast<int32_t *>(p + a + b + c + a + d);
+    w.bytes = a + b + c + a + d + g;
     return w;
 }
 
 // Every launcher enqueues on `s` and returns the status of its own launches (take_launch_status()).
 
+// gap (optional): the run list of the workspace; its two counters are cleared here
 hipError_t launch_partition(int64_t rows, int64_t nnz, const int32_t *pos, int32_t tile, int method,
-                            int32_t *tile_row, hipStream_t s);
+                            int32_t *tile_row, hipStream_t s, int32_t *gap = nullptr);
 hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s);
 hipError_t launch_fill_zero_2d(float *p, int64_t rows, int32_t width, int64_t ld, hipStream_t s);
 hipError_t launch_validate_csr(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
@@ -79,15 +84,20 @@ hipError_t launch_probe_locality(int32_t nnz, const int32_t *crd, int32_t *resul
 // out[(row*nsub + e / k) * ld + e % k].
 // `pos2` (optional): two-level hierarchy, a row's last position is pos2[pos[r+1]] - 1.  `rowmap` (optional):
 // row r of the hierarchy is stored at output row rowmap[r].
+// gaps = true (CSR SpMV only): extra workgroups clear the long runs of empty rows that the tile kernel listed in w.gap
 hipError_t launch_carry_fixup(int32_t ntiles, int32_t nsub, int32_t k, int64_t ld, int32_t tile, const int32_t *pos,
                               const Workspace &w, float *out, hipStream_t s, const int32_t *pos2 = nullptr,
-                              const int32_t *rowmap = nullptr);
+                              const int32_t *rowmap = nullptr, bool gaps = false);
+// A tile whose rows span more than this many rows does not walk them: it finds the rows of its positions by search
+// and leaves the run of empty rows to the fix-up step (which clears it with many workgroups).
+constexpr int32_t kGapRows = 32768;
+constexpr int32_t kGapFillGroups = 512;
 
 // CSR SpMV
 bool spmv_csr_tile_ok(int32_t tile);
 hipError_t launch_spmv_csr_main(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
                                 const float *vals, const float *x, float *y, int32_t tile, int32_t col_passes,
-                                const Workspace &w, hipStream_t s, const int32_t *rowmap = nullptr);
+                                const Workspace &w, hipStream_t s, const int32_t *rowmap = nullptr, bool gaps = false);
 // the whole matrix as one tile of one workgroup (nnz <= kSingleTile): no table, no carries
 constexpr int32_t kSingleTile = 16384;
 hipError_t launch_spmv_csr_single(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
@@ -161,7 +171,7 @@ hipError_t launch_slab_build(int32_t rows, int32_t cols, int32_t nnz, const int3
                              int32_t *chunk_pair, int32_t *slab_chunk, int32_t *qpos, int32_t *qidx, hipStream_t s);
 hipError_t launch_slab_pairs(const float *svals, const uint16_t *scol, const int32_t *chunk_pair,
                              const int32_t *slab_chunk, const float *x, float *P, int32_t cols, int32_t nslabs,
-                             int32_t nchunks, int32_t nwg, hipStream_t s);
+                             int32_t nchunks, int32_t nwg, int32_t *gap, hipStream_t s);
 hipError_t launch_fill_int(int32_t *p, int64_t n, int32_t v, hipStream_t s);
 // y = Q * P with unit values: the tile kernel of the CSR SpMV without the load of vals (tile 2048)
 hipError_t launch_spmv_csr_ones(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,

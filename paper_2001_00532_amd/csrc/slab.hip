@@ -80,9 +80,11 @@ __global__ __launch_bounds__(1024) void k_slab_pairs(const float *__restrict__ s
                                                      const int *__restrict__ chunk_pair,
                                                      const int *__restrict__ slab_chunk,
                                                      const float *__restrict__ x, float *__restrict__ P, int cols,
-                                                     int nslabs, int nchunks, int cpw)
+                                                     int nslabs, int nchunks, int cpw, int *__restrict__ gap)
 {
     constexpr int WAVES = 16;
+    // the run list of the second step starts empty (that step's tiles append to it, the fix-up consumes it)
+    if (blockIdx.x == 0 && threadIdx.x == 0 && gap) { gap[0] = 0; gap[1] = 0; }
     __shared__ float xs[SLAB_W];
     __shared__ float stage[WAVES * SLAB_CH + 16];
     const int tid = threadIdx.x, lane = tid & (WAVE - 1);
@@ -173,14 +175,14 @@ __global__ __launch_bounds__(1024) void k_slab_pairs(const float *__restrict__ s
 
 hipError_t launch_slab_pairs(const float *svals, const uint16_t *scol, const int32_t *chunk_pair,
                              const int32_t *slab_chunk, const float *x, float *P, int32_t cols, int32_t nslabs,
-                             int32_t nchunks, int32_t nwg, hipStream_t s)
+                             int32_t nchunks, int32_t nwg, int32_t *gap, hipStream_t s)
 {
     if (nchunks <= 0) return hipSuccess;
     if (nwg < 1) nwg = 1;
     const int cpw = (nchunks + nwg - 1) / nwg;
     const int grid = (nchunks + cpw - 1) / cpw;
     PSK_LAUNCH(k_slab_pairs, dim3(grid), dim3(1024), 0, s, svals, scol, chunk_pair, slab_chunk, x, P, cols, nslabs,
-               nchunks, cpw);
+               nchunks, cpw, gap);
     return take_launch_status();
 }
 

@@ -80,7 +80,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
                                                       int *__restrict__ carry_row,
                                                       float *__restrict__ carry_val, int ntiles, int clo,
                                                       int chi, int accum, const int *__restrict__ rowmap,
-                                                      int *__restrict__ tile_cols)
+                                                      int *__restrict__ tile_cols, int *__restrict__ gap)
 {
     constexpr int T = THREADS * NPT;
     constexpr int NW = THREADS / WAVE;
@@ -91,11 +91,13 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
     constexpr bool ROWMAP = VARIANT == 4 || VARIANT == 5;
     constexpr bool ONES = VARIANT == 6;
     constexpr bool SINGLE = VARIANT == 7;
+    constexpr bool GAPS = VARIANT == 0 || VARIANT == 1 || VARIANT == 6;   // may leave long runs of empty rows to the fix-up
     static_assert(NPT % 4 == 0, "NPT must be a multiple of 4");
     __shared__ float sprod[skewed_size<1>(T)];
     __shared__ int slong[MAXLONG * 3];
     __shared__ int nlong;
     __shared__ float swave[NW];
+    __shared__ int srowid[GAPS ? T : 1];
 
     const int t = SINGLE ? (blockIdx.x == 0 ? 0 : -1) : xcd_tile(blockIdx.x, ntiles);
     if (t < 0) return;
@@ -306,6 +308,52 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos(int rows, int cols, int nn
         for (int g = 0; g < NPT; ++g) sprod[skew<1>(tile_index<MODE, THREADS>(g, tid))] = prod[g];
     }
     __syncthreads();
+    if (GAPS && gap && rend - rbeg > kGapRows) {
+        // The tile's rows span a long run of empty rows (Section 6.2 walks past empty rows one by one; here that walk
+        // would be done by this one workgroup).  Instead the row of every position is found by search -- a thread takes
+        // NPT consecutive positions, searches once for the first and again whenever a row ends --, the row segments
+        // are summed by the thread that holds their first position, and the run of rows is handed to the fix-up step,
+        // whose extra workgroups clear its empty rows at full width.
+        const int i0 = tid * NPT;
+        if (i0 < cnt) {
+            int lo = r0, hi = r1;                       // max { r in [r0, r1] : pos[r] <= t0 + i0 }
+            while (lo < hi) {
+                const int mid = lo + ((hi - lo + 1) >> 1);
+                if (pos[mid] <= t0 + i0) lo = mid; else hi = mid - 1;
+            }
+            int r = lo;
+            int next = pos[r + 1];
+#pragma unroll 1
+            for (int k = 0; k < NPT && i0 + k < cnt; ++k) {
+                const int p = t0 + i0 + k;
+                if (p >= next) {                        // the row ended: the next row with entries owns p
+                    int l2 = r + 1, h2 = r1;
+                    while (l2 < h2) {
+                        const int mid = l2 + ((h2 - l2 + 1) >> 1);
+                        if (pos[mid] <= p) l2 = mid; else h2 = mid - 1;
+                    }
+                    r = l2;
+                    next = pos[r + 1];
+                }
+                srowid[i0 + k] = r;
+            }
+        }
+        __syncthreads();
+#pragma unroll 1
+        for (int k = 0; k < NPT && i0 + k < cnt; ++k) {
+            const int i = i0 + k;
+            const int r = srowid[i];
+            if (i > 0 && srowid[i - 1] == r) continue;  // not the first position of its row segment
+            float sum = 0.0f;
+            for (int j = i; j < cnt && srowid[j] == r; ++j) sum += sprod[skew<1>(j)];
+            emit(r, sum);
+        }
+        if (tid == 0 && !(WIN && accum)) {
+            const int e = atomicAdd(&gap[0], 1);
+            if (e < ntiles) { gap[2 + 2 * e] = rbeg; gap[3 + 2 * e] = rend; }
+        }
+        return;
+    }
     for (int r = rbeg + tid; r < rend; r += THREADS) {
         int lo = my_lo - t0, hi = my_hi - t0;
         if (r + THREADS < rend) { my_lo = pos[r + THREADS]; my_hi = pos[r + THREADS + 1]; }
@@ -347,12 +395,12 @@ bool spmv_csr_tile_ok(int32_t tile)
 template <int THREADS, int NPT>
 static void launch_pos(int mode, int grid, hipStream_t s, int rows, int cols, int nnz, const int *pos, const int *crd,
                        const float *vals, const float *x, float *y, const Workspace &w, int ntiles, int clo, int chi,
-                       int accum, const int *rowmap)
+                       int accum, const int *rowmap, int *gap)
 {
 #define PSK_GO(M, W)                                                                                             \
     PSK_LAUNCH((k_spmv_pos<THREADS, NPT, M, W>), dim3(grid), dim3(THREADS), 0, s, rows, cols, nnz, pos,  \
                        crd, vals, x, y, w.tile_row, w.carry_row, w.carry_val, ntiles, clo, chi, accum, rowmap,    \
-                       w.tile_cols)
+                       w.tile_cols, gap)
     const bool window = clo > 0 || chi < cols;
     const int variant = rowmap ? (window ? 5 : 4) : (accum >= 2 ? accum : (window ? 1 : 0));
     if (variant == 3) PSK_GO(0, 3);
@@ -374,10 +422,10 @@ hipError_t launch_spmv_csr_single(int32_t rows, int32_t cols, int32_t nnz, const
     const bool aligned = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
     if (aligned)
         PSK_LAUNCH((k_spmv_pos<1024, 16, 1, 7>), dim3(1), dim3(1024), 0, s, rows, cols, nnz, pos, crd, vals, x, y, notable,
-                   nocarry, nocarryval, 1, 0, cols, 0, notable, nocarry);
+                   nocarry, nocarryval, 1, 0, cols, 0, notable, nocarry, nocarry);
     else
         PSK_LAUNCH((k_spmv_pos<1024, 16, 0, 7>), dim3(1), dim3(1024), 0, s, rows, cols, nnz, pos, crd, vals, x, y, notable,
-                   nocarry, nocarryval, 1, 0, cols, 0, notable, nocarry);
+                   nocarry, nocarryval, 1, 0, cols, 0, notable, nocarry, nocarry);
     return take_launch_status();
 }
 
@@ -391,20 +439,21 @@ hipError_t launch_spmv_csr_ones(int32_t rows, int32_t cols, int32_t nnz, const i
     const int *nomap = nullptr;
     if ((reinterpret_cast<uintptr_t>(crd) & 15) == 0)
         PSK_LAUNCH((k_spmv_pos<256, 8, 1, 6>), dim3(grid), dim3(256), 0, s, rows, cols, nnz, pos, crd, none, x, y,
-                   w.tile_row, w.carry_row, w.carry_val, ntiles, 0, cols, 0, nomap, w.tile_cols);
+                   w.tile_row, w.carry_row, w.carry_val, ntiles, 0, cols, 0, nomap, w.tile_cols, w.gap);
     else
         PSK_LAUNCH((k_spmv_pos<256, 8, 0, 6>), dim3(grid), dim3(256), 0, s, rows, cols, nnz, pos, crd, none, x, y,
-                   w.tile_row, w.carry_row, w.carry_val, ntiles, 0, cols, 0, nomap, w.tile_cols);
+                   w.tile_row, w.carry_row, w.carry_val, ntiles, 0, cols, 0, nomap, w.tile_cols, w.gap);
     return take_launch_status();
 }
 
 hipError_t launch_spmv_csr_main(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
                                 const float *vals, const float *x, float *y, int32_t tile, int32_t col_passes,
-                                const Workspace &w, hipStream_t s, const int32_t *rowmap)
+                                const Workspace &w, hipStream_t s, const int32_t *rowmap, bool gaps)
 {
     const int ntiles = (int)(((int64_t)nnz + tile - 1) / tile);
     if (ntiles == 0) return hipSuccess;
     const int grid = xcd_grid(ntiles);
+    int *gap = gaps ? w.gap : nullptr;
     // baselines: -1 = one pass with atomic adds for rows that span tiles, -2 = one pass without the
     // register temporary and the unrolled load loop
     const int baseline = col_passes == -1 ? 2 : (col_passes == -2 ? 3 : 0);
@@ -415,11 +464,11 @@ hipError_t launch_spmv_csr_main(int32_t rows, int32_t cols, int32_t nnz, const i
     const bool aligned = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
     const int vec = aligned ? 1 : 0;
     switch (tile) {
-        case 256:  launch_pos<64, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap); break;
-        case 512:  launch_pos<128, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap); break;
-        case 1024: launch_pos<256, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap); break;
-        case 2048: launch_pos<256, 8>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap); break;
-        case 4096: launch_pos<256, 16>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap); break;
+        case 256:  launch_pos<64, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap, gap); break;
+        case 512:  launch_pos<128, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap, gap); break;
+        case 1024: launch_pos<256, 4>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap, gap); break;
+        case 2048: launch_pos<256, 8>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap, gap); break;
+        case 4096: launch_pos<256, 16>(vec, grid, s, rows, cols, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, rowmap, gap); break;
         default: return hipErrorInvalidValue;
     }
     }

@@ -118,3 +118,39 @@ def test_sweep_shapes_every_schedule():
             fn(y)
             torch.cuda.synchronize()
             check(y.cpu().numpy(), ref, mag, "%s, %s" % (name, what))
+
+
+def test_long_runs_of_empty_rows():
+    """Ten million empty rows between two groups of stored rows (and more before the first and after the last): the
+    tile that spans the run must not walk it.  Every path that walks rows is exercised: the CSR position cut with one
+    and two column passes and a small tile, a second product on the same table (the run list must start empty again),
+    and the row sums of the slab path."""
+    import time
+
+    rng = np.random.default_rng(77)
+    rows, cols = 10_000_000 + 45_000, 120_000
+    L = np.zeros(rows, dtype=np.int64)
+    L[20_000:22_500] = rng.integers(1, 60, size=2_500)
+    L[21_000] = 30_000                                      # a long row right before the run
+    L[10_022_500:10_025_000] = rng.integers(0, 60, size=2_500)
+    A = wl.csr_from_lengths(L, cols, seed=77)
+    x = wl.dense_uniform(cols, 77, wl.S_X)
+    ref, mag = oracle.spmv_csr(A.pos, A.crd, A.vals, x, threads=8)
+    pos, crd, vals, xd = dev(A.pos), dev(A.crd), dev(A.vals), dev(x)
+    for tile, passes in ((0, 1), (256, 1), (0, 2), (4096, 1)):
+        ws = psk.workspace(psk.PSK_OP_SPMV_CSR, rows, A.nnz, tile=tile)
+        for rep, phases in enumerate((psk.PSK_PHASE_ALL, psk.PSK_PHASE_MAIN | psk.PSK_PHASE_FIXUP)):
+            y = torch.full((rows,), float("nan"), device="cuda")
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            psk.psk_spmv_csr(rows, cols, A.nnz, pos, crd, vals, xd, y, tile=tile, col_passes=passes, phases=phases, ws=ws)
+            torch.cuda.synchronize()
+            say("empty-row run: tile", tile, "passes", passes, "product", rep, "nnz", A.nnz,
+                "%.0f us" % ((time.perf_counter() - t0) * 1e6))
+            check(y.cpu().numpy(), ref, mag, "empty-row run, tile %d passes %d product %d" % (tile, passes, rep))
+    S = psk.psk_slab_build_csr(rows, cols, A.nnz, pos, crd, vals)
+    for rep in range(2):
+        y = torch.full((rows,), float("nan"), device="cuda")
+        psk.psk_spmv_slab(S, xd, y)
+        torch.cuda.synchronize()
+        check(y.cpu().numpy(), ref, mag, "empty-row run, slab path, product %d" % rep)
