@@ -257,6 +257,7 @@ __global__ __launch_bounds__(256) void k_carry_fixup1(int ntiles, long long ld, 
     if ((int)blockIdx.x >= carry_groups) {
         const int fillers = (int)gridDim.x - carry_groups, me = (int)blockIdx.x - carry_groups;
         int n = gap[0];
+        if (n == 0) return;                      // the usual case: no run was listed, nothing to clear or to reset
         n = n < ntiles ? n : ntiles;
         for (int e = 0; e < n; ++e) {
             const long long lo = gap[2 + 2 * e], hi = gap[3 + 2 * e];
