@@ -384,8 +384,10 @@ int psk_spmm_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t
  *   - every slab is padded with empty slots (value 0, column 0) to a multiple of PSK_SLAB_CHUNK slots;
  *     nslots = all slots, nchunks = nslots / PSK_SLAB_CHUNK; slab_chunk[s] = first chunk of slab s
  *     (nslabs + 1 entries);
- *   - a pair is a maximal run of slots of one row inside one chunk; svals[j] / scol[j] hold a slot's value
- *     and its column inside the slab (low 15 bits), bit 15 of scol[j] is set on the last slot of a pair;
+ *   - a pair is a maximal run of slots of one row inside one chunk; scol[j] holds slot j's column inside the
+ *     slab (low 15 bits), bit 15 is set on the last slot of a pair; the slot's value is svals[v(j)], where
+ *     v permutes the slots inside each chunk (slot 8l + k of a chunk sits at (k / 4) * 256 + 4l + k % 4 of the
+ *     chunk, so that 64 lanes that own 8 consecutive slots each fetch them with two contiguous loads);
  *     chunk_pair[c] = index of the pair of chunk c's first slot (nchunks + 1 entries, last = npairs);
  *   - qpos[rows + 1], qidx[nq]: the pairs of each row, in the order of their first slots in the CSR;
  *     qtile_row: the position cut (psk_partition_csr) of (qpos, nq) with tiles of `tile` pairs.

@@ -319,7 +319,11 @@ int oracle_validate_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *
  *
  *   svals[N], scol[N]: value and 15-bit in-slab column of each slot, bit 15 of scol = the slot is the
  *                      last of its pair; pad slots have value 0, column 0 and form pairs of their own
- *                      that no row lists;
+ *                      that no row lists.  scol is stored in slot order.  svals is stored in an order
+ *                      permuted inside every chunk (a storage detail that lets 64 lanes which own 8
+ *                      consecutive slots each fetch them with two contiguous 16-byte loads): when CH is
+ *                      a multiple of 8, slot j of a chunk (lane l = j / 8 of CH / 8 lanes, k = j % 8) sits
+ *                      at offset (k / 4) * (CH / 2) + 4 * l + k % 4 of the chunk; otherwise at offset j.
  *   srow[N]:           row of each slot, -1 for pad slots (only needed while building);
  *   chunk_pair[N/CH + 1]: index of the pair that owns the first slot of each chunk; last = npairs;
  *   slab_chunk[S + 1]: first chunk of each slab; last = N/CH;
@@ -357,6 +361,14 @@ static void slab_slots(int64_t rows, int64_t cols, int64_t nnz, const int32_t *p
             slot_src[j] = p;
         }
     (void)nnz;
+}
+
+/* where the value of slot j is stored (see above) */
+static int64_t slab_value_index(int64_t CH, int64_t j)
+{
+    if (CH % 8 != 0) return j;
+    int64_t c = j / CH, o = j % CH, l = o / 8, k = o % 8;
+    return c * CH + (k / 4) * (CH / 2) + 4 * l + k % 4;
 }
 
 static int slab_is_start(const int32_t *slot_row, int64_t CH, int64_t j)
@@ -409,7 +421,7 @@ int oracle_slab_build(int64_t rows, int64_t cols, int64_t nnz, const int32_t *po
         if (slab_is_start(srow, CH, j)) ++npairs;
         pair_of[j] = (int32_t)(npairs - 1);
         int64_t p = slot_src[j];
-        svals[j] = p >= 0 ? vals[p] : 0.0f;
+        svals[slab_value_index(CH, j)] = p >= 0 ? vals[p] : 0.0f;
         scol[j] = p >= 0 ? (uint16_t)(crd[p] % W) : 0;
         if (p >= 0) slot_of[p] = j;
         if (j % CH == 0) chunk_pair[j / CH] = pair_of[j];
@@ -445,7 +457,7 @@ void oracle_spmv_slab(int64_t rows, int64_t cols, int64_t N, int64_t W, int64_t 
             double acc = 0.0, m = 0.0;
             for (;; ++j) {
                 int64_t col = s * W + (scol[j] & 0x7fff);      /* pad slots: column 0 of the slab, value 0 */
-                double t = (double)svals[j] * (double)x[col];
+                double t = (double)svals[slab_value_index(CH, j)] * (double)x[col];
                 acc += t;
                 m += fabs(t);
                 if (scol[j] & 0x8000u) break;

@@ -42,6 +42,17 @@ def decode(S):
     return slab, col, end, start, pair
 
 
+def value_index(S):
+    """Storage index of every slot's value: inside a chunk whose size is a multiple of 8, slot 8*l + k sits at
+    (k // 4) * (CH // 2) + 4 * l + k % 4; otherwise values are stored in slot order."""
+    j = np.arange(S.nslots, dtype=np.int64)
+    if S.CH % 8:
+        return j
+    c, o = j // S.CH, j % S.CH
+    l, k = o // 8, o % 8
+    return c * S.CH + (k // 4) * (S.CH // 2) + 4 * l + k % 4
+
+
 def structure_ok(A, S) -> bool:
     """Everything the definition fixes, checked without the oracle's own code."""
     rows_of = np.repeat(np.arange(A.rows), np.diff(A.pos))
@@ -55,8 +66,9 @@ def structure_ok(A, S) -> bool:
     order = np.argsort(A.crd // S.W, kind="stable")
     if real.sum() != A.nnz:
         return False
+    vals_by_slot = S.svals[value_index(S)]
     if not (np.array_equal(S.srow[real], rows_of[order]) and np.array_equal(col[real], A.crd[order])
-            and np.array_equal(S.svals[real].view(np.uint32), A.vals[order].view(np.uint32))):
+            and np.array_equal(vals_by_slot[real].view(np.uint32), A.vals[order].view(np.uint32))):
         return False
     # every slab holds its entries first, then fewer than CH pad slots (value 0, column 0)
     counts = np.bincount(A.crd // S.W, minlength=S.nslabs)
@@ -66,7 +78,7 @@ def structure_ok(A, S) -> bool:
         lo, hi = S.slab_chunk[s] * S.CH, S.slab_chunk[s + 1] * S.CH
         if not (real[lo:lo + counts[s]].all() and not real[lo + counts[s]:hi].any()):
             return False
-    if S.svals[~real].any() or (S.scol[~real] & 0x7FFF).any():
+    if vals_by_slot[~real].any() or (S.scol[~real] & 0x7FFF).any():
         return False
     # pairs: a new pair starts exactly where the row changes or a chunk begins; the last slot is an end
     want_start = np.ones(S.nslots, dtype=bool)
@@ -86,7 +98,7 @@ def structure_ok(A, S) -> bool:
     return np.array_equal(S.qpos, want_qpos) and S.nq == int(firsts.sum())
 
 
-CASES = [("mixed", 97, 13), ("empty rows", 1000, 8), ("one long row", 333, 4), ("mixed", 32736, 512),
+CASES = [("mixed", 97, 13), ("empty rows", 1000, 8), ("one long row", 333, 4), ("mixed", 32736, 512), ("mixed", 500, 16),
          ("single entries", 5, 2), ("mixed", 1, 1)]
 
 
@@ -158,7 +170,9 @@ MUTANTS = [
     ("slab_chunk_pair_off_by_one", "if (j % CH == 0) chunk_pair[j / CH] = pair_of[j];", "if (j % CH == 0) chunk_pair[j / CH] = pair_of[j] + 1;"),
     ("slab_spmv_wrong_slab_offset", "int64_t col = s * W + (scol[j] & 0x7fff);", "int64_t col = s * CH + (scol[j] & 0x7fff);"),
     ("slab_spmv_drops_pair", "for (int64_t q = qpos[i]; q < qpos[i + 1]; ++q) { acc += P[qidx[q]];", "for (int64_t q = qpos[i] + 1; q < qpos[i + 1]; ++q) { acc += P[qidx[q]];"),
-    ("slab_values_by_slot", "svals[j] = p >= 0 ? vals[p] : 0.0f;", "svals[j] = p >= 0 ? vals[j < nnz ? j : 0] : 0.0f;"),
+    ("slab_values_by_slot", "svals[slab_value_index(CH, j)] = p >= 0 ? vals[p] : 0.0f;", "svals[slab_value_index(CH, j)] = p >= 0 ? vals[j < nnz ? j : 0] : 0.0f;"),
+    ("slab_values_not_permuted", "svals[slab_value_index(CH, j)] = p >= 0 ? vals[p] : 0.0f;", "svals[j] = p >= 0 ? vals[p] : 0.0f;"),
+    ("slab_permutation_swaps_halves", "return c * CH + (k / 4) * (CH / 2) + 4 * l + k % 4;", "return c * CH + (1 - k / 4) * (CH / 2) + 4 * l + k % 4;"),
 ]
 
 
@@ -202,3 +216,16 @@ def test_mutant_is_caught(tmp_path, name, old, new):
     assert SRC.count(old) >= 1, "mutation site not found: the oracle source changed, update this test"
     mutated = SRC.replace(old, new)
     assert not pins_pass(compile_variant(tmp_path, name, mutated)), "mutant survived: " + name
+
+
+def test_value_order_inside_a_chunk_of_16():
+    """Listed by hand: with chunks of 16 slots two lanes own slots 0-7 and 8-15; the values are stored as the first
+    halves of both lanes' slots, then the second halves: s0 s1 s2 s3 | s8 s9 s10 s11 | s4 s5 s6 s7 | s12 s13 s14 s15."""
+    pos = np.array([0, 16], dtype=np.int32)
+    crd = np.arange(16, dtype=np.int32)
+    vals = np.arange(100, 116, dtype=np.float32)
+    S = oracle.slab_build(1, 40, pos, crd, vals, W=40, CH=16)
+    assert S.svals.tolist() == [100, 101, 102, 103, 108, 109, 110, 111, 104, 105, 106, 107, 112, 113, 114, 115]
+    assert (S.scol & 0x7FFF).tolist() == list(range(16))        # columns stay in slot order
+    y, _ = oracle.spmv_slab(S, np.arange(40, dtype=np.float32))
+    assert y.tolist() == [float(sum((100 + i) * i for i in range(16)))]
