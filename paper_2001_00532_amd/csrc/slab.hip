@@ -96,11 +96,11 @@ __global__ __launch_bounds__(1024) void k_slab_pairs(const float *__restrict__ s
     // the run list of the second step starts empty (that step's tiles append to it, the fix-up consumes it)
     if (blockIdx.x == 0 && threadIdx.x == 0 && gap) { gap[0] = 0; gap[1] = 0; }
     __shared__ float xs[SLAB_W];
-    __shared__ float stage[WAVES * SLAB_CH + 16];
+    __shared__ float stage[WAVES * SLAB_CH + 32];     // + one dummy word per LDS bank
     const int tid = threadIdx.x, lane = tid & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
     float *st = stage + wave * SLAB_CH;
-    const int dummy = (WAVES - wave) * SLAB_CH + (lane & 15);      // index, relative to st, of a word nobody reads
+    const int dummy = (WAVES - wave) * SLAB_CH + (lane & 31);      // index, relative to st, of a word nobody reads
     int c0 = blockIdx.x * cpw;
     const int c1 = min(c0 + cpw, nchunks);
     if (c0 >= c1) return;
