@@ -138,3 +138,32 @@ def test_mttkrp_full_size():
     sel = sample_rows(T.nslices, 20000, 9)
     ref, mag = oracle.mttkrp_csf3(T.pos_k, T.crd_k, T.pos_l, T.crd_l, T.vals, C, D, sel=sel, threads=16)
     check(A[torch.from_numpy(sel).cuda()].cpu().numpy(), ref, mag, "mttkrp sampled slices")
+
+
+def test_slab_path_full_size_power_law():
+    """The launch configuration bench.py times by default: the power-law matrix at full size through the slab path.
+    The structure is compared in full with the oracle's (bit for bit), the product in full with the CSR definition."""
+    c = wl.config(2)
+    A = c["A"]
+    pos, crd, vals, x = dev(A.pos), dev(A.crd), dev(A.vals), dev(c["x"])
+    say("slab path, full size: rows", A.rows, "nnz", A.nnz)
+    S = psk.psk_slab_build_csr(A.rows, A.cols, A.nnz, pos, crd, vals)
+    O = oracle.slab_build(A.rows, A.cols, A.pos, A.crd, A.vals)
+    d = S.desc
+    assert (d.nslots, d.npairs, d.nq, d.nslabs) == (O.nslots, O.npairs, O.nq, O.nslabs)
+    for arr in ("slab_chunk", "chunk_pair", "qpos", "qidx"):
+        assert np.array_equal(S.array(arr).cpu().numpy(), getattr(O, arr)), arr
+    assert np.array_equal(S.array("scol").cpu().numpy().view(np.uint16), O.scol)
+    assert np.array_equal(S.array("svals").cpu().numpy().view(np.uint32), O.svals.view(np.uint32))
+    assert np.array_equal(S.array("qtile_row").cpu().numpy(), oracle.partition(O.qpos, d.tile))
+    ws = psk.psk_slab_spmv_workspace(S)
+    y = torch.full((A.rows,), float("nan"), device="cuda")
+    psk.psk_spmv_slab(S, x, y, ws=ws)
+    torch.cuda.synchronize()
+    first = y.clone()
+    ref, mag = oracle.spmv_csr(A.pos, A.crd, A.vals, c["x"], threads=16)
+    check(y.cpu().numpy(), ref, mag, "slab path, configuration 2 in full")
+    y.fill_(float("nan"))
+    psk.psk_spmv_slab(S, x, y, ws=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(first, y), "the slab product is not deterministic"
