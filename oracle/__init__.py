@@ -70,6 +70,10 @@ def _lib():
         lib.oracle_slab_build.restype = ci
         lib.oracle_spmv_slab.argtypes = [i64, i64, i64, i64, i64, p, p, p, p, p, p, p, p, p, p]
         lib.oracle_spmv_slab.restype = None
+        lib.oracle_slab_build_f64.argtypes = [i64, i64, i64, p, p, p, i64, i64, p, p, p, p, p, p, p]
+        lib.oracle_slab_build_f64.restype = ci
+        lib.oracle_spmv_slab_f64.argtypes = [i64, i64, i64, i64, i64, p, p, p, p, p, p, p, p]
+        lib.oracle_spmv_slab_f64.restype = ci
         _h = lib
     return _h
 
@@ -248,8 +252,11 @@ class Slab:
     slab_chunk, qpos, qidx and the sizes nslots, npairs, nq, nslabs."""
 
 
-def slab_build(rows: int, cols: int, pos, crd, vals, W: int = 32736, CH: int = 512) -> Slab:
-    pos, crd, vals = _i32(pos), _i32(crd), _f32(vals)
+def slab_build(rows: int, cols: int, pos, crd, vals, W: int = 32736, CH: int = 512, f64: bool = False) -> Slab:
+    """fp32 values by default; f64=True keeps the values as doubles (the structure is the same, the values'
+    storage order inside a chunk follows the 8-byte rule)."""
+    pos, crd = _i32(pos), _i32(crd)
+    vals = np.ascontiguousarray(vals, dtype=np.float64) if f64 else _f32(vals)
     nnz = int(crd.size)
     sizes = np.zeros(4, dtype=np.int64)
     if _lib().oracle_slab_count(rows, cols, nnz, pos.ctypes.data, crd.ctypes.data, W, CH, sizes.ctypes.data) != 0:
@@ -257,22 +264,33 @@ def slab_build(rows: int, cols: int, pos, crd, vals, W: int = 32736, CH: int = 5
     S = Slab()
     S.rows, S.cols, S.nnz, S.W, S.CH = rows, cols, nnz, W, CH
     S.nslots, S.npairs, S.nq, S.nslabs = (int(v) for v in sizes)
-    S.svals = np.empty(S.nslots, dtype=np.float32)
+    S.f64 = bool(f64)
+    S.svals = np.empty(S.nslots, dtype=np.float64 if f64 else np.float32)
     S.scol = np.empty(S.nslots, dtype=np.uint16)
     S.srow = np.empty(S.nslots, dtype=np.int32)
     S.chunk_pair = np.empty(S.nslots // CH + 1, dtype=np.int32)
     S.slab_chunk = np.empty(S.nslabs + 1, dtype=np.int32)
     S.qpos = np.empty(rows + 1, dtype=np.int32)
     S.qidx = np.empty(S.nq, dtype=np.int32)
-    if _lib().oracle_slab_build(rows, cols, nnz, pos.ctypes.data, crd.ctypes.data, vals.ctypes.data, W, CH,
-                                S.svals.ctypes.data, S.scol.ctypes.data, S.srow.ctypes.data, S.chunk_pair.ctypes.data,
-                                S.slab_chunk.ctypes.data, S.qpos.ctypes.data, S.qidx.ctypes.data) != 0:
+    build = _lib().oracle_slab_build_f64 if f64 else _lib().oracle_slab_build
+    if build(rows, cols, nnz, pos.ctypes.data, crd.ctypes.data, vals.ctypes.data, W, CH, S.svals.ctypes.data,
+             S.scol.ctypes.data, S.srow.ctypes.data, S.chunk_pair.ctypes.data, S.slab_chunk.ctypes.data,
+             S.qpos.ctypes.data, S.qidx.ctypes.data) != 0:
         raise MemoryError("oracle_slab_build")
     return S
 
 
 def spmv_slab(S: Slab, x):
     """y and mag (float64, one per row) evaluated over the slab structure: P per pair, then the pairs of each row."""
+    if getattr(S, "f64", False):
+        x = np.ascontiguousarray(x, dtype=np.float64)
+        y = np.empty(S.rows, dtype=np.float64)
+        mag = np.empty(S.rows, dtype=np.float64)
+        if _lib().oracle_spmv_slab_f64(S.rows, S.cols, S.npairs, S.W, S.CH, S.svals.ctypes.data, S.scol.ctypes.data,
+                                       S.slab_chunk.ctypes.data, S.qpos.ctypes.data, S.qidx.ctypes.data,
+                                       x.ctypes.data, y.ctypes.data, mag.ctypes.data) != 0:
+            raise MemoryError("oracle_spmv_slab_f64")
+        return y, mag
     x = _f32(x)
     P = np.empty(max(S.npairs, 1), dtype=np.float64)
     Pm = np.empty(max(S.npairs, 1), dtype=np.float64)

@@ -320,10 +320,12 @@ int oracle_validate_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *
  *   svals[N], scol[N]: value and 15-bit in-slab column of each slot, bit 15 of scol = the slot is the
  *                      last of its pair; pad slots have value 0, column 0 and form pairs of their own
  *                      that no row lists.  scol is stored in slot order.  svals is stored in an order
- *                      permuted inside every chunk (a storage detail that lets 64 lanes which own 8
- *                      consecutive slots each fetch them with two contiguous 16-byte loads): when CH is
- *                      a multiple of 8, slot j of a chunk (lane l = j / 8 of CH / 8 lanes, k = j % 8) sits
- *                      at offset (k / 4) * (CH / 2) + 4 * l + k % 4 of the chunk; otherwise at offset j.
+ *                      permuted inside every chunk (a storage detail that lets CH / 8 lanes which own 8
+ *                      consecutive slots each fetch them with contiguous 16-byte loads): when CH is a
+ *                      multiple of 8, slot j of a chunk (lane l = j / 8, k = j % 8) sits at offset
+ *                      (k / g) * (CH / 8 * g) + g * l + k % g of the chunk, g = values per 16 bytes
+ *                      (4 for fp32: (k / 4) * (CH / 2) + 4 * l + k % 4; 2 for fp64:
+ *                      (k / 2) * (CH / 4) + 2 * l + k % 2); otherwise at offset j.
  *   srow[N]:           row of each slot, -1 for pad slots (only needed while building);
  *   chunk_pair[N/CH + 1]: index of the pair that owns the first slot of each chunk; last = npairs;
  *   slab_chunk[S + 1]: first chunk of each slab; last = N/CH;
@@ -363,13 +365,14 @@ static void slab_slots(int64_t rows, int64_t cols, int64_t nnz, const int32_t *p
     (void)nnz;
 }
 
-/* where the value of slot j is stored (see above) */
-static int64_t slab_value_index(int64_t CH, int64_t j)
+/* where the value of slot j is stored (see above); g = values per 16 bytes */
+static int64_t slab_value_index_g(int64_t CH, int64_t j, int64_t g)
 {
     if (CH % 8 != 0) return j;
     int64_t c = j / CH, o = j % CH, l = o / 8, k = o % 8;
-    return c * CH + (k / 4) * (CH / 2) + 4 * l + k % 4;
+    return c * CH + (k / g) * (CH / 8 * g) + g * l + k % g;
 }
+static int64_t slab_value_index(int64_t CH, int64_t j) { return slab_value_index_g(CH, j, 4); }
 
 static int slab_is_start(const int32_t *slot_row, int64_t CH, int64_t j)
 {
@@ -400,11 +403,13 @@ int oracle_slab_count(int64_t rows, int64_t cols, int64_t nnz, const int32_t *po
     return 0;
 }
 
-int oracle_slab_build(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
-                      const float *vals, int64_t W, int64_t CH, float *svals, uint16_t *scol, int32_t *srow,
-                      int32_t *chunk_pair, int32_t *slab_chunk, int32_t *qpos, int32_t *qidx)
+/* The structure for values of vbytes bytes each (4: float, 8: double); values are only moved. */
+static int slab_build_any(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                          const void *vals, int vbytes, int64_t W, int64_t CH, void *svals, uint16_t *scol,
+                          int32_t *srow, int32_t *chunk_pair, int32_t *slab_chunk, int32_t *qpos, int32_t *qidx)
 {
     int64_t S = (cols + W - 1) / W;
+    int64_t g = 16 / vbytes;
     int64_t *base = (int64_t *)malloc((size_t)(S + 1) * sizeof(int64_t));
     int64_t *fill = (int64_t *)malloc((size_t)(S + 1) * sizeof(int64_t));
     if (!base || !fill) { free(base); free(fill); return -1; }
@@ -421,7 +426,9 @@ int oracle_slab_build(int64_t rows, int64_t cols, int64_t nnz, const int32_t *po
         if (slab_is_start(srow, CH, j)) ++npairs;
         pair_of[j] = (int32_t)(npairs - 1);
         int64_t p = slot_src[j];
-        svals[slab_value_index(CH, j)] = p >= 0 ? vals[p] : 0.0f;
+        int64_t at = slab_value_index_g(CH, j, g);
+        if (vbytes == 4) ((float *)svals)[at] = p >= 0 ? ((const float *)vals)[p] : 0.0f;
+        else ((double *)svals)[at] = p >= 0 ? ((const double *)vals)[p] : 0.0;
         scol[j] = p >= 0 ? (uint16_t)(crd[p] % W) : 0;
         if (p >= 0) slot_of[p] = j;
         if (j % CH == 0) chunk_pair[j / CH] = pair_of[j];
@@ -441,6 +448,23 @@ int oracle_slab_build(int64_t rows, int64_t cols, int64_t nnz, const int32_t *po
     qpos[rows] = (int32_t)nq;
     free(base); free(fill); free(slot_src); free(pair_of); free(slot_of);
     return 0;
+}
+
+int oracle_slab_build(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                      const float *vals, int64_t W, int64_t CH, float *svals, uint16_t *scol, int32_t *srow,
+                      int32_t *chunk_pair, int32_t *slab_chunk, int32_t *qpos, int32_t *qidx)
+{
+    return slab_build_any(rows, cols, nnz, pos, crd, vals, 4, W, CH, svals, scol, srow, chunk_pair, slab_chunk, qpos,
+                          qidx);
+}
+
+/* fp64 values (the paper's own value type, appendix "SPMV on a GPU"): same structure, 8-byte values */
+int oracle_slab_build_f64(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                          const double *vals, int64_t W, int64_t CH, double *svals, uint16_t *scol, int32_t *srow,
+                          int32_t *chunk_pair, int32_t *slab_chunk, int32_t *qpos, int32_t *qidx)
+{
+    return slab_build_any(rows, cols, nnz, pos, crd, vals, 8, W, CH, svals, scol, srow, chunk_pair, slab_chunk, qpos,
+                          qidx);
 }
 
 /* The SpMV evaluated over the structure, step by step as described above, in fp64: first P per pair, then
@@ -473,4 +497,39 @@ void oracle_spmv_slab(int64_t rows, int64_t cols, int64_t N, int64_t W, int64_t 
         y[i] = acc;
         if (mag) mag[i] = m;
     }
+}
+
+/* The same for fp64 operands: products and sums in long double, P kept in long double, one rounding per row
+ * (as oracle_spmv_csr_f64).  P and Pmag have npairs long doubles (scratch, allocated here). */
+int oracle_spmv_slab_f64(int64_t rows, int64_t cols, int64_t npairs, int64_t W, int64_t CH, const double *svals,
+                         const uint16_t *scol, const int32_t *slab_chunk, const int32_t *qpos,
+                         const int32_t *qidx, const double *x, double *y, double *mag)
+{
+    int64_t S = (cols + W - 1) / W;
+    long double *P = (long double *)malloc((size_t)(npairs + 1) * sizeof(long double));
+    long double *Pmag = (long double *)malloc((size_t)(npairs + 1) * sizeof(long double));
+    if (!P || !Pmag) { free(P); free(Pmag); return -1; }
+    int64_t pair = 0;
+    for (int64_t s = 0; s < S; ++s)
+        for (int64_t j = (int64_t)slab_chunk[s] * CH; j < (int64_t)slab_chunk[s + 1] * CH; ++j) {
+            long double acc = 0.0L, m = 0.0L;
+            for (;; ++j) {
+                int64_t col = s * W + (scol[j] & 0x7fff);
+                long double t = (long double)svals[slab_value_index_g(CH, j, 2)] * (long double)x[col];
+                acc += t;
+                m += fabsl(t);
+                if (scol[j] & 0x8000u) break;
+            }
+            P[pair] = acc;
+            Pmag[pair] = m;
+            ++pair;
+        }
+    for (int64_t i = 0; i < rows; ++i) {
+        long double acc = 0.0L, m = 0.0L;
+        for (int64_t q = qpos[i]; q < qpos[i + 1]; ++q) { acc += P[qidx[q]]; m += Pmag[qidx[q]]; }
+        y[i] = (double)acc;
+        if (mag) mag[i] = (double)m;
+    }
+    free(P); free(Pmag);
+    return 0;
 }

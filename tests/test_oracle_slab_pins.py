@@ -20,14 +20,19 @@ SRC = open(os.path.join(os.path.dirname(HERE), "oracle", "oracle.c")).read()
 
 def hand_case_ok() -> bool:
     g = GOLD
-    S = oracle.slab_build(g["rows"], g["cols"], g["pos"], g["crd"], g["vals"], W=g["W"], CH=g["CH"])
-    if (S.nslots, S.npairs, S.nq, S.nslabs) != (g["nslots"], g["npairs"], g["nq"], g["nslabs"]):
-        return False
-    for name in ("svals", "scol", "srow", "chunk_pair", "slab_chunk", "qpos", "qidx"):
-        if getattr(S, name).tolist() != g[name]:
+    for f64 in (False, True):            # chunks of 2 slots: values in slot order for either value type
+        S = oracle.slab_build(g["rows"], g["cols"], g["pos"], g["crd"], g["vals"], W=g["W"], CH=g["CH"], f64=f64)
+        if (S.nslots, S.npairs, S.nq, S.nslabs) != (g["nslots"], g["npairs"], g["nq"], g["nslabs"]):
             return False
-    y, mag = oracle.spmv_slab(S, g["x"])
-    return y.tolist() == g["y"] and mag.tolist() == g["mag"]
+        if S.svals.dtype != (np.float64 if f64 else np.float32):
+            return False
+        for name in ("svals", "scol", "srow", "chunk_pair", "slab_chunk", "qpos", "qidx"):
+            if getattr(S, name).tolist() != g[name]:
+                return False
+        y, mag = oracle.spmv_slab(S, g["x"])
+        if not (y.tolist() == g["y"] and mag.tolist() == g["mag"]):
+            return False
+    return True
 
 
 def decode(S):
@@ -44,12 +49,15 @@ def decode(S):
 
 def value_index(S):
     """Storage index of every slot's value: inside a chunk whose size is a multiple of 8, slot 8*l + k sits at
-    (k // 4) * (CH // 2) + 4 * l + k % 4; otherwise values are stored in slot order."""
+    (k // 4) * (CH // 2) + 4 * l + k % 4 for 4-byte values and at (k // 2) * (CH // 4) + 2 * l + k % 2 for 8-byte
+    values (groups of 16 bytes, lane after lane); otherwise values are stored in slot order."""
     j = np.arange(S.nslots, dtype=np.int64)
     if S.CH % 8:
         return j
     c, o = j // S.CH, j % S.CH
     l, k = o // 8, o % 8
+    if S.svals.dtype == np.float64:
+        return c * S.CH + (k // 2) * (S.CH // 4) + 2 * l + k % 2
     return c * S.CH + (k // 4) * (S.CH // 2) + 4 * l + k % 4
 
 
@@ -67,8 +75,9 @@ def structure_ok(A, S) -> bool:
     if real.sum() != A.nnz:
         return False
     vals_by_slot = S.svals[value_index(S)]
+    want_vals = A.vals[order].astype(S.svals.dtype)          # fp32 -> fp64 is exact
     if not (np.array_equal(S.srow[real], rows_of[order]) and np.array_equal(col[real], A.crd[order])
-            and np.array_equal(vals_by_slot[real].view(np.uint32), A.vals[order].view(np.uint32))):
+            and vals_by_slot[real].tobytes() == want_vals.tobytes()):
         return False
     # every slab holds its entries first, then fewer than CH pad slots (value 0, column 0)
     counts = np.bincount(A.crd // S.W, minlength=S.nslabs)
@@ -120,6 +129,20 @@ def properties_ok() -> bool:
         ref, rmag = oracle.spmv_csr(A.pos, A.crd, A.vals, x)
         if not (np.allclose(y, ref, rtol=0, atol=1e-12) and np.allclose(mag, rmag, rtol=1e-12, atol=0)):
             return False
+        # 8-byte values: same structure, other storage order of the values, product in extended precision
+        v64 = A.vals.astype(np.float64) * (1.0 + 2.0 ** -40)            # not representable in fp32
+        x64 = x.astype(np.float64) * (1.0 - 2.0 ** -41)
+        S64 = oracle.slab_build(A.rows, A.cols, A.pos, A.crd, v64, W=W, CH=CH, f64=True)
+        for name in ("scol", "srow", "chunk_pair", "slab_chunk", "qpos", "qidx"):
+            if not np.array_equal(getattr(S64, name), getattr(S, name)):
+                return False
+        if S64.svals[value_index(S64)][S64.srow >= 0].tobytes() != v64[np.argsort(A.crd // W, kind="stable")].tobytes():
+            return False
+        y64, mag64 = oracle.spmv_slab(S64, x64)
+        ref64, rmag64 = oracle.spmv_csr_f64(A.pos, A.crd, v64, x64)
+        if not (np.allclose(y64, ref64, rtol=0, atol=1e-15 * max(1.0, float(rmag64.max(initial=0.0))))
+                and np.allclose(mag64, rmag64, rtol=1e-15, atol=0)):
+            return False
     # unsorted and repeated columns inside a row: the order of the CSR is kept inside a slab
     pos = np.array([0, 5, 5, 7], dtype=np.int32)
     crd = np.array([9, 1, 9, 0, 4, 8, 8], dtype=np.int32)
@@ -170,9 +193,22 @@ MUTANTS = [
     ("slab_chunk_pair_off_by_one", "if (j % CH == 0) chunk_pair[j / CH] = pair_of[j];", "if (j % CH == 0) chunk_pair[j / CH] = pair_of[j] + 1;"),
     ("slab_spmv_wrong_slab_offset", "int64_t col = s * W + (scol[j] & 0x7fff);", "int64_t col = s * CH + (scol[j] & 0x7fff);"),
     ("slab_spmv_drops_pair", "for (int64_t q = qpos[i]; q < qpos[i + 1]; ++q) { acc += P[qidx[q]];", "for (int64_t q = qpos[i] + 1; q < qpos[i + 1]; ++q) { acc += P[qidx[q]];"),
-    ("slab_values_by_slot", "svals[slab_value_index(CH, j)] = p >= 0 ? vals[p] : 0.0f;", "svals[slab_value_index(CH, j)] = p >= 0 ? vals[j < nnz ? j : 0] : 0.0f;"),
-    ("slab_values_not_permuted", "svals[slab_value_index(CH, j)] = p >= 0 ? vals[p] : 0.0f;", "svals[j] = p >= 0 ? vals[p] : 0.0f;"),
-    ("slab_permutation_swaps_halves", "return c * CH + (k / 4) * (CH / 2) + 4 * l + k % 4;", "return c * CH + (1 - k / 4) * (CH / 2) + 4 * l + k % 4;"),
+    ("slab_values_by_slot", "((float *)svals)[at] = p >= 0 ? ((const float *)vals)[p] : 0.0f;",
+     "((float *)svals)[at] = p >= 0 ? ((const float *)vals)[j < nnz ? j : 0] : 0.0f;"),
+    ("slab_values_not_permuted", "int64_t at = slab_value_index_g(CH, j, g);", "int64_t at = j;"),
+    ("slab_permutation_swaps_groups", "return c * CH + (k / g) * (CH / 8 * g) + g * l + k % g;",
+     "return c * CH + (8 / g - 1 - k / g) * (CH / 8 * g) + g * l + k % g;"),
+    ("slab_f64_values_by_slot", "((double *)svals)[at] = p >= 0 ? ((const double *)vals)[p] : 0.0;",
+     "((double *)svals)[at] = p >= 0 ? ((const double *)vals)[j < nnz ? j : 0] : 0.0;"),
+    ("slab_f64_values_rounded_to_fp32", "((double *)svals)[at] = p >= 0 ? ((const double *)vals)[p] : 0.0;",
+     "((double *)svals)[at] = p >= 0 ? (float)((const double *)vals)[p] : 0.0;"),
+    ("slab_f64_groups_of_four", "int64_t g = 16 / vbytes;", "int64_t g = 4;"),
+    ("slab_f64_spmv_reads_fp32_order", "(long double)svals[slab_value_index_g(CH, j, 2)] * (long double)x[col];",
+     "(long double)svals[slab_value_index_g(CH, j, 4)] * (long double)x[col];"),
+    ("slab_f64_spmv_drops_pair", "for (int64_t q = qpos[i]; q < qpos[i + 1]; ++q) { acc += P[qidx[q]]; m += Pmag[qidx[q]]; }\n        y[i] = (double)acc;",
+     "for (int64_t q = qpos[i] + 1; q < qpos[i + 1]; ++q) { acc += P[qidx[q]]; m += Pmag[qidx[q]]; }\n        y[i] = (double)acc;"),
+    ("slab_f64_spmv_in_double_products_of_floats", "long double t = (long double)svals[slab_value_index_g(CH, j, 2)] * (long double)x[col];",
+     "long double t = (long double)((float)svals[slab_value_index_g(CH, j, 2)] * (float)x[col]);"),
 ]
 
 
@@ -201,7 +237,7 @@ def compile_variant(tmp_path, name, text):
 def pins_pass(lib) -> bool:
     def run():
         try:
-            return hand_case_ok() and properties_ok()
+            return hand_case_ok() and properties_ok() and value_order_16_ok()
         except (IndexError, ValueError):
             return False          # a mutant may produce arrays that do not even decode
     return with_library(lib, run)
@@ -218,14 +254,42 @@ def test_mutant_is_caught(tmp_path, name, old, new):
     assert not pins_pass(compile_variant(tmp_path, name, mutated)), "mutant survived: " + name
 
 
-def test_value_order_inside_a_chunk_of_16():
-    """Listed by hand: with chunks of 16 slots two lanes own slots 0-7 and 8-15; the values are stored as the first
-    halves of both lanes' slots, then the second halves: s0 s1 s2 s3 | s8 s9 s10 s11 | s4 s5 s6 s7 | s12 s13 s14 s15."""
+def value_order_16_ok() -> bool:
+    """Listed by hand: with chunks of 16 slots two lanes own slots 0-7 and 8-15.  4-byte values are stored as the
+    first halves of both lanes' slots, then the second halves: s0 s1 s2 s3 | s8 s9 s10 s11 | s4 s5 s6 s7 | s12 s13 s14
+    s15; 8-byte values as the lanes' first, second, third and fourth pairs of slots: s0 s1 | s8 s9 | s2 s3 | s10 s11 |
+    s4 s5 | s12 s13 | s6 s7 | s14 s15."""
     pos = np.array([0, 16], dtype=np.int32)
     crd = np.arange(16, dtype=np.int32)
     vals = np.arange(100, 116, dtype=np.float32)
     S = oracle.slab_build(1, 40, pos, crd, vals, W=40, CH=16)
-    assert S.svals.tolist() == [100, 101, 102, 103, 108, 109, 110, 111, 104, 105, 106, 107, 112, 113, 114, 115]
-    assert (S.scol & 0x7FFF).tolist() == list(range(16))        # columns stay in slot order
+    if S.svals.tolist() != [100, 101, 102, 103, 108, 109, 110, 111, 104, 105, 106, 107, 112, 113, 114, 115]:
+        return False
+    if (S.scol & 0x7FFF).tolist() != list(range(16)):           # columns stay in slot order
+        return False
     y, _ = oracle.spmv_slab(S, np.arange(40, dtype=np.float32))
-    assert y.tolist() == [float(sum((100 + i) * i for i in range(16)))]
+    if y.tolist() != [float(sum((100 + i) * i for i in range(16)))]:
+        return False
+    S = oracle.slab_build(1, 40, pos, crd, vals, W=40, CH=16, f64=True)
+    if S.svals.tolist() != [100, 101, 108, 109, 102, 103, 110, 111, 104, 105, 112, 113, 106, 107, 114, 115]:
+        return False
+    if (S.scol & 0x7FFF).tolist() != list(range(16)):
+        return False
+    y, _ = oracle.spmv_slab(S, np.arange(40, dtype=np.float64))
+    return y.tolist() == [float(sum((100 + i) * i for i in range(16)))]
+
+
+def test_value_order_inside_a_chunk_of_16():
+    assert value_order_16_ok()
+
+
+def test_f64_product_rounds_once():
+    """A row whose exact sum needs more than 53 bits on the way: 1 + 2^-60 - 1 over three slabs.  Sums kept in
+    extended precision give 2^-60; a double accumulator would give 0."""
+    pos = np.array([0, 3], dtype=np.int32)
+    crd = np.array([0, 5, 9], dtype=np.int32)
+    vals = np.array([1.0, 2.0 ** -60, -1.0])
+    S = oracle.slab_build(1, 12, pos, crd, vals, W=4, CH=2, f64=True)
+    y, mag = oracle.spmv_slab(S, np.ones(12))
+    assert y.tolist() == [2.0 ** -60]
+    assert mag.tolist() == [2.0]                 # 2 + 2^-60 rounded to double
