@@ -387,7 +387,8 @@ int psk_spmm_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t
  *   - a pair is a maximal run of slots of one row inside one chunk; scol[j] holds slot j's column inside the
  *     slab (low 15 bits), bit 15 is set on the last slot of a pair; the slot's value is svals[v(j)], where
  *     v permutes the slots inside each chunk (slot 8l + k of a chunk sits at (k / 4) * 256 + 4l + k % 4 of the
- *     chunk, so that 64 lanes that own 8 consecutive slots each fetch them with two contiguous loads);
+ *     chunk, so that 64 lanes that own 8 consecutive slots each fetch them with two contiguous loads; with
+ *     8-byte values at (k / 2) * 128 + 2l + k % 2: four loads);
  *     chunk_pair[c] = index of the pair of chunk c's first slot (nchunks + 1 entries, last = npairs);
  *   - qpos[rows + 1], qidx[nq]: the pairs of each row, in the order of their first slots in the CSR;
  *     qtile_row: the position cut (psk_partition_csr) of (qpos, nq) with tiles of `tile` pairs.
@@ -397,14 +398,20 @@ int psk_spmm_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t
  *
  * Limits: cols <= 8192 * PSK_SLAB_COLS, nnz + 511 * nslabs < 2^31, nslabs * ceil(nnz / 2048) <= 2^30
  * (PSK_ERR_UNSUPPORTED / PSK_ERR_SIZE otherwise).
+ *
+ * fp64 values (the value type of the paper's own schedules, appendix "SPMV on a GPU"): the _f64 entry points
+ * build and use the same structure with 8-byte values and slabs of PSK_SLAB_COLS_F64 columns (a slab of x and
+ * the staging area of the pair sums share the 160 KB of on-chip memory); x, y and the pair sums are doubles.
+ * The fp64 row-sum kernel clears rows without entries one by one (no run list for long runs of empty rows).
  */
 #define PSK_SLAB_COLS 32736
+#define PSK_SLAB_COLS_F64 12256
 #define PSK_SLAB_CHUNK 512
 typedef struct psk_slab {
     int64_t rows, cols, nnz;
     int64_t nslabs, nslots, nchunks, npairs, nq;
-    int32_t slab_cols, chunk, tile, reserved;
-    const float *svals;          /* [nslots]  device */
+    int32_t slab_cols, chunk, tile, value_bytes;   /* value_bytes: 4 (float) or 8 (double) */
+    const void *svals;           /* [nslots] floats or doubles, device */
     const uint16_t *scol;        /* [nslots]  device */
     const int32_t *chunk_pair;   /* [nchunks + 1] device */
     const int32_t *slab_chunk;   /* [nslabs + 1]  device */
@@ -417,8 +424,10 @@ typedef struct psk_slab {
  * exact size depends on how the entries fall into slabs and chunks; about 10 bytes per entry + 4 per row);
  * 0 when the sizes are outside the limits above. */
 size_t psk_slab_mem_bytes(int64_t rows, int64_t cols, int64_t nnz);
+size_t psk_slab_mem_bytes_f64(int64_t rows, int64_t cols, int64_t nnz);
 /* Bytes of scratch memory psk_slab_build_csr needs (about 20 bytes per entry); free to reuse afterwards. */
 size_t psk_slab_build_workspace_bytes(int64_t rows, int64_t cols, int64_t nnz);
+size_t psk_slab_build_workspace_bytes_f64(int64_t rows, int64_t cols, int64_t nnz);
 /* Bytes of workspace a product over S needs (the pair sums and the carry records); 0 if S is NULL. */
 size_t psk_slab_spmv_workspace_bytes(const psk_slab *S);
 
@@ -434,6 +443,10 @@ size_t psk_slab_spmv_workspace_bytes(const psk_slab *S);
 int psk_slab_build_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
                        const float *vals, void *mem, size_t mem_bytes, void *workspace, size_t workspace_bytes,
                        psk_slab *out, void *stream);
+/* The same for fp64 values (8-byte aligned, PSK_ERR_ALIGNMENT otherwise); sizes from the _f64 size functions. */
+int psk_slab_build_csr_f64(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,
+                           const double *vals, void *mem, size_t mem_bytes, void *workspace,
+                           size_t workspace_bytes, psk_slab *out, void *stream);
 
 /*
  * y = A x over the structure: x has S->cols entries, y S->rows entries (assigned, rows without entries
@@ -445,6 +458,10 @@ int psk_slab_build_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *p
  */
 int psk_spmv_slab(const psk_slab *S, const float *x, float *y, int phases, void *workspace,
                   size_t workspace_bytes, void *stream);
+/* The same over a structure built by psk_slab_build_csr_f64 (PSK_ERR_SIZE for a structure of the other value
+ * type); x and y doubles, 8-byte aligned; products and sums in fp64; result bar as psk_spmv_csr_f64. */
+int psk_spmv_slab_f64(const psk_slab *S, const double *x, double *y, int phases, void *workspace,
+                      size_t workspace_bytes, void *stream);
 
 /*
  * ---- per-CU load balance (instrumented build only) ----

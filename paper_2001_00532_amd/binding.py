@@ -30,7 +30,8 @@ EXPORTS = [
     "psk_partition_csf3", "psk_spmv_csr_notemp", "psk_spmv_csr_f64", "psk_spmv_dcsr", "psk_spmv_csr_divide", "psk_suggest_schedule_csr", "psk_default_tile_bcsr", "psk_validate_csr",
     "psk_spmv_csr_static", "psk_static_scratch_bytes",
     "psk_slab_mem_bytes", "psk_slab_build_workspace_bytes", "psk_slab_spmv_workspace_bytes", "psk_slab_build_csr",
-    "psk_spmv_slab", "psk_cu_trace_set", "psk_calibrate_stream_read", "psk_calibrate_gather", "psk_calibrate_gather_lds",
+    "psk_spmv_slab", "psk_slab_mem_bytes_f64", "psk_slab_build_workspace_bytes_f64", "psk_slab_build_csr_f64",
+    "psk_spmv_slab_f64", "psk_cu_trace_set", "psk_calibrate_stream_read", "psk_calibrate_gather", "psk_calibrate_gather_lds",
 ]
 
 
@@ -40,7 +41,7 @@ PSK_SLAB_COLS, PSK_SLAB_CHUNK = 32736, 512
 class psk_slab(ctypes.Structure):
     """Mirror of the C struct psk_slab (host memory; the pointers are device addresses)."""
     _fields_ = [(n, ctypes.c_int64) for n in ("rows", "cols", "nnz", "nslabs", "nslots", "nchunks", "npairs", "nq")] + \
-               [(n, ctypes.c_int32) for n in ("slab_cols", "chunk", "tile", "reserved")] + \
+               [(n, ctypes.c_int32) for n in ("slab_cols", "chunk", "tile", "value_bytes")] + \
                [(n, ctypes.c_void_p) for n in ("svals", "scol", "chunk_pair", "slab_chunk", "qpos", "qidx", "qtile_row")]
 
 
@@ -92,6 +93,12 @@ def lib() -> ctypes.CDLL:
         L.psk_slab_build_csr.restype = ci
         L.psk_spmv_slab.argtypes = [ctypes.POINTER(psk_slab), p, p, ci, p, sz, p]
         L.psk_spmv_slab.restype = ci
+        L.psk_slab_mem_bytes_f64.argtypes, L.psk_slab_mem_bytes_f64.restype = [i64, i64, i64], sz
+        L.psk_slab_build_workspace_bytes_f64.argtypes, L.psk_slab_build_workspace_bytes_f64.restype = [i64, i64, i64], sz
+        L.psk_slab_build_csr_f64.argtypes = [i64, i64, i64, p, p, p, p, sz, p, sz, ctypes.POINTER(psk_slab), p]
+        L.psk_slab_build_csr_f64.restype = ci
+        L.psk_spmv_slab_f64.argtypes = [ctypes.POINTER(psk_slab), p, p, ci, p, sz, p]
+        L.psk_spmv_slab_f64.restype = ci
         L.psk_cu_trace_set.argtypes, L.psk_cu_trace_set.restype = [p, sz], ci
         L.psk_calibrate_stream_read.argtypes, L.psk_calibrate_stream_read.restype = [p, sz, p, p], ci
         L.psk_calibrate_gather.argtypes, L.psk_calibrate_gather.restype = [p, i64, p, i64, p, p], ci
@@ -456,7 +463,7 @@ class Slab:
     def array(self, name):
         """Device view of one array of the structure (for inspection and tests)."""
         d = self.desc
-        dtype, n = {"svals": (torch.float32, d.nslots), "scol": (torch.int16, d.nslots),
+        dtype, n = {"svals": (torch.float64 if d.value_bytes == 8 else torch.float32, d.nslots), "scol": (torch.int16, d.nslots),
                     "chunk_pair": (torch.int32, d.nchunks + 1), "slab_chunk": (torch.int32, d.nslabs + 1),
                     "qpos": (torch.int32, d.rows + 1), "qidx": (torch.int32, d.nq),
                     "qtile_row": (torch.int32, psk_num_tiles(d.nq, d.tile) + 1)}[name]
@@ -488,6 +495,42 @@ def psk_slab_build_csr(rows, cols, nnz, pos, crd, vals, mem=None, ws=None, strea
                                   ctypes.byref(desc), _stream(stream))
     _check(st, "psk_slab_build_csr")
     return Slab(desc, mem)
+
+
+def psk_slab_mem_bytes_f64(rows, cols, nnz) -> int:
+    return int(lib().psk_slab_mem_bytes_f64(int(rows), int(cols), int(nnz)))
+
+
+def psk_slab_build_workspace_bytes_f64(rows, cols, nnz) -> int:
+    return int(lib().psk_slab_build_workspace_bytes_f64(int(rows), int(cols), int(nnz)))
+
+
+def psk_slab_build_csr_f64(rows, cols, nnz, pos, crd, vals, mem=None, ws=None, stream=None) -> Slab:
+    """The structure with fp64 values (synchronises the stream)."""
+    nm, nw = psk_slab_mem_bytes_f64(rows, cols, nnz), psk_slab_build_workspace_bytes_f64(rows, cols, nnz)
+    if nm == 0 or nw == 0:
+        raise PskError(5, "psk_slab_build_csr_f64 (sizes outside the limits of the slab structure)")
+    if mem is None:
+        mem = _alloc_bytes(nm, pos.device, stream)
+    if ws is None:
+        ws = _alloc_bytes(nw, pos.device, stream)
+    desc = psk_slab()
+    st = lib().psk_slab_build_csr_f64(int(rows), int(cols), int(nnz), _ptr(pos, torch.int32), _ptr(crd, torch.int32),
+                                      _ptr(vals, torch.float64), _ptr(mem), mem.numel(), _ptr(ws), ws.numel(),
+                                      ctypes.byref(desc), _stream(stream))
+    _check(st, "psk_slab_build_csr_f64")
+    return Slab(desc, mem)
+
+
+def psk_spmv_slab_f64(S: Slab, x, y, phases=PSK_PHASE_ALL, ws=None, stream=None):
+    if ws is None:
+        if int(phases) != PSK_PHASE_ALL:
+            raise ValueError("psk_spmv_slab_f64: a partial product needs the workspace (ws=...) of the earlier steps")
+        ws = psk_slab_spmv_workspace(S, x.device if x is not None else y.device, stream)
+    st = lib().psk_spmv_slab_f64(ctypes.byref(S.desc), _ptr(x, torch.float64), _ptr(y, torch.float64), int(phases), _ptr(ws),
+                                 ws.numel(), _stream(stream))
+    _check(st, "psk_spmv_slab_f64")
+    return y
 
 
 def psk_slab_spmv_workspace(S: Slab, device="cuda", stream=None):

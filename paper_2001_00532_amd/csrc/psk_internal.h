@@ -150,13 +150,14 @@ hipError_t launch_spmm_bcsr_main(int32_t bs, int32_t brows, int32_t nblocks, con
 
 // Column-slab hierarchy of a CSR matrix (slab.hip)
 constexpr int32_t kSlabCols = 32736;        // columns per slab: 32 * 1023 floats = 127.9 KB of x in LDS (15-bit in-slab column)
+constexpr int32_t kSlabColsF64 = 12256;     // fp64: 95.75 KB of x next to 64 KB of pair sums (16 waves x 512 doubles)
 constexpr int32_t kSlabChunk = 512;         // slots per chunk (one wave: 8 per lane)
 constexpr int32_t kSlabBuildBlock = 2048;   // CSR positions per block of the bucketing kernels
 constexpr int32_t kSlabMaxSlabs = 8192;     // the bucketing kernels keep one counter per slab in LDS
 constexpr int32_t kSlabTile = 2048;         // position tile of the second step (pairs per workgroup)
-inline int64_t slab_max_slots(int64_t cols, int64_t nnz)
+inline int64_t slab_max_slots(int64_t cols, int64_t nnz, int32_t W)
 {
-    const int64_t S = (cols + kSlabCols - 1) / kSlabCols;
+    const int64_t S = (cols + W - 1) / W;
     const int64_t padded = nnz + S * (kSlabChunk - 1);
     return (padded + kSlabChunk - 1) / kSlabChunk * kSlabChunk;
 }
@@ -165,10 +166,16 @@ struct SlabBuildSpace {
     size_t bytes;
 };
 size_t scan_tmp_ints(int64_t n);
-SlabBuildSpace carve_slab_build(void *base, int64_t rows, int64_t cols, int64_t nnz);
+SlabBuildSpace carve_slab_build(void *base, int64_t rows, int64_t cols, int64_t nnz, int32_t W);
 hipError_t launch_slab_build(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
                              const float *vals, const SlabBuildSpace &w, float *svals, uint16_t *scol,
                              int32_t *chunk_pair, int32_t *slab_chunk, int32_t *qpos, int32_t *qidx, hipStream_t s);
+hipError_t launch_slab_build_f64(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                                 const double *vals, const SlabBuildSpace &w, double *svals, uint16_t *scol,
+                                 int32_t *chunk_pair, int32_t *slab_chunk, int32_t *qpos, int32_t *qidx, hipStream_t s);
+hipError_t launch_slab_pairs_f64(const double *svals, const uint16_t *scol, const int32_t *chunk_pair,
+                                 const int32_t *slab_chunk, const double *x, double *P, int32_t cols, int32_t nslabs,
+                                 int32_t nchunks, int32_t nwg, int32_t *gap, hipStream_t s);
 hipError_t launch_slab_pairs(const float *svals, const uint16_t *scol, const int32_t *chunk_pair,
                              const int32_t *slab_chunk, const float *x, float *P, int32_t cols, int32_t nslabs,
                              int32_t nchunks, int32_t nwg, int32_t *gap, hipStream_t s);
@@ -176,6 +183,8 @@ hipError_t launch_fill_int(int32_t *p, int64_t n, int32_t v, hipStream_t s);
 // y = Q * P with unit values: the tile kernel of the CSR SpMV without the load of vals (tile 2048)
 hipError_t launch_spmv_csr_ones(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
                                 const float *x, float *y, const Workspace &w, hipStream_t s);
+hipError_t launch_spmv_csr_f64_ones(int32_t rows, int32_t nnz, const int32_t *pos, const int32_t *crd, const double *x,
+                                    double *y, const Workspace &w, hipStream_t s);
 
 #ifdef PSK_CU_TRACE
 hipError_t cu_trace_set_spmv_csr(void *buf, unsigned records);

@@ -24,18 +24,25 @@
 
 namespace psk {
 
-constexpr int SLAB_W = kSlabCols;
 constexpr int SLAB_CH = kSlabChunk;
 constexpr int BUILD_BT = kSlabBuildBlock;     // CSR positions per block of the bucketing kernels
 
+// Per value type: columns per slab (what fits into the LDS next to the staging area) and values per 16 bytes.
+typedef double v2d __attribute__((ext_vector_type(2)));
+template <typename T> struct SlabOf;
+template <> struct SlabOf<float>  { static constexpr int W = kSlabCols,    G = 4; typedef v4f V; };
+template <> struct SlabOf<double> { static constexpr int W = kSlabColsF64, G = 2; typedef v2d V; };
+
 // Where the value of slot j is stored.  A lane of the pair kernel owns 8 consecutive slots of a chunk; stored in
-// slot order its two 16-byte loads would each touch every other 16 bytes of a 2 KB range.  Inside each chunk the
-// values are therefore stored as [first four slots of lane 0, of lane 1, ... | second four slots of lane 0, ...],
-// so that both loads are contiguous over the wave (measured on the streams alone: 60 instead of 65 us).
+// slot order its 16-byte loads would each touch every other 16 bytes of the chunk.  Inside each chunk the values
+// are therefore stored in groups of G = 16 bytes / value size: [first G slots of lane 0, of lane 1, ... | next G
+// slots of lane 0, ...], so that every load is contiguous over the wave (measured for fp32 on the streams alone: 60
+// instead of 65 us).
+template <int G>
 __host__ __device__ __forceinline__ int slab_value_index(int j)
 {
     const int o = j & (SLAB_CH - 1), l = o >> 3, k = o & 7;
-    return (j - o) + (k >> 2) * (SLAB_CH / 2) + 4 * l + (k & 3);
+    return (j - o) + (k / G) * (SLAB_CH / 8 * G) + G * l + (k % G);
 }
 
 // ------------------------------------------------------------------ DPP scans over the 64 lanes of a wave
@@ -45,6 +52,13 @@ template <int CTRL, int ROWMASK>
 __device__ __forceinline__ float dpp_f(float v)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROWMASK, 0xF, false));
+}
+template <int CTRL, int ROWMASK>
+__device__ __forceinline__ double dpp_f(double v)
+{
+    const long long b = __builtin_bit_cast(long long, v);
+    const unsigned lo = (unsigned)dpp_i<CTRL, ROWMASK>((int)(unsigned)b), hi = (unsigned)dpp_i<CTRL, ROWMASK>((int)(b >> 32));
+    return __builtin_bit_cast(double, (long long)(((unsigned long long)hi << 32) | lo));
 }
 // row_shr 1, 2, 4, 8 scan each row of 16 lanes; row_bcast15 hands lane 15 of rows 0 and 2 to rows 1 and 3,
 // row_bcast31 hands lane 31 to rows 2 and 3.  Lanes without a source receive 0.
@@ -59,11 +73,12 @@ __device__ __forceinline__ int wave_scan_add(int v)
     return v;
 }
 // Inclusive segmented sum: a lane with f != 0 starts afresh (takes nothing from the lanes below it).
-__device__ __forceinline__ float wave_segscan(float v, int f)
+template <typename T>
+__device__ __forceinline__ T wave_segscan(T v, int f)
 {
 #define PSK_SEG_STEP(CTRL, MASK)                       \
     {                                                  \
-        const float pv = dpp_f<CTRL, MASK>(v);         \
+        const T pv = dpp_f<CTRL, MASK>(v);             \
         const int pf = dpp_i<CTRL, MASK>(f);           \
         v = f ? v : v + pv;                            \
         f |= pf;                                       \
@@ -84,22 +99,27 @@ __device__ __forceinline__ float wave_segscan(float v, int f)
 // it) when the slot ends a pair, to a dummy word otherwise; a segmented DPP scan then hands each lane the
 // open sum of the lanes below it, which is added to the lane's first pair.  The chunk's pair sums, now
 // compact in LDS, leave with full-width coalesced stores to P[chunk_pair[c] ...].
-// LDS: 127.9 KB of x + 2 KB of pair sums per wave + the dummy words = the CU's 160 KB.
-__global__ __launch_bounds__(1024) void k_slab_pairs(const float *__restrict__ svals,
+// LDS: 127.9 KB of x + 2 KB of pair sums per wave + the dummy words = the CU's 160 KB (fp64: 95.75 KB of x, 12 256
+// columns, + 4 KB of pair sums per wave).
+template <typename T>
+__global__ __launch_bounds__(1024) void k_slab_pairs(const T *__restrict__ svals,
                                                      const unsigned short *__restrict__ scol,
                                                      const int *__restrict__ chunk_pair,
                                                      const int *__restrict__ slab_chunk,
-                                                     const float *__restrict__ x, float *__restrict__ P, int cols,
+                                                     const T *__restrict__ x, T *__restrict__ P, int cols,
                                                      int nslabs, int nchunks, int cpw, int *__restrict__ gap)
 {
     constexpr int WAVES = 16;
+    constexpr int W = SlabOf<T>::W, G = SlabOf<T>::G, NV = 8 / G;      // NV 16-byte loads of values per lane
+    typedef typename SlabOf<T>::V V;
     // the run list of the second step starts empty (that step's tiles append to it, the fix-up consumes it)
     if (blockIdx.x == 0 && threadIdx.x == 0 && gap) { gap[0] = 0; gap[1] = 0; }
-    __shared__ float xs[SLAB_W];
-    __shared__ float stage[WAVES * SLAB_CH + 32];     // + one dummy word per LDS bank
+    __shared__ T xs[W];
+    __shared__ T stage[WAVES * SLAB_CH + 32];         // + one dummy word per LDS bank
+    static_assert(sizeof(T) * (W + WAVES * SLAB_CH + 32) <= 163840, "the window and the staging area fill the CU's LDS");
     const int tid = threadIdx.x, lane = tid & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
-    float *st = stage + wave * SLAB_CH;
+    T *st = stage + wave * SLAB_CH;
     const int dummy = (WAVES - wave) * SLAB_CH + (lane & 31);      // index, relative to st, of a word nobody reads
     int c0 = blockIdx.x * cpw;
     const int c1 = min(c0 + cpw, nchunks);
@@ -118,25 +138,28 @@ __global__ __launch_bounds__(1024) void k_slab_pairs(const float *__restrict__ s
         while (slab_chunk[s + 1] <= c0) ++s;            // skips empty slabs; c0 < nchunks = slab_chunk[nslabs]
         const int ce = min(c1, slab_chunk[s + 1]);
         __syncthreads();                                  // the previous slab's window is no longer read
-        const long long xb = (long long)s * SLAB_W;
-        const int wlen = (int)min((long long)SLAB_W, (long long)cols - xb);
+        const long long xb = (long long)s * W;
+        const int wlen = (int)min((long long)W, (long long)cols - xb);
         const bool x16 = (reinterpret_cast<uintptr_t>(x + xb) & 15) == 0;
-        for (int i = tid * 4; i < wlen; i += 4096) {
-            if (x16 && i + 4 <= wlen) {
-                *reinterpret_cast<v4f *>(&xs[i]) = *reinterpret_cast<const v4f *>(x + xb + i);
+        for (int i = tid * G; i < wlen; i += 1024 * G) {
+            if (x16 && i + G <= wlen) {
+                *reinterpret_cast<V *>(&xs[i]) = *reinterpret_cast<const V *>(x + xb + i);
             } else {
-                for (int j = i; j < i + 4 && j < wlen; ++j) xs[j] = x[xb + j];
+                for (int j = i; j < i + G && j < wlen; ++j) xs[j] = x[xb + j];
             }
         }
         __syncthreads();
         int c = c0 + wave;
-        v4f va = {0, 0, 0, 0}, vb = {0, 0, 0, 0};
+        V va[NV];
+#pragma unroll
+        for (int g = 0; g < NV; ++g) va[g] = V{};
         v4i cc = {0, 0, 0, 0};
         int pb = 0;
         auto issue = [&](int ci) {
             const long long b = (long long)ci * SLAB_CH;
-            va = ld_stream(reinterpret_cast<const v4f *>(svals + b + lane * 4));                    // slots 8*lane .. +3
-            vb = ld_stream(reinterpret_cast<const v4f *>(svals + b + SLAB_CH / 2 + lane * 4));      // slots 8*lane+4 .. +7
+#pragma unroll
+            for (int g = 0; g < NV; ++g)                                       // slots 8*lane + g*G .. + G-1
+                va[g] = ld_stream(reinterpret_cast<const V *>(svals + b + g * (SLAB_CH / 8 * G) + lane * G));
             cc = ld_stream(reinterpret_cast<const v4i *>(scol + b + lane * 8));
             // lanes 0 and 1 fetch the chunk's first pair and the next chunk's: a vector load on purpose, a scalar
             // load would share its counter with the LDS reads and make each of them wait for its round trip
@@ -144,7 +167,9 @@ __global__ __launch_bounds__(1024) void k_slab_pairs(const float *__restrict__ s
         };
         if (c < ce) issue(c);
         for (; c < ce; c += WAVES) {
-            const v4f a0 = va, a1 = vb;
+            T v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = va[j / G][j % G];
             const v4i q = cc;
             const int pbase = rl(pb, 0), np = rl(pb, 1) - pbase;
             if (c + WAVES < ce) issue(c + WAVES);
@@ -153,8 +178,7 @@ __global__ __launch_bounds__(1024) void k_slab_pairs(const float *__restrict__ s
             const unsigned ends = ((w0 >> 15) & 1u) | ((w0 >> 30) & 2u) | ((w1 >> 13) & 4u) | ((w1 >> 28) & 8u) |
                                   ((w2 >> 11) & 16u) | ((w2 >> 26) & 32u) | ((w3 >> 9) & 64u) | ((w3 >> 24) & 128u);
             const unsigned w[4] = {w0, w1, w2, w3};
-            const float v[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-            float p[8];
+            T p[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const unsigned h = (j & 1) ? (w[j >> 1] >> 16) : w[j >> 1];
@@ -162,19 +186,19 @@ __global__ __launch_bounds__(1024) void k_slab_pairs(const float *__restrict__ s
             }
             const int cnt = __popc(ends);
             const int first = wave_scan_add(cnt) - cnt;         // place of this lane's first pair end in the chunk
-            float run = 0.0f;
+            T run = 0;
             int place = first;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const bool e = (ends >> j) & 1u;
                 run += p[j];
                 st[e ? place : dummy] = run;
-                run = e ? 0.0f : run;
+                run = e ? T(0) : run;
                 place += e ? 1 : 0;
             }
             // `run` is the lane's open sum; the lane below hands over the open sum of all lanes below it
-            const float open = wave_segscan(run, cnt ? 1 : 0);
-            const float carry = __shfl_up(open, 1, WAVE);
+            const T open = wave_segscan<T>(run, cnt ? 1 : 0);
+            const T carry = __shfl_up(open, 1, WAVE);
             if (cnt && lane) st[first] += carry;                // head + carry (a chunk's first slot starts a pair)
             for (int k = lane; k < np; k += WAVE) P[pbase + k] = st[k];
         }
@@ -183,17 +207,32 @@ __global__ __launch_bounds__(1024) void k_slab_pairs(const float *__restrict__ s
     }
 }
 
-hipError_t launch_slab_pairs(const float *svals, const uint16_t *scol, const int32_t *chunk_pair,
-                             const int32_t *slab_chunk, const float *x, float *P, int32_t cols, int32_t nslabs,
-                             int32_t nchunks, int32_t nwg, int32_t *gap, hipStream_t s)
+template <typename T>
+static hipError_t launch_slab_pairs_t(const T *svals, const uint16_t *scol, const int32_t *chunk_pair,
+                                      const int32_t *slab_chunk, const T *x, T *P, int32_t cols, int32_t nslabs,
+                                      int32_t nchunks, int32_t nwg, int32_t *gap, hipStream_t s)
 {
     if (nchunks <= 0) return hipSuccess;
     if (nwg < 1) nwg = 1;
     const int cpw = (nchunks + nwg - 1) / nwg;
     const int grid = (nchunks + cpw - 1) / cpw;
-    PSK_LAUNCH(k_slab_pairs, dim3(grid), dim3(1024), 0, s, svals, scol, chunk_pair, slab_chunk, x, P, cols, nslabs,
+    PSK_LAUNCH(k_slab_pairs<T>, dim3(grid), dim3(1024), 0, s, svals, scol, chunk_pair, slab_chunk, x, P, cols, nslabs,
                nchunks, cpw, gap);
     return take_launch_status();
+}
+
+hipError_t launch_slab_pairs(const float *svals, const uint16_t *scol, const int32_t *chunk_pair,
+                             const int32_t *slab_chunk, const float *x, float *P, int32_t cols, int32_t nslabs,
+                             int32_t nchunks, int32_t nwg, int32_t *gap, hipStream_t s)
+{
+    return launch_slab_pairs_t<float>(svals, scol, chunk_pair, slab_chunk, x, P, cols, nslabs, nchunks, nwg, gap, s);
+}
+
+hipError_t launch_slab_pairs_f64(const double *svals, const uint16_t *scol, const int32_t *chunk_pair,
+                                 const int32_t *slab_chunk, const double *x, double *P, int32_t cols, int32_t nslabs,
+                                 int32_t nchunks, int32_t nwg, int32_t *gap, hipStream_t s)
+{
+    return launch_slab_pairs_t<double>(svals, scol, chunk_pair, slab_chunk, x, P, cols, nslabs, nchunks, nwg, gap, s);
 }
 
 // ------------------------------------------------------------------ prefix sums over int32 arrays
@@ -277,7 +316,7 @@ static void launch_scan(const int32_t *in, int32_t *out, int64_t n, int32_t *bsu
 
 // ------------------------------------------------------------------ the analysis step: CSR -> slab hierarchy
 // H[s * nblk + b] = number of positions of block b (BUILD_BT consecutive CSR positions) that fall into slab s.
-__global__ __launch_bounds__(256) void k_slab_hist(int nnz, const int *__restrict__ crd, int nslabs, int nblk,
+__global__ __launch_bounds__(256) void k_slab_hist(int nnz, const int *__restrict__ crd, int W, int nslabs, int nblk,
                                                    int *__restrict__ H)
 {
     extern __shared__ int hist[];
@@ -286,7 +325,7 @@ __global__ __launch_bounds__(256) void k_slab_hist(int nnz, const int *__restric
     const int b = blockIdx.x;
     const long long p0 = (long long)b * BUILD_BT;
     for (int i = threadIdx.x; i < BUILD_BT; i += 256)
-        if (p0 + i < nnz) atomicAdd(&hist[crd[p0 + i] / SLAB_W], 1);
+        if (p0 + i < nnz) atomicAdd(&hist[crd[p0 + i] / W], 1);
     __syncthreads();
     for (int s = threadIdx.x; s < nslabs; s += 256) H[(long long)s * nblk + b] = hist[s];
 }
@@ -318,15 +357,16 @@ __global__ __launch_bounds__(256) void k_slab_bases(const int *__restrict__ E, i
 }
 
 // The pad slots of slab s (fewer than a chunk): value 0, column 0, no row, no source position.
+template <typename T>
 __global__ __launch_bounds__(64) void k_slab_pads(const int *__restrict__ E, int nblk, const int *__restrict__ slab_chunk,
-                                                  float *__restrict__ svals, unsigned short *__restrict__ scol,
+                                                  T *__restrict__ svals, unsigned short *__restrict__ scol,
                                                   int *__restrict__ srow, int *__restrict__ src)
 {
     const int s = blockIdx.x;
     const int cnt = E[(long long)(s + 1) * nblk] - E[(long long)s * nblk];
     const long long lo = (long long)slab_chunk[s] * SLAB_CH + cnt, hi = (long long)slab_chunk[s + 1] * SLAB_CH;
     for (long long j = lo + threadIdx.x; j < hi; j += 64) {
-        svals[slab_value_index((int)j)] = 0.0f;
+        svals[slab_value_index<SlabOf<T>::G>((int)j)] = T(0);
         scol[j] = 0;
         srow[j] = -1;
         src[j] = -1;
@@ -338,14 +378,16 @@ __global__ __launch_bounds__(64) void k_slab_pads(const int *__restrict__ E, int
 // lane number (ballot), so the order of the CSR is kept inside every slab.  The row of a position is the
 // largest r with pos[r] <= p, searched between the rows of the block's first and last position
 // (tile_row = the position cut of pos with tiles of BUILD_BT).
+template <typename T>
 __global__ __launch_bounds__(64) void k_slab_scatter(int rows, int nnz, const int *__restrict__ pos,
-                                                     const int *__restrict__ crd, const float *__restrict__ vals,
+                                                     const int *__restrict__ crd, const T *__restrict__ vals,
                                                      const int *__restrict__ tile_row, const int *__restrict__ E,
                                                      const int *__restrict__ slab_chunk, int nslabs, int nblk,
-                                                     float *__restrict__ svals, unsigned short *__restrict__ scol,
+                                                     T *__restrict__ svals, unsigned short *__restrict__ scol,
                                                      int *__restrict__ srow, int *__restrict__ src)
 {
     extern __shared__ int off[];
+    constexpr int W = SlabOf<T>::W;
     const int b = blockIdx.x, lane = threadIdx.x;
     for (int s = lane; s < nslabs; s += WAVE)
         off[s] = slab_chunk[s] * SLAB_CH + (E[(long long)s * nblk + b] - E[(long long)s * nblk]);
@@ -357,11 +399,11 @@ __global__ __launch_bounds__(64) void k_slab_scatter(int rows, int nnz, const in
         const bool valid = pl < nnz;
         const int p = valid ? (int)pl : 0;
         int c = 0, s = -1, r = 0;
-        float v = 0.0f;
+        T v = 0;
         if (valid) {
             c = crd[p];
             v = vals[p];
-            s = c / SLAB_W;
+            s = c / W;
             int lo = r_lo, hi = r_hi;
             while (lo < hi) {
                 const int mid = lo + ((hi - lo + 1) >> 1);
@@ -382,8 +424,8 @@ __global__ __launch_bounds__(64) void k_slab_scatter(int rows, int nnz, const in
             todo &= ~same;
         }
         if (valid) {
-            svals[slab_value_index(dst)] = v;
-            scol[dst] = (unsigned short)(c - s * SLAB_W);
+            svals[slab_value_index<SlabOf<T>::G>(dst)] = v;
+            scol[dst] = (unsigned short)(c - s * W);
             srow[dst] = r;
             src[dst] = p;
         }
@@ -463,13 +505,13 @@ hipError_t launch_fill_int(int32_t *p, int64_t n, int32_t v, hipStream_t s)
     return take_launch_status();
 }
 
-SlabBuildSpace carve_slab_build(void *base, int64_t rows, int64_t cols, int64_t nnz)
+SlabBuildSpace carve_slab_build(void *base, int64_t rows, int64_t cols, int64_t nnz, int32_t W)
 {
     (void)rows;
     SlabBuildSpace w;
-    const int64_t S = (cols + SLAB_W - 1) / SLAB_W;
+    const int64_t S = (cols + W - 1) / W;
     const int64_t nblk = (nnz + BUILD_BT - 1) / BUILD_BT;
-    const int64_t nmax = slab_max_slots(cols, nnz);
+    const int64_t nmax = slab_max_slots(cols, nnz, W);
     char *p = static_cast<char *>(base);
     size_t o = 0;
     auto take = [&](size_t bytes) { char *q = p + o; o += align256(bytes); return q; };
@@ -490,23 +532,26 @@ SlabBuildSpace carve_slab_build(void *base, int64_t rows, int64_t cols, int64_t 
 }
 
 // Enqueues the whole analysis on `s`.  When it has run, meta[0..2] = {slots, pairs, listed pairs}.
-hipError_t launch_slab_build(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
-                             const float *vals, const SlabBuildSpace &w, float *svals, uint16_t *scol,
-                             int32_t *chunk_pair, int32_t *slab_chunk, int32_t *qpos, int32_t *qidx, hipStream_t s)
+template <typename T>
+static hipError_t launch_slab_build_t(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                                      const T *vals, const SlabBuildSpace &w, T *svals, uint16_t *scol,
+                                      int32_t *chunk_pair, int32_t *slab_chunk, int32_t *qpos, int32_t *qidx,
+                                      hipStream_t s)
 {
-    const int S = (int)(((int64_t)cols + SLAB_W - 1) / SLAB_W);
+    constexpr int W = SlabOf<T>::W;
+    const int S = (int)(((int64_t)cols + W - 1) / W);
     const int nblk = (int)(((int64_t)nnz + BUILD_BT - 1) / BUILD_BT);
-    const int64_t nmax = slab_max_slots(cols, nnz);
+    const int64_t nmax = slab_max_slots(cols, nnz, W);
     unsigned short *scol_d = reinterpret_cast<unsigned short *>(scol);
     hipError_t e = launch_partition(rows, nnz, pos, BUILD_BT, 0, w.tile_row, s);
     if (e != hipSuccess) return e;
     const size_t lds = (size_t)S * 4;
-    PSK_LAUNCH(k_slab_hist, dim3(nblk), dim3(256), (unsigned)lds, s, nnz, crd, S, nblk, w.H);
+    PSK_LAUNCH(k_slab_hist, dim3(nblk), dim3(256), (unsigned)lds, s, nnz, crd, W, S, nblk, w.H);
     PSK_LAUNCH(k_fill_int, dim3(1), dim3(64), 0, s, w.H + (long long)S * nblk, 1ll, 0);      // the scan's total slot
     launch_scan(w.H, w.H, (int64_t)S * nblk + 1, w.scan_tmp, false, s);
     PSK_LAUNCH(k_slab_bases, dim3(1), dim3(256), 0, s, w.H, S, nblk, slab_chunk, w.meta);
-    PSK_LAUNCH(k_slab_pads, dim3(S), dim3(64), 0, s, w.H, nblk, slab_chunk, svals, scol_d, w.srow, w.src);
-    PSK_LAUNCH(k_slab_scatter, dim3(nblk), dim3(64), (unsigned)lds, s, rows, nnz, pos, crd, vals, w.tile_row, w.H,
+    PSK_LAUNCH(k_slab_pads<T>, dim3(S), dim3(64), 0, s, w.H, nblk, slab_chunk, svals, scol_d, w.srow, w.src);
+    PSK_LAUNCH(k_slab_scatter<T>, dim3(nblk), dim3(64), (unsigned)lds, s, rows, nnz, pos, crd, vals, w.tile_row, w.H,
                slab_chunk, S, nblk, svals, scol_d, w.srow, w.src);
     PSK_LAUNCH(k_slab_starts, dim3((unsigned)((nmax + 1 + 255) / 256)), dim3(256), 0, s, w.meta, w.srow,
                (long long)(nmax + 1), w.F);
@@ -523,6 +568,20 @@ hipError_t launch_slab_build(int32_t rows, int32_t cols, int32_t nnz, const int3
     PSK_LAUNCH(k_slab_rows, dim3((unsigned)((span + 255) / 256)), dim3(256), 0, s, rows, nnz, pos, w.mark, w.pair_at,
                qpos, qidx, w.meta);
     return take_launch_status();
+}
+
+hipError_t launch_slab_build(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                             const float *vals, const SlabBuildSpace &w, float *svals, uint16_t *scol,
+                             int32_t *chunk_pair, int32_t *slab_chunk, int32_t *qpos, int32_t *qidx, hipStream_t s)
+{
+    return launch_slab_build_t<float>(rows, cols, nnz, pos, crd, vals, w, svals, scol, chunk_pair, slab_chunk, qpos, qidx, s);
+}
+
+hipError_t launch_slab_build_f64(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
+                                 const double *vals, const SlabBuildSpace &w, double *svals, uint16_t *scol,
+                                 int32_t *chunk_pair, int32_t *slab_chunk, int32_t *qpos, int32_t *qidx, hipStream_t s)
+{
+    return launch_slab_build_t<double>(rows, cols, nnz, pos, crd, vals, w, svals, scol, chunk_pair, slab_chunk, qpos, qidx, s);
 }
 
 #ifdef PSK_CU_TRACE

@@ -22,7 +22,8 @@ __device__ __forceinline__ double wave_sum_f64(double v)
 // WIN: a column pass as in the fp32 kernel: only columns in [clo, chi) contribute, accum adds to what the
 // earlier passes stored; the first pass records the tile's column range, later passes skip tiles outside
 // their window.
-template <int THREADS, int NPT, bool VEC, bool WIN>
+// ONES: every stored value is 1 and `vals` is not read (the row sums over the pair array of the slab path).
+template <int THREADS, int NPT, bool VEC, bool WIN, bool ONES = false>
 __global__ __launch_bounds__(THREADS) void k_spmv_pos_f64(int rows, int nnz, const int *__restrict__ pos,
                                                           const int *__restrict__ crd,
                                                           const double *__restrict__ vals,
@@ -74,8 +75,11 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos_f64(int rows, int nnz, con
             for (int g = 0; g < NPT / 4; ++g) {
                 const int off = t0 + (g * THREADS + tid) * 4;
                 const v4i cv = ld_stream(reinterpret_cast<const v4i *>(crd + off));
-                const v2d va = ld_stream(reinterpret_cast<const v2d *>(vals + off));
-                const v2d vb = ld_stream(reinterpret_cast<const v2d *>(vals + off + 2));
+                v2d va = {1.0, 1.0}, vb = {1.0, 1.0};
+                if (!ONES) {
+                    va = ld_stream(reinterpret_cast<const v2d *>(vals + off));
+                    vb = ld_stream(reinterpret_cast<const v2d *>(vals + off + 2));
+                }
                 c[4 * g] = cv.x; c[4 * g + 1] = cv.y; c[4 * g + 2] = cv.z; c[4 * g + 3] = cv.w;
                 v[4 * g] = va.x; v[4 * g + 1] = va.y; v[4 * g + 2] = vb.x; v[4 * g + 3] = vb.y;
             }
@@ -83,7 +87,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos_f64(int rows, int nnz, con
 #pragma unroll
             for (int g = 0; g < NPT; ++g) {
                 c[g] = ld_stream(crd + t0 + g * THREADS + tid);
-                v[g] = ld_stream(vals + t0 + g * THREADS + tid);
+                v[g] = ONES ? 1.0 : ld_stream(vals + t0 + g * THREADS + tid);
             }
         }
         double xg[NPT];
@@ -114,7 +118,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos_f64(int rows, int nnz, con
                 const int c = crd[t0 + i];
                 cmin = min(cmin, c);
                 cmax = max(cmax, c);
-                if (!WIN || (c >= clo && c < chi)) pr = vals[t0 + i] * x[c];
+                if (!WIN || (c >= clo && c < chi)) pr = ONES ? x[c] : vals[t0 + i] * x[c];
             }
             prod[g] = pr;
         }
@@ -231,6 +235,24 @@ hipError_t launch_spmv_csr_f64_main(int32_t rows, int32_t cols, int32_t nnz, con
             default: return hipErrorInvalidValue;
         }
     }
+    return take_launch_status();
+}
+
+// y = Q * P with unit values over (pos, crd) = the row lists of the slab structure; tile 2048
+hipError_t launch_spmv_csr_f64_ones(int32_t rows, int32_t nnz, const int32_t *pos, const int32_t *crd, const double *x,
+                                    double *y, const Workspace &w, hipStream_t s)
+{
+    const int ntiles = (int)(((int64_t)nnz + 2047) / 2048);
+    if (ntiles == 0) return hipSuccess;
+    const int grid = xcd_grid(ntiles);
+    const double *none = nullptr;
+    double *cv = reinterpret_cast<double *>(w.carry_val);
+    if ((reinterpret_cast<uintptr_t>(crd) & 15) == 0)
+        PSK_LAUNCH((k_spmv_pos_f64<256, 8, true, false, true>), dim3(grid), dim3(256), 0, s, rows, nnz, pos, crd, none, x, y,
+                   w.tile_row, w.carry_row, cv, ntiles, 0, 0x7fffffff, 0, w.tile_cols);
+    else
+        PSK_LAUNCH((k_spmv_pos_f64<256, 8, false, false, true>), dim3(grid), dim3(256), 0, s, rows, nnz, pos, crd, none, x,
+                   y, w.tile_row, w.carry_row, cv, ntiles, 0, 0x7fffffff, 0, w.tile_cols);
     return take_launch_status();
 }
 
