@@ -586,6 +586,9 @@ def main():
                 col_passes = int(min(4, -(-(8 * A.cols) // (6 << 20))))
     path = "csr"
     analysis = None
+    if kind == "csr_spmv" and f64:
+        suggested64 = psk.psk_analyze_csr(A.rows, A.cols, A.nnz, sets[0]["pos"], sets[0]["crd"], stream=stream)
+        path = args.path if args.path != "auto" else ("slab" if suggested64 > 1 and not args.col_passes else "csr")
     if kind == "csr_spmv" and not f64:
         suggested = psk.psk_analyze_csr(A.rows, A.cols, A.nnz, sets[0]["pos"], sets[0]["crd"], stream=stream)
         path = args.path if args.path != "auto" else ("slab" if suggested > 1 and not args.col_passes else "csr")
@@ -602,20 +605,23 @@ def main():
         for i, s in enumerate(sets):
             torch.cuda.synchronize()
             t_b = time.perf_counter()
-            s["slab"] = psk.psk_slab_build_csr(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], stream=stream)
+            build = psk.psk_slab_build_csr_f64 if f64 else psk.psk_slab_build_csr
+            s["slab"] = build(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], stream=stream)
             torch.cuda.synchronize()
             build_ms.append((time.perf_counter() - t_b) * 1e3)
             s["slab_ws"] = psk.psk_slab_spmv_workspace(s["slab"], dev)
         d0 = sets[0]["slab"].desc
-        analysis = {"call": "psk_slab_build_csr", "ms_median": round(statistics.median(build_ms), 3),
+        analysis = {"call": "psk_slab_build_csr_f64" if f64 else "psk_slab_build_csr", "ms_median": round(statistics.median(build_ms), 3),
                     "ms_first": round(build_ms[0], 3), "builds": len(build_ms),
                     "slabs": int(d0.nslabs), "slots": int(d0.nslots), "pairs": int(d0.npairs),
-                    "listed_pairs": int(d0.nq), "structure_bytes": int(6 * d0.nslots + 4 * (d0.nchunks + 1) + 4 * (d0.nslabs + 1)
+                    "listed_pairs": int(d0.nq), "structure_bytes": int((2 + d0.value_bytes) * d0.nslots + 4 * (d0.nchunks + 1) + 4 * (d0.nslabs + 1)
                                                                    + 4 * (A.rows + 1) + 4 * d0.nq)}
         tile, col_passes = int(d0.tile), 1
 
     def step(s, phases=psk.PSK_PHASE_ALL):
-        if f64:
+        if f64 and path == "slab":
+            psk.psk_spmv_slab_f64(s["slab"], s["dense"], s["out"], phases=phases, ws=s["slab_ws"], stream=stream)
+        elif f64:
             psk.psk_spmv_csr_f64(A.rows, A.cols, A.nnz, s["pos"], s["crd"], s["vals"], s["dense"], s["out"], tile=tile,
                                  col_passes=col_passes, phases=phases, ws=s["ws"], stream=stream)
         elif kind == "csr_spmv" and path == "slab":
@@ -697,7 +703,7 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": "%s: %s%s, %d x %d%s, nnz %d (max row %d, mean %.2f), tile %d, col_passes %d, k %d, %d operand copies rotated"
-                        % (args.workload, kind, " over the column-slab copy of A (built once by psk_slab_build_csr)" if path == "slab" else "",
+                        % (args.workload, kind, " over the column-slab copy of A (built once by %s)" % analysis["call"] if path == "slab" else "",
                            A.rows * A.bs, A.cols * A.bs, " in %dx%d blocks" % (A.bs, A.bs) if A.bs > 1 else "",
                            A.nnz * A.bs * A.bs, int(L.max()) if L.size else 0, float(L.mean()) if L.size else 0.0,
                            tile, col_passes, k, copies),
@@ -719,7 +725,8 @@ def main():
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "k_spmv_pos_f64" if f64 else ("k_slab_pairs + k_spmv_pos<256,8,*,6>" if path == "slab" else
+            "kernel": ("k_slab_pairs<double> + k_spmv_pos_f64<256,8,*,unit values>" if path == "slab" else "k_spmv_pos_f64") if f64
+                      else ("k_slab_pairs + k_spmv_pos<256,8,*,6>" if path == "slab" else
                        {"csr_spmv": "k_spmv_pos", "csr_spmm": "k_spmm_pos<1,*>", "bcsr_spmv": "k_spmv_bcsr4",
                         "bcsr_spmm": "k_spmm_pos<4,*>"}[kind]),
             "achieved": round(achieved, 2),
@@ -765,8 +772,9 @@ def main():
             s_ = sets[i % copies]
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
-            psk.psk_spmv_csr(A.rows, A.cols, A.nnz, s_["pos"], s_["crd"], s_["vals"], s_["dense"], s_["out"], tile=csr_tile,
-                             col_passes=csr_passes, ws=s_["ws"], stream=stream)
+            csr_call = psk.psk_spmv_csr_f64 if f64 else psk.psk_spmv_csr
+            csr_call(A.rows, A.cols, A.nnz, s_["pos"], s_["crd"], s_["vals"], s_["dense"], s_["out"], tile=csr_tile,
+                     col_passes=csr_passes, ws=s_["ws"], stream=stream)
             e1.record(stream)
             e1.synchronize()
             if i >= 8:
@@ -776,7 +784,7 @@ def main():
         analysis["repaid_after_products"] = (int(np.ceil(analysis["ms_median"] * 1e3 / (csr_us - slab_us)))
                                              if csr_us > slab_us else None)
         rec["analysis"] = analysis
-        rec["csr_path"] = {"call": "psk_spmv_csr", "tile": csr_tile, "col_passes": csr_passes,
+        rec["csr_path"] = {"call": "psk_spmv_csr_f64" if f64 else "psk_spmv_csr", "tile": csr_tile, "col_passes": csr_passes,
                            "us_median": round(csr_us, 2), "gflops": round(fl / (csr_us * 1e-6) / 1e9, 3),
                            "frac_of_hbm_peak_whole_call": round(comp_bytes / (csr_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
 

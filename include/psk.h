@@ -405,7 +405,7 @@ int psk_spmm_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t
  * The fp64 row-sum kernel clears rows without entries one by one (no run list for long runs of empty rows).
  */
 #define PSK_SLAB_COLS 32736
-#define PSK_SLAB_COLS_F64 12256
+#define PSK_SLAB_COLS_F64 16352
 #define PSK_SLAB_CHUNK 512
 typedef struct psk_slab {
     int64_t rows, cols, nnz;

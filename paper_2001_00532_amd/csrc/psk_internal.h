@@ -150,7 +150,8 @@ hipError_t launch_spmm_bcsr_main(int32_t bs, int32_t brows, int32_t nblocks, con
 
 // Column-slab hierarchy of a CSR matrix (slab.hip)
 constexpr int32_t kSlabCols = 32736;        // columns per slab: 32 * 1023 floats = 127.9 KB of x in LDS (15-bit in-slab column)
-constexpr int32_t kSlabColsF64 = 12256;     // fp64: 95.75 KB of x next to 64 KB of pair sums (16 waves x 512 doubles)
+constexpr int32_t kSlabColsF64 = 16352;     // fp64: 127.75 KB of x next to 32 KB of pair sums (8 waves x 512 doubles)
+constexpr int32_t kSlabWavesF64 = 8;
 constexpr int32_t kSlabChunk = 512;         // slots per chunk (one wave: 8 per lane)
 constexpr int32_t kSlabBuildBlock = 2048;   // CSR positions per block of the bucketing kernels
 constexpr int32_t kSlabMaxSlabs = 8192;     // the bucketing kernels keep one counter per slab in LDS

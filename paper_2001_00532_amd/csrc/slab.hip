@@ -30,8 +30,8 @@ constexpr int BUILD_BT = kSlabBuildBlock;     // CSR positions per block of the 
 // Per value type: columns per slab (what fits into the LDS next to the staging area) and values per 16 bytes.
 typedef double v2d __attribute__((ext_vector_type(2)));
 template <typename T> struct SlabOf;
-template <> struct SlabOf<float>  { static constexpr int W = kSlabCols,    G = 4; typedef v4f V; };
-template <> struct SlabOf<double> { static constexpr int W = kSlabColsF64, G = 2; typedef v2d V; };
+template <> struct SlabOf<float>  { static constexpr int W = kSlabCols,    G = 4, WAVES = 16; typedef v4f V; };
+template <> struct SlabOf<double> { static constexpr int W = kSlabColsF64, G = 2, WAVES = kSlabWavesF64; typedef v2d V; };
 
 // Where the value of slot j is stored.  A lane of the pair kernel owns 8 consecutive slots of a chunk; stored in
 // slot order its 16-byte loads would each touch every other 16 bytes of the chunk.  Inside each chunk the values
@@ -92,24 +92,25 @@ __device__ __forceinline__ T wave_segscan(T v, int f)
 // ------------------------------------------------------------------ step 1 of the product
 // Persistent workgroups: workgroup b owns the chunks [b*cpw, (b+1)*cpw) (the position space DIVIDED into
 // equal pieces, Section 5), walks them slab by slab, loads the slab's part of x into LDS once and lets its
-// 16 waves take the chunks of that slab round-robin.  A lane owns 8 consecutive slots (two 16-byte loads of
+// waves (16; 8 for fp64) take the chunks of that slab round-robin.  A lane owns 8 consecutive slots (two 16-byte loads of
 // values, one of columns); the next chunk's loads are issued before the current one is processed.
 // Inside a chunk (no branches): the lane walks its 8 slots with a running sum that restarts after a pair
 // end and writes every running sum to LDS -- to the pair's place in the chunk (number of pair ends before
 // it) when the slot ends a pair, to a dummy word otherwise; a segmented DPP scan then hands each lane the
 // open sum of the lanes below it, which is added to the lane's first pair.  The chunk's pair sums, now
 // compact in LDS, leave with full-width coalesced stores to P[chunk_pair[c] ...].
-// LDS: 127.9 KB of x + 2 KB of pair sums per wave + the dummy words = the CU's 160 KB (fp64: 95.75 KB of x, 12 256
-// columns, + 4 KB of pair sums per wave).
+// LDS: 127.9 KB of x + 2 KB of pair sums per wave + the dummy words = the CU's 160 KB (fp64: 8 waves, 127.75 KB of
+// x = 16 352 columns, + 4 KB of pair sums per wave; 16 waves with 12 256 columns measured the same, 191.5 against
+// 190.3 us on the power-law configuration, and make more pairs).
 template <typename T>
-__global__ __launch_bounds__(1024) void k_slab_pairs(const T *__restrict__ svals,
+__global__ __launch_bounds__(SlabOf<T>::WAVES * WAVE) void k_slab_pairs(const T *__restrict__ svals,
                                                      const unsigned short *__restrict__ scol,
                                                      const int *__restrict__ chunk_pair,
                                                      const int *__restrict__ slab_chunk,
                                                      const T *__restrict__ x, T *__restrict__ P, int cols,
                                                      int nslabs, int nchunks, int cpw, int *__restrict__ gap)
 {
-    constexpr int WAVES = 16;
+    constexpr int WAVES = SlabOf<T>::WAVES;
     constexpr int W = SlabOf<T>::W, G = SlabOf<T>::G, NV = 8 / G;      // NV 16-byte loads of values per lane
     typedef typename SlabOf<T>::V V;
     // the run list of the second step starts empty (that step's tiles append to it, the fix-up consumes it)
@@ -141,7 +142,7 @@ __global__ __launch_bounds__(1024) void k_slab_pairs(const T *__restrict__ svals
         const long long xb = (long long)s * W;
         const int wlen = (int)min((long long)W, (long long)cols - xb);
         const bool x16 = (reinterpret_cast<uintptr_t>(x + xb) & 15) == 0;
-        for (int i = tid * G; i < wlen; i += 1024 * G) {
+        for (int i = tid * G; i < wlen; i += WAVES * WAVE * G) {
             if (x16 && i + G <= wlen) {
                 *reinterpret_cast<V *>(&xs[i]) = *reinterpret_cast<const V *>(x + xb + i);
             } else {
@@ -216,7 +217,7 @@ static hipError_t launch_slab_pairs_t(const T *svals, const uint16_t *scol, cons
     if (nwg < 1) nwg = 1;
     const int cpw = (nchunks + nwg - 1) / nwg;
     const int grid = (nchunks + cpw - 1) / cpw;
-    PSK_LAUNCH(k_slab_pairs<T>, dim3(grid), dim3(1024), 0, s, svals, scol, chunk_pair, slab_chunk, x, P, cols, nslabs,
+    PSK_LAUNCH(k_slab_pairs<T>, dim3(grid), dim3(SlabOf<T>::WAVES * WAVE), 0, s, svals, scol, chunk_pair, slab_chunk, x, P, cols, nslabs,
                nchunks, cpw, gap);
     return take_launch_status();
 }

@@ -167,3 +167,30 @@ def test_slab_path_full_size_power_law():
     psk.psk_spmv_slab(S, x, y, ws=ws)
     torch.cuda.synchronize()
     assert torch.equal(first, y), "the slab product is not deterministic"
+
+
+def test_slab_path_full_size_power_law_f64():
+    """The configuration `bench.py --workload powerlaw --f64` times: the power-law matrix at full size with fp64
+    values through the slab path; structure bit for bit against the oracle's, product in full against the
+    extended-precision CSR definition within 1e-14 * sum |a x| + 1e-300."""
+    A = wl.config(2)["A"]
+    vals = wl.dense_uniform_f64(A.nnz, wl.BASE_SEED + 2, wl.S_VALS)
+    xh = wl.dense_uniform_f64(A.cols, wl.BASE_SEED + 2, wl.S_X)
+    pos, crd = dev(A.pos), dev(A.crd)
+    say("fp64 slab path, full size: rows", A.rows, "nnz", A.nnz)
+    S = psk.psk_slab_build_csr_f64(A.rows, A.cols, A.nnz, pos, crd, dev(vals))
+    d = S.desc
+    O = oracle.slab_build(A.rows, A.cols, A.pos, A.crd, vals, W=int(d.slab_cols), CH=512, f64=True)
+    assert int(d.slab_cols) == 16352 and int(d.value_bytes) == 8
+    assert (d.nslots, d.npairs, d.nq, d.nslabs) == (O.nslots, O.npairs, O.nq, O.nslabs)
+    for arr in ("slab_chunk", "chunk_pair", "qpos", "qidx"):
+        assert np.array_equal(S.array(arr).cpu().numpy(), getattr(O, arr)), arr
+    assert np.array_equal(S.array("scol").cpu().numpy().view(np.uint16), O.scol)
+    assert S.array("svals").cpu().numpy().tobytes() == O.svals.tobytes()
+    ws = psk.psk_slab_spmv_workspace(S)
+    y = torch.full((A.rows,), float("nan"), dtype=torch.float64, device="cuda")
+    psk.psk_spmv_slab_f64(S, dev(xh), y, ws=ws)
+    torch.cuda.synchronize()
+    ref, mag = oracle.spmv_csr_f64(A.pos, A.crd, vals, xh, threads=16)
+    ok, worst = oracle.within_tolerance(y.cpu().numpy(), ref, mag, 1e-14, 1e-300)
+    assert ok, "fp64 slab path, configuration 2 in full: worst |err|/bound = %.3g" % worst
