@@ -74,3 +74,53 @@ def test_captured_products_replay_correctly():
         ref, mag = oracle.spmm_csr(M.pos, M.crd, M.vals, Bh, threads=8)
         ok, worst = oracle.within_tolerance(C.cpu().numpy(), ref, mag)
         assert ok, "replay %d, C: %.3g" % (rep, worst)
+
+
+def test_captured_slab_products_replay_correctly():
+    """The products over the column-slab structure (fp32 and fp64) captured into one graph: the structure is built
+    before the capture (its build synchronises), the products only enqueue kernels."""
+    A = wl.config(2, 0.02)["A"]
+    pos, crd = dev(A.pos), dev(A.crd)
+    v64 = wl.dense_uniform_f64(A.nnz, 31, wl.S_VALS)
+    S32 = psk.psk_slab_build_csr(A.rows, A.cols, A.nnz, pos, crd, dev(A.vals))
+    S64 = psk.psk_slab_build_csr_f64(A.rows, A.cols, A.nnz, pos, crd, dev(v64))
+    ws32, ws64 = psk.psk_slab_spmv_workspace(S32), psk.psk_slab_spmv_workspace(S64)
+    x32 = torch.zeros(A.cols, device="cuda")
+    x64 = torch.zeros(A.cols, dtype=torch.float64, device="cuda")
+    y32 = torch.zeros(A.rows, device="cuda")
+    y64 = torch.zeros(A.rows, dtype=torch.float64, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        psk.psk_spmv_slab(S32, x32, y32, ws=ws32)
+        psk.psk_spmv_slab_f64(S64, x64, y64, ws=ws64)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    say("capturing the slab products")
+    with torch.cuda.graph(g):
+        psk.psk_spmv_slab(S32, x32, y32, ws=ws32)
+        psk.psk_spmv_slab_f64(S64, x64, y64, ws=ws64)
+    for rep in range(4):
+        xh = wl.dense_uniform(A.cols, 300 + rep, wl.S_X)
+        xh64 = wl.dense_uniform_f64(A.cols, 400 + rep, wl.S_X)
+        x32.copy_(dev(xh))
+        x64.copy_(dev(xh64))
+        y32.fill_(float("nan"))
+        y64.fill_(float("nan"))
+        ws32.fill_(0xFF)
+        ws64.fill_(0xFF)
+        say("slab replay", rep)
+        g.replay()
+        torch.cuda.synchronize()
+        e32, e64 = torch.empty_like(y32), torch.empty_like(y64)
+        psk.psk_spmv_slab(S32, x32, e32)
+        psk.psk_spmv_slab_f64(S64, x64, e64)
+        torch.cuda.synchronize()
+        assert torch.equal(y32, e32) and torch.equal(y64, e64), "slab replay %d differs from the eager result" % rep
+        ref, mag = oracle.spmv_csr(A.pos, A.crd, A.vals, xh, threads=8)
+        ok, worst = oracle.within_tolerance(y32.cpu().numpy(), ref, mag)
+        assert ok, "slab replay %d: %.3g" % (rep, worst)
+        ref, mag = oracle.spmv_csr_f64(A.pos, A.crd, v64, xh64, threads=8)
+        ok, worst = oracle.within_tolerance(y64.cpu().numpy(), ref, mag, 1e-14, 1e-300)
+        assert ok, "fp64 slab replay %d: %.3g" % (rep, worst)
