@@ -255,13 +255,31 @@ __device__ __forceinline__ int block_scan_256(int v, int *s_w, int *total)
     return inc + off;
 }
 
+// a thread's SCAN_EPT consecutive elements, as four 16-byte loads when they all exist (the arrays start on 256-byte
+// boundaries and a thread's share on a 64-byte one)
+__device__ __forceinline__ void scan_load(const int *__restrict__ in, long long base, long long n, int (&v)[SCAN_EPT])
+{
+    if (base + SCAN_EPT <= n) {
+#pragma unroll
+        for (int g = 0; g < SCAN_EPT / 4; ++g) {
+            const v4i t = *reinterpret_cast<const v4i *>(in + base + 4 * g);
+            v[4 * g] = t.x; v[4 * g + 1] = t.y; v[4 * g + 2] = t.z; v[4 * g + 3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < SCAN_EPT; ++i) v[i] = base + i < n ? in[base + i] : 0;
+    }
+}
+
 __global__ __launch_bounds__(256) void k_scan_reduce(const int *__restrict__ in, long long n, int *__restrict__ bsum)
 {
     __shared__ int s_w[4];
     const long long base = (long long)blockIdx.x * SCAN_BLOCK + threadIdx.x * SCAN_EPT;
+    int v[SCAN_EPT];
+    scan_load(in, base, n, v);
     int t = 0;
 #pragma unroll
-    for (int i = 0; i < SCAN_EPT; ++i) t += base + i < n ? in[base + i] : 0;
+    for (int i = 0; i < SCAN_EPT; ++i) t += v[i];
     int total;
     block_scan_256(t, s_w, &total);
     if (threadIdx.x == 0) bsum[blockIdx.x] = total;
@@ -289,17 +307,28 @@ __global__ __launch_bounds__(256) void k_scan_apply(const int *__restrict__ in, 
     __shared__ int s_w[4];
     const long long base = (long long)blockIdx.x * SCAN_BLOCK + threadIdx.x * SCAN_EPT;
     int v[SCAN_EPT];
+    scan_load(in, base, n, v);
     int t = 0;
 #pragma unroll
-    for (int i = 0; i < SCAN_EPT; ++i) { v[i] = base + i < n ? in[base + i] : 0; t += v[i]; }
+    for (int i = 0; i < SCAN_EPT; ++i) t += v[i];
     int total;
     const int inc = block_scan_256(t, s_w, &total);
     int run = bsum[blockIdx.x] + inc - t;
+    int o[SCAN_EPT];
 #pragma unroll
     for (int i = 0; i < SCAN_EPT; ++i) {
         if (INCLUSIVE) run += v[i];
-        if (base + i < n) out[base + i] = run;
+        o[i] = run;
         if (!INCLUSIVE) run += v[i];
+    }
+    if (base + SCAN_EPT <= n) {
+#pragma unroll
+        for (int g = 0; g < SCAN_EPT / 4; ++g)
+            *reinterpret_cast<v4i *>(out + base + 4 * g) = v4i{o[4 * g], o[4 * g + 1], o[4 * g + 2], o[4 * g + 3]};
+    } else {
+#pragma unroll
+        for (int i = 0; i < SCAN_EPT; ++i)
+            if (base + i < n) out[base + i] = o[i];
     }
 }
 
@@ -376,54 +405,74 @@ __global__ __launch_bounds__(64) void k_slab_pads(const int *__restrict__ E, int
 
 // Stable bucketing.  One wave per block of BUILD_BT CSR positions, taken 64 at a time in order; off[s] is the
 // slot the block's next position of slab s goes to.  The lanes of one step that share a slab are ranked by
-// lane number (ballot), so the order of the CSR is kept inside every slab.  The row of a position is the
-// largest r with pos[r] <= p, searched between the rows of the block's first and last position
-// (tile_row = the position cut of pos with tiles of BUILD_BT).
+// lane number, so the order of the CSR is kept inside every slab: `nbits` ballots, one per bit of the slab
+// number, leave every lane with the mask of the lanes of its slab.  The row of a position is the largest r
+// with pos[r] <= p, searched between the rows of the block's first and last position (tile_row = the position
+// cut of pos with tiles of BUILD_BT) -- in a copy of that part of pos in LDS when it has at most SCATTER_ROWS
+// entries, in global memory otherwise.  The loads of the next 64 positions are issued before the current ones
+// are placed.
+constexpr int SCATTER_ROWS = 1024;
 template <typename T>
 __global__ __launch_bounds__(64) void k_slab_scatter(int rows, int nnz, const int *__restrict__ pos,
                                                      const int *__restrict__ crd, const T *__restrict__ vals,
                                                      const int *__restrict__ tile_row, const int *__restrict__ E,
                                                      const int *__restrict__ slab_chunk, int nslabs, int nblk,
-                                                     T *__restrict__ svals, unsigned short *__restrict__ scol,
-                                                     int *__restrict__ srow, int *__restrict__ src)
+                                                     int nbits, T *__restrict__ svals,
+                                                     unsigned short *__restrict__ scol, int *__restrict__ srow,
+                                                     int *__restrict__ src)
 {
-    extern __shared__ int off[];
+    extern __shared__ int off[];                 // [nslabs] next slot of each slab, then [SCATTER_ROWS] row starts
     constexpr int W = SlabOf<T>::W;
     const int b = blockIdx.x, lane = threadIdx.x;
+    int *spos = off + nslabs;
     for (int s = lane; s < nslabs; s += WAVE)
         off[s] = slab_chunk[s] * SLAB_CH + (E[(long long)s * nblk + b] - E[(long long)s * nblk]);
-    __syncthreads();
     const long long p0 = (long long)b * BUILD_BT;
     const int r_lo = tile_row[b], r_hi = tile_row[b + 1];
+    const bool local = r_hi - r_lo < SCATTER_ROWS;          // rows r_lo .. r_hi: at most SCATTER_ROWS of them
+    if (local)
+        for (int i = lane; i <= r_hi - r_lo; i += WAVE) spos[i] = pos[r_lo + i];
+    __syncthreads();
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int c_next = 0;
+    T v_next = 0;
+    if (p0 + lane < nnz) { c_next = crd[p0 + lane]; v_next = vals[p0 + lane]; }
     for (int it = 0; it < BUILD_BT / WAVE; ++it) {
         const long long pl = p0 + it * WAVE + lane;
         const bool valid = pl < nnz;
         const int p = valid ? (int)pl : 0;
-        int c = 0, s = -1, r = 0;
-        T v = 0;
+        const int c = c_next;
+        const T v = v_next;
+        if (it + 1 < BUILD_BT / WAVE && pl + WAVE < nnz) { c_next = crd[pl + WAVE]; v_next = vals[pl + WAVE]; }
+        const int s = valid ? c / W : 0;
+        int r = 0;
         if (valid) {
-            c = crd[p];
-            v = vals[p];
-            s = c / W;
             int lo = r_lo, hi = r_hi;
-            while (lo < hi) {
-                const int mid = lo + ((hi - lo + 1) >> 1);
-                if (pos[mid] <= p) lo = mid; else hi = mid - 1;
+            if (local) {
+                while (lo < hi) {
+                    const int mid = lo + ((hi - lo + 1) >> 1);
+                    if (spos[mid - r_lo] <= p) lo = mid; else hi = mid - 1;
+                }
+            } else {
+                while (lo < hi) {
+                    const int mid = lo + ((hi - lo + 1) >> 1);
+                    if (pos[mid] <= p) lo = mid; else hi = mid - 1;
+                }
             }
             r = lo;
         }
-        int dst = -1;
-        unsigned long long todo = __ballot(valid);
-        while (todo) {
-            const int leader = __ffsll((long long)todo) - 1;
-            const int sl = __shfl(s, leader, WAVE);
-            const unsigned long long same = __ballot(valid && s == sl);
-            if (valid && s == sl) dst = off[sl] + __popcll(same & ((1ull << lane) - 1ull));
-            __syncthreads();                                  // one wave: orders the LDS read before the update
-            if (lane == leader) off[sl] += __popcll(same);
-            __syncthreads();
-            todo &= ~same;
+        // peers = the valid lanes with the same slab number
+        unsigned long long peers = __ballot(valid);
+        for (int k = 0; k < nbits; ++k) {
+            const bool one = (s >> k) & 1;
+            const unsigned long long m = __ballot(valid && one);
+            peers &= one ? m : ~m;
         }
+        int dst = -1;
+        if (valid) dst = off[s] + __popcll(peers & below);
+        __syncthreads();                                  // one wave: orders the LDS reads before the updates
+        if (valid && (peers & below) == 0) off[s] += __popcll(peers);
+        __syncthreads();
         if (valid) {
             svals[slab_value_index<SlabOf<T>::G>(dst)] = v;
             scol[dst] = (unsigned short)(c - s * W);
@@ -547,13 +596,15 @@ static hipError_t launch_slab_build_t(int32_t rows, int32_t cols, int32_t nnz, c
     hipError_t e = launch_partition(rows, nnz, pos, BUILD_BT, 0, w.tile_row, s);
     if (e != hipSuccess) return e;
     const size_t lds = (size_t)S * 4;
+    int nbits = 0;                                  // bits of a slab number
+    while ((1 << nbits) < S) ++nbits;
     PSK_LAUNCH(k_slab_hist, dim3(nblk), dim3(256), (unsigned)lds, s, nnz, crd, W, S, nblk, w.H);
     PSK_LAUNCH(k_fill_int, dim3(1), dim3(64), 0, s, w.H + (long long)S * nblk, 1ll, 0);      // the scan's total slot
     launch_scan(w.H, w.H, (int64_t)S * nblk + 1, w.scan_tmp, false, s);
     PSK_LAUNCH(k_slab_bases, dim3(1), dim3(256), 0, s, w.H, S, nblk, slab_chunk, w.meta);
     PSK_LAUNCH(k_slab_pads<T>, dim3(S), dim3(64), 0, s, w.H, nblk, slab_chunk, svals, scol_d, w.srow, w.src);
-    PSK_LAUNCH(k_slab_scatter<T>, dim3(nblk), dim3(64), (unsigned)lds, s, rows, nnz, pos, crd, vals, w.tile_row, w.H,
-               slab_chunk, S, nblk, svals, scol_d, w.srow, w.src);
+    PSK_LAUNCH(k_slab_scatter<T>, dim3(nblk), dim3(64), (unsigned)(lds + SCATTER_ROWS * 4), s, rows, nnz, pos, crd, vals,
+               w.tile_row, w.H, slab_chunk, S, nblk, nbits, svals, scol_d, w.srow, w.src);
     PSK_LAUNCH(k_slab_starts, dim3((unsigned)((nmax + 1 + 255) / 256)), dim3(256), 0, s, w.meta, w.srow,
                (long long)(nmax + 1), w.F);
     launch_scan(w.F, w.F, nmax + 1, w.scan_tmp, true, s);
