@@ -30,7 +30,7 @@
  *    synchronises.  Calls that share a workspace must be stream-ordered.
  *  - Index arrays are int32, values and dense operands fp32; products and sums
  *    are fp32 on the device (carries between tiles are combined in fp64).
- *    psk_spmv_csr_f64 is all fp64.
+ *    psk_spmv_csr_f64, psk_slab_build_csr_f64 and psk_spmv_slab_f64 are all fp64.
  *  - Outputs are assigned, not accumulated: rows without stored entries
  *    become +0.0f.  Inputs and outputs must not overlap.
  *  - Results are run-to-run deterministic: every y(i) / C(i,k) has one writer
@@ -183,6 +183,8 @@ int psk_spmv_csr_static(int64_t rows, int64_t cols, int64_t nnz, const int32_t *
  * can be kept).  Answers 1 when x fits a die's L2 or the matrix is small; otherwise it samples up to
  * 16384 positions and, if fewer than half of them have their successor's column in the same 128-byte
  * line of x, suggests ceil(4*cols bytes / 6 MiB), at most PSK_MAX_COL_PASSES.
+ * A suggestion above 1 also marks the matrices for which the column-slab copy (psk_slab_build_csr, then
+ * psk_spmv_slab) pays once the matrix is multiplied about ten times or more.
  * `col_passes` is a HOST pointer.  This call SYNCHRONISES `stream` when it samples (it reads the count
  * back); `workspace` needs 256 bytes.
  */
