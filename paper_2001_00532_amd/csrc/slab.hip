@@ -90,7 +90,7 @@ __device__ __forceinline__ T wave_segscan(T v, int f)
 }
 
 // ------------------------------------------------------------------ step 1 of the product
-// Persistent workgroups: workgroup b owns the chunks [b*cpw, (b+1)*cpw) (the position space DIVIDED into
+// Persistent workgroups: every workgroup owns one piece of cpw consecutive chunks (the position space DIVIDED into
 // equal pieces, Section 5), walks them slab by slab, loads the slab's part of x into LDS once and lets its
 // waves (16; 8 for fp64) take the chunks of that slab round-robin.  A lane owns 8 consecutive slots (two 16-byte loads of
 // values, one of columns); the next chunk's loads are issued before the current one is processed.
@@ -122,7 +122,11 @@ __global__ __launch_bounds__(SlabOf<T>::WAVES * WAVE) void k_slab_pairs(const T 
     const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
     T *st = stage + wave * SLAB_CH;
     const int dummy = (WAVES - wave) * SLAB_CH + (lane & 31);      // index, relative to st, of a word nobody reads
-    int c0 = blockIdx.x * cpw;
+    // piece of this workgroup: neighbouring pieces go to workgroups of the same die, so that the slabs of x they share
+    // are fetched into that die's L2 once (measured on the power-law matrix: 76.2 against 79.4 us)
+    const int piece = xcd_tile(blockIdx.x, (nchunks + cpw - 1) / cpw);
+    if (piece < 0) return;
+    int c0 = piece * cpw;
     const int c1 = min(c0 + cpw, nchunks);
     if (c0 >= c1) return;
     PSK_TRACE_WORKGROUP();
@@ -216,7 +220,7 @@ static hipError_t launch_slab_pairs_t(const T *svals, const uint16_t *scol, cons
     if (nchunks <= 0) return hipSuccess;
     if (nwg < 1) nwg = 1;
     const int cpw = (nchunks + nwg - 1) / nwg;
-    const int grid = (nchunks + cpw - 1) / cpw;
+    const int grid = xcd_grid((nchunks + cpw - 1) / cpw);
     PSK_LAUNCH(k_slab_pairs<T>, dim3(grid), dim3(SlabOf<T>::WAVES * WAVE), 0, s, svals, scol, chunk_pair, slab_chunk, x, P, cols, nslabs,
                nchunks, cpw, gap);
     return take_launch_status();
