@@ -404,7 +404,6 @@ int psk_spmm_csr_rowsplit(int64_t rows, int64_t cols, int64_t nnz, const int32_t
  * fp64 values (the value type of the paper's own schedules, appendix "SPMV on a GPU"): the _f64 entry points
  * build and use the same structure with 8-byte values and slabs of PSK_SLAB_COLS_F64 columns (a slab of x and
  * the staging area of the pair sums share the 160 KB of on-chip memory); x, y and the pair sums are doubles.
- * The fp64 row-sum kernel clears rows without entries one by one (no run list for long runs of empty rows).
  */
 #define PSK_SLAB_COLS 32736
 #define PSK_SLAB_COLS_F64 16352

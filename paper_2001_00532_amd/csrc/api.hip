@@ -316,13 +316,13 @@ int psk_spmv_csr_f64(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int32_t ntiles = (int32_t)psk_num_tiles(nnz, tile);
     hipError_t e = hipSuccess;
-    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, 0, ws.tile_row, s);
+    if ((phases & PSK_PHASE_PARTITION) && e == hipSuccess) e = launch_partition(rows, nnz, pos, tile, 0, ws.tile_row, s, ws.gap);
     if ((phases & PSK_PHASE_MAIN) && e == hipSuccess) {
         if (ntiles == 0) e = launch_fill_zero(reinterpret_cast<float *>(y), 2 * rows, s);
         else e = launch_spmv_csr_f64_main((int32_t)rows, (int32_t)cols, (int32_t)nnz, pos, crd, vals, x, y, tile, col_passes,
-                                          ws, s);
+                                          ws, s, true);
     }
-    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup_f64(ntiles, tile, pos, ws, y, s);
+    if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup_f64(ntiles, tile, pos, ws, y, s, true);
     return hip_status(e);
 }
 

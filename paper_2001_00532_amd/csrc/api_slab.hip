@@ -156,16 +156,15 @@ int spmv_slab(const psk_slab *S, const void *x, void *y, int vbytes, int phases,
         double *P = static_cast<double *>(workspace);
         double *yd = static_cast<double *>(y);
         if (phases & PSK_PHASE_MAIN) {
-            // the fp64 tile kernel keeps no run list: it clears empty rows itself
             e = launch_slab_pairs_f64(static_cast<const double *>(S->svals), S->scol, S->chunk_pair, S->slab_chunk,
                                       static_cast<const double *>(x), P, (int32_t)S->cols, (int32_t)S->nslabs,
-                                      (int32_t)S->nchunks, cus, nullptr, s);
+                                      (int32_t)S->nchunks, cus, ws.gap, s);
             if (e == hipSuccess) {
                 if (ntiles == 0) e = launch_fill_zero(static_cast<float *>(y), zero_words, s);
                 else e = launch_spmv_csr_f64_ones((int32_t)S->rows, (int32_t)S->nq, S->qpos, S->qidx, P, yd, ws, s);
             }
         }
-        if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup_f64(ntiles, kSlabTile, S->qpos, ws, yd, s);
+        if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup_f64(ntiles, kSlabTile, S->qpos, ws, yd, s, true);
         return hip_status(e);
     }
     float *P = static_cast<float *>(workspace);

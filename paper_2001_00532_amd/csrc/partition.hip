@@ -362,15 +362,16 @@ hipError_t launch_carry_fixup(int32_t ntiles, int32_t nsub, int32_t k, int64_t l
 }
 
 hipError_t launch_carry_fixup_f64(int32_t ntiles, int32_t tile, const int32_t *pos, const Workspace &w, double *out,
-                                  hipStream_t s)
+                                  hipStream_t s, bool gaps)
 {
-    if (ntiles <= 1) return hipSuccess;
+    gaps = gaps && ntiles >= 1;
+    if (ntiles <= 1 && !gaps) return hipSuccess;
     int shift = -1;
     if ((tile & (tile - 1)) == 0) { shift = 0; while ((1 << shift) < tile) ++shift; }
-    int *nogap = nullptr;
-    PSK_LAUNCH(k_carry_fixup1<double>, dim3((unsigned)((ntiles + 255) / 256)), dim3(256), 0, s, ntiles, 1ll,
-                       tile, shift, pos, w.carry_row, reinterpret_cast<const double *>(w.carry_val), out,
-                       (ntiles + 255) / 256, nogap);
+    const int carry_groups = ntiles <= 1 ? 0 : (ntiles + 255) / 256;
+    int *gap = gaps ? w.gap : nullptr;
+    PSK_LAUNCH(k_carry_fixup1<double>, dim3((unsigned)(carry_groups + (gaps ? kGapFillGroups : 0))), dim3(256), 0, s, ntiles,
+               1ll, tile, shift, pos, w.carry_row, reinterpret_cast<const double *>(w.carry_val), out, carry_groups, gap);
     return take_launch_status();
 }
 

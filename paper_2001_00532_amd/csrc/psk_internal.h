@@ -118,9 +118,9 @@ hipError_t launch_spmv_csr_divide(int32_t rows, int32_t nnz, const int32_t *pos,
 bool spmv_csr_f64_tile_ok(int32_t tile);
 hipError_t launch_spmv_csr_f64_main(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
                                     const double *vals, const double *x, double *y, int32_t tile, int32_t col_passes,
-                                    const Workspace &w, hipStream_t s);
+                                    const Workspace &w, hipStream_t s, bool gaps = false);
 hipError_t launch_carry_fixup_f64(int32_t ntiles, int32_t tile, const int32_t *pos, const Workspace &w, double *out,
-                                  hipStream_t s);
+                                  hipStream_t s, bool gaps = false);
 
 // CSR SpMM
 bool spmm_csr_tile_ok(int32_t tile);

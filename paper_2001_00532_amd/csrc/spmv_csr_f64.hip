@@ -31,7 +31,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos_f64(int rows, int nnz, con
                                                           const int *__restrict__ tile_row,
                                                           int *__restrict__ carry_row,
                                                           double *__restrict__ carry_val, int ntiles, int clo,
-                                                          int chi, int accum, int *__restrict__ tile_cols)
+                                                          int chi, int accum, int *__restrict__ tile_cols,
+                                                          int *__restrict__ gap)
 {
     constexpr int T = THREADS * NPT;
     constexpr int NW = THREADS / WAVE;
@@ -42,6 +43,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos_f64(int rows, int nnz, con
     __shared__ int slong[MAXLONG * 3];
     __shared__ int nlong;
     __shared__ double swave[NW];
+    __shared__ int srowid[T];            // row of every position of the tile (only when the tile spans a long run of empty rows)
 
     const int t = xcd_tile(blockIdx.x, ntiles);
     if (t < 0) return;
@@ -168,6 +170,51 @@ __global__ __launch_bounds__(THREADS) void k_spmv_pos_f64(int rows, int nnz, con
 #pragma unroll
     for (int g = 0; g < NPT; ++g) sprod[skew<1>(index(g))] = prod[g];
     __syncthreads();
+    if (gap && rend - rbeg > kGapRows) {
+        // The tile's rows span a long run of empty rows (Section 6.2 walks past empty rows one by one; here that walk
+        // would be done by this one workgroup).  As in the fp32 kernel: the row of every position is found by search (a
+        // thread takes NPT consecutive positions), the row segments are summed by the thread that holds their first
+        // position, and the run of rows is handed to the fix-up step, whose extra workgroups clear its empty rows.
+        const int i0 = tid * NPT;
+        if (i0 < cnt) {
+            int lo = r0, hi = r1;                       // max { r in [r0, r1] : pos[r] <= t0 + i0 }
+            while (lo < hi) {
+                const int mid = lo + ((hi - lo + 1) >> 1);
+                if (pos[mid] <= t0 + i0) lo = mid; else hi = mid - 1;
+            }
+            int r = lo;
+            int next = pos[r + 1];
+#pragma unroll 1
+            for (int k = 0; k < NPT && i0 + k < cnt; ++k) {
+                const int p = t0 + i0 + k;
+                if (p >= next) {                        // the row ended: the next row with entries owns p
+                    int l2 = r + 1, h2 = r1;
+                    while (l2 < h2) {
+                        const int mid = l2 + ((h2 - l2 + 1) >> 1);
+                        if (pos[mid] <= p) l2 = mid; else h2 = mid - 1;
+                    }
+                    r = l2;
+                    next = pos[r + 1];
+                }
+                srowid[i0 + k] = r;
+            }
+        }
+        __syncthreads();
+#pragma unroll 1
+        for (int k = 0; k < NPT && i0 + k < cnt; ++k) {
+            const int i = i0 + k;
+            const int r = srowid[i];
+            if (i > 0 && srowid[i - 1] == r) continue;  // not the first position of its row segment
+            double sum = 0.0;
+            for (int j = i; j < cnt && srowid[j] == r; ++j) sum += sprod[skew<1>(j)];
+            emit(r, sum);
+        }
+        if (tid == 0 && !(WIN && accum)) {
+            const int e = atomicAdd(&gap[0], 1);
+            if (e < ntiles) { gap[2 + 2 * e] = rbeg; gap[3 + 2 * e] = rend; }
+        }
+        return;
+    }
     for (int r = rbeg + tid; r < rend; r += THREADS) {
         int lo = my_lo - t0, hi = my_hi - t0;
         if (r + THREADS < rend) { my_lo = pos[r + THREADS]; my_hi = pos[r + THREADS + 1]; }
@@ -203,12 +250,13 @@ bool spmv_csr_f64_tile_ok(int32_t tile) { return tile == 256 || tile == 512 || t
 
 template <int THREADS, int NPT>
 static void go(bool vec, bool win, int grid, hipStream_t s, int rows, int nnz, const int *pos, const int *crd,
-               const double *vals, const double *x, double *y, const Workspace &w, int ntiles, int clo, int chi, int accum)
+               const double *vals, const double *x, double *y, const Workspace &w, int ntiles, int clo, int chi, int accum,
+               int *gap)
 {
     double *cv = reinterpret_cast<double *>(w.carry_val);
 #define PSK_GO(V, W)                                                                                                  \
     PSK_LAUNCH((k_spmv_pos_f64<THREADS, NPT, V, W>), dim3(grid), dim3(THREADS), 0, s, rows, nnz, pos, crd, vals, \
-                       x, y, w.tile_row, w.carry_row, cv, ntiles, clo, chi, accum, w.tile_cols)
+                       x, y, w.tile_row, w.carry_row, cv, ntiles, clo, chi, accum, w.tile_cols, gap)
     if (vec) { if (win) PSK_GO(true, true); else PSK_GO(true, false); }
     else { if (win) PSK_GO(false, true); else PSK_GO(false, false); }
 #undef PSK_GO
@@ -216,8 +264,9 @@ static void go(bool vec, bool win, int grid, hipStream_t s, int rows, int nnz, c
 
 hipError_t launch_spmv_csr_f64_main(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
                                     const double *vals, const double *x, double *y, int32_t tile, int32_t col_passes,
-                                    const Workspace &w, hipStream_t s)
+                                    const Workspace &w, hipStream_t s, bool gaps)
 {
+    int *gap = gaps ? w.gap : nullptr;
     const int ntiles = (int)(((int64_t)nnz + tile - 1) / tile);
     if (ntiles == 0) return hipSuccess;
     const int grid = xcd_grid(ntiles);
@@ -228,10 +277,10 @@ hipError_t launch_spmv_csr_f64_main(int32_t rows, int32_t cols, int32_t nnz, con
         const bool win = col_passes > 1;
         const int accum = p > 0;
         switch (tile) {
-            case 256:  go<64, 4>(vec, win, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
-            case 512:  go<128, 4>(vec, win, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
-            case 1024: go<256, 4>(vec, win, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
-            case 2048: go<256, 8>(vec, win, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum); break;
+            case 256:  go<64, 4>(vec, win, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, gap); break;
+            case 512:  go<128, 4>(vec, win, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, gap); break;
+            case 1024: go<256, 4>(vec, win, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, gap); break;
+            case 2048: go<256, 8>(vec, win, grid, s, rows, nnz, pos, crd, vals, x, y, w, ntiles, clo, chi, accum, gap); break;
             default: return hipErrorInvalidValue;
         }
     }
@@ -249,10 +298,10 @@ hipError_t launch_spmv_csr_f64_ones(int32_t rows, int32_t nnz, const int32_t *po
     double *cv = reinterpret_cast<double *>(w.carry_val);
     if ((reinterpret_cast<uintptr_t>(crd) & 15) == 0)
         PSK_LAUNCH((k_spmv_pos_f64<256, 8, true, false, true>), dim3(grid), dim3(256), 0, s, rows, nnz, pos, crd, none, x, y,
-                   w.tile_row, w.carry_row, cv, ntiles, 0, 0x7fffffff, 0, w.tile_cols);
+                   w.tile_row, w.carry_row, cv, ntiles, 0, 0x7fffffff, 0, w.tile_cols, w.gap);
     else
         PSK_LAUNCH((k_spmv_pos_f64<256, 8, false, false, true>), dim3(grid), dim3(256), 0, s, rows, nnz, pos, crd, none, x,
-                   y, w.tile_row, w.carry_row, cv, ntiles, 0, 0x7fffffff, 0, w.tile_cols);
+                   y, w.tile_row, w.carry_row, cv, ntiles, 0, 0x7fffffff, 0, w.tile_cols, w.gap);
     return take_launch_status();
 }
 

@@ -108,3 +108,43 @@ def test_f64_full_size_powerlaw_sampled():
     ref, mag = oracle.spmv_csr_f64(A.pos, A.crd, vals, x, sel=sel, threads=16)
     ok, worst = oracle.within_tolerance(y[torch.from_numpy(sel).cuda()].cpu().numpy(), ref, mag, REL, FLOOR)
     assert ok, "worst %.3g" % worst
+
+
+def test_f64_long_runs_of_empty_rows():
+    """Ten million empty rows between two groups of stored rows: the tile that spans the run lists it and the fix-up's
+    extra workgroups clear it, as in the fp32 kernel; one and two column passes, a second product on the same table,
+    and the row sums of the fp64 slab path."""
+    import time
+
+    rng = np.random.default_rng(78)
+    rows, cols = 10_000_000 + 45_000, 120_000
+    L = np.zeros(rows, dtype=np.int64)
+    L[20_000:22_500] = rng.integers(1, 60, size=2_500)
+    L[21_000] = 30_000
+    L[10_022_500:10_025_000] = rng.integers(0, 60, size=2_500)
+    A = wl.csr_from_lengths(L, cols, seed=78)
+    vals = wl.dense_uniform_f64(A.nnz, 78, wl.S_VALS)
+    x = wl.dense_uniform_f64(cols, 79, wl.S_X)
+    ref, mag = oracle.spmv_csr_f64(A.pos, A.crd, vals, x, threads=8)
+    pos, crd, vd, xd = dev(A.pos), dev(A.crd), dev(vals), dev(x)
+    for tile, passes in ((0, 1), (256, 1), (0, 2)):
+        ws = psk.workspace(psk.PSK_OP_SPMV_CSR_F64, rows, A.nnz, tile=tile)
+        for rep, phases in enumerate((psk.PSK_PHASE_ALL, psk.PSK_PHASE_MAIN | psk.PSK_PHASE_FIXUP)):
+            y = torch.full((rows,), float("nan"), dtype=torch.float64, device="cuda")
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            psk.psk_spmv_csr_f64(rows, cols, A.nnz, pos, crd, vd, xd, y, tile=tile, col_passes=passes, phases=phases, ws=ws)
+            torch.cuda.synchronize()
+            say("f64 empty-row run: tile", tile, "passes", passes, "product", rep, "%.0f us" % ((time.perf_counter() - t0) * 1e6))
+            ok, worst = oracle.within_tolerance(y.cpu().numpy(), ref, mag, REL, FLOOR)
+            assert ok, "f64 empty-row run, tile %d passes %d product %d: %.3g" % (tile, passes, rep, worst)
+    S = psk.psk_slab_build_csr_f64(rows, cols, A.nnz, pos, crd, vd)
+    for rep in range(2):
+        y = torch.full((rows,), float("nan"), dtype=torch.float64, device="cuda")
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        psk.psk_spmv_slab_f64(S, xd, y)
+        torch.cuda.synchronize()
+        say("f64 empty-row run, slab path, product", rep, "%.0f us" % ((time.perf_counter() - t0) * 1e6))
+        ok, worst = oracle.within_tolerance(y.cpu().numpy(), ref, mag, REL, FLOOR)
+        assert ok, "f64 empty-row run, slab path, product %d: %.3g" % (rep, worst)
