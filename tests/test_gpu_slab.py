@@ -156,3 +156,51 @@ def test_slab_rejects_bad_arguments():
     assert L.psk_slab_build_csr(4, 4, 4, one, one, one, one, 16, one, 1 << 30, ctypes.byref(d), None) == 4
     assert L.psk_slab_build_csr(-1, 4, 4, one, one, one, one, 1 << 30, one, 1 << 30, ctypes.byref(d), None) == 2
     assert L.psk_spmv_slab(None, one, one, 7, one, 1 << 30, None) == 1
+
+
+def test_slab_unaligned_vector_split_phases_own_buffers_and_stream():
+    """x that is 4-byte but not 16-byte aligned (the window is then loaded element by element), the two phases of a
+    product issued by separate calls, caller-provided structure memory and build workspace, and a stream of the
+    caller's; the same for fp64 with an x that is 8- but not 16-byte aligned."""
+    A = wl.config(2, 0.01)["A"]
+    xh = wl.dense_uniform(A.cols, 61, wl.S_X)
+    pos, crd, vals = dev(A.pos), dev(A.crd), dev(A.vals)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    mem = torch.empty(psk.psk_slab_mem_bytes(A.rows, A.cols, A.nnz), dtype=torch.uint8, device="cuda")
+    bws = torch.empty(psk.psk_slab_build_workspace_bytes(A.rows, A.cols, A.nnz), dtype=torch.uint8, device="cuda")
+    mem.fill_(0xA5)
+    bws.fill_(0x5A)
+    xbuf = torch.zeros(A.cols + 4, device="cuda")
+    x = xbuf[1:1 + A.cols]
+    x.copy_(dev(xh))
+    assert x.data_ptr() % 16 == 4
+    y = torch.full((A.rows,), float("nan"), device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        S = psk.psk_slab_build_csr(A.rows, A.cols, A.nnz, pos, crd, vals, mem=mem, ws=bws, stream=side)
+        ws = psk.psk_slab_spmv_workspace(S, stream=side)
+        psk.psk_spmv_slab(S, x, y, phases=psk.PSK_PHASE_MAIN, ws=ws, stream=side)
+        psk.psk_spmv_slab(S, x, y, phases=psk.PSK_PHASE_FIXUP, ws=ws, stream=side)
+    side.synchronize()
+    O = oracle.slab_build(A.rows, A.cols, A.pos, A.crd, A.vals)
+    assert np.array_equal(S.array("qidx").cpu().numpy(), O.qidx) and np.array_equal(S.array("scol").cpu().numpy().view(np.uint16), O.scol)
+    ref, mag = oracle.spmv_csr(A.pos, A.crd, A.vals, xh, threads=8)
+    ok, worst = oracle.within_tolerance(y.cpu().numpy(), ref, mag)
+    assert ok, "unaligned x, split phases: worst |err|/bound = %.3g" % worst
+    # fp64
+    v64 = wl.dense_uniform_f64(A.nnz, 62, wl.S_VALS)
+    x64h = wl.dense_uniform_f64(A.cols, 63, wl.S_X)
+    xbuf64 = torch.zeros(A.cols + 2, dtype=torch.float64, device="cuda")
+    x64 = xbuf64[1:1 + A.cols]
+    x64.copy_(dev(x64h))
+    assert x64.data_ptr() % 16 == 8
+    y64 = torch.full((A.rows,), float("nan"), dtype=torch.float64, device="cuda")
+    S64 = psk.psk_slab_build_csr_f64(A.rows, A.cols, A.nnz, pos, crd, dev(v64))
+    ws64 = psk.psk_slab_spmv_workspace(S64)
+    psk.psk_spmv_slab_f64(S64, x64, y64, phases=psk.PSK_PHASE_MAIN, ws=ws64)
+    psk.psk_spmv_slab_f64(S64, x64, y64, phases=psk.PSK_PHASE_FIXUP, ws=ws64)
+    torch.cuda.synchronize()
+    ref, mag = oracle.spmv_csr_f64(A.pos, A.crd, v64, x64h, threads=8)
+    ok, worst = oracle.within_tolerance(y64.cpu().numpy(), ref, mag, 1e-14, 1e-300)
+    assert ok, "fp64, unaligned x, split phases: worst |err|/bound = %.3g" % worst
