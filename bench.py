@@ -726,7 +726,7 @@ def main():
         "roofline": {
             "bound": "hbm",
             "kernel": ("k_slab_pairs<double> + k_spmv_pos_f64<256,8,*,unit values>" if path == "slab" else "k_spmv_pos_f64") if f64
-                      else ("k_slab_pairs + k_spmv_pos<256,8,*,6>" if path == "slab" else
+                      else ("k_slab_pairs<float> + k_spmv_pos<256,8,*,6>" if path == "slab" else
                        {"csr_spmv": "k_spmv_pos", "csr_spmm": "k_spmm_pos<1,*>", "bcsr_spmv": "k_spmv_bcsr4",
                         "bcsr_spmm": "k_spmm_pos<4,*>"}[kind]),
             "achieved": round(achieved, 2),
