@@ -261,6 +261,7 @@ __device__ __forceinline__ int block_scan_256(int v, int *s_w, int *total)
 
 // a thread's SCAN_EPT consecutive elements, as four 16-byte loads when they all exist (the arrays start on 256-byte
 // boundaries and a thread's share on a 64-byte one)
+template <bool NONZERO>
 __device__ __forceinline__ void scan_load(const int *__restrict__ in, long long base, long long n, int (&v)[SCAN_EPT])
 {
     if (base + SCAN_EPT <= n) {
@@ -273,14 +274,20 @@ __device__ __forceinline__ void scan_load(const int *__restrict__ in, long long 
 #pragma unroll
         for (int i = 0; i < SCAN_EPT; ++i) v[i] = base + i < n ? in[base + i] : 0;
     }
+    if (NONZERO) {
+#pragma unroll
+        for (int i = 0; i < SCAN_EPT; ++i) v[i] = v[i] != 0;
+    }
 }
 
+// NONZERO: the scanned sequence is (in[i] != 0)
+template <bool NONZERO>
 __global__ __launch_bounds__(256) void k_scan_reduce(const int *__restrict__ in, long long n, int *__restrict__ bsum)
 {
     __shared__ int s_w[4];
     const long long base = (long long)blockIdx.x * SCAN_BLOCK + threadIdx.x * SCAN_EPT;
     int v[SCAN_EPT];
-    scan_load(in, base, n, v);
+    scan_load<NONZERO>(in, base, n, v);
     int t = 0;
 #pragma unroll
     for (int i = 0; i < SCAN_EPT; ++i) t += v[i];
@@ -304,14 +311,14 @@ __global__ __launch_bounds__(256) void k_scan_spine(int *__restrict__ bsum, long
     }
 }
 
-template <bool INCLUSIVE>
+template <bool INCLUSIVE, bool NONZERO>
 __global__ __launch_bounds__(256) void k_scan_apply(const int *__restrict__ in, int *__restrict__ out, long long n,
                                                     const int *__restrict__ bsum)
 {
     __shared__ int s_w[4];
     const long long base = (long long)blockIdx.x * SCAN_BLOCK + threadIdx.x * SCAN_EPT;
     int v[SCAN_EPT];
-    scan_load(in, base, n, v);
+    scan_load<NONZERO>(in, base, n, v);
     int t = 0;
 #pragma unroll
     for (int i = 0; i < SCAN_EPT; ++i) t += v[i];
@@ -338,14 +345,16 @@ __global__ __launch_bounds__(256) void k_scan_apply(const int *__restrict__ in, 
 
 size_t scan_tmp_ints(int64_t n) { return (size_t)((n + SCAN_BLOCK - 1) / SCAN_BLOCK) + 1; }
 
-static void launch_scan(const int32_t *in, int32_t *out, int64_t n, int32_t *bsum, bool inclusive, hipStream_t s)
+// exclusive scan of in[0 .. n) into out (in place allowed); nonzero: of the sequence (in[i] != 0)
+static void launch_scan(const int32_t *in, int32_t *out, int64_t n, int32_t *bsum, bool nonzero, hipStream_t s)
 {
     if (n <= 0) return;
     const long long nb = (n + SCAN_BLOCK - 1) / SCAN_BLOCK;
-    PSK_LAUNCH(k_scan_reduce, dim3((unsigned)nb), dim3(256), 0, s, in, (long long)n, bsum);
+    if (nonzero) PSK_LAUNCH(k_scan_reduce<true>, dim3((unsigned)nb), dim3(256), 0, s, in, (long long)n, bsum);
+    else PSK_LAUNCH(k_scan_reduce<false>, dim3((unsigned)nb), dim3(256), 0, s, in, (long long)n, bsum);
     PSK_LAUNCH(k_scan_spine, dim3(1), dim3(256), 0, s, bsum, nb);
-    if (inclusive) PSK_LAUNCH(k_scan_apply<true>, dim3((unsigned)nb), dim3(256), 0, s, in, out, (long long)n, bsum);
-    else PSK_LAUNCH(k_scan_apply<false>, dim3((unsigned)nb), dim3(256), 0, s, in, out, (long long)n, bsum);
+    if (nonzero) PSK_LAUNCH((k_scan_apply<false, true>), dim3((unsigned)nb), dim3(256), 0, s, in, out, (long long)n, bsum);
+    else PSK_LAUNCH((k_scan_apply<false, false>), dim3((unsigned)nb), dim3(256), 0, s, in, out, (long long)n, bsum);
 }
 
 // ------------------------------------------------------------------ the analysis step: CSR -> slab hierarchy
@@ -486,48 +495,82 @@ __global__ __launch_bounds__(64) void k_slab_scatter(int rows, int nnz, const in
     }
 }
 
-// F[j] = 1 when slot j starts a pair (first slot of a chunk, or another row than the slot before), for
-// j < nslots = meta[0]; 0 beyond (the array is scanned over its whole allocated length).
-__global__ __launch_bounds__(256) void k_slab_starts(const int *__restrict__ meta, const int *__restrict__ srow,
-                                                     long long nmax, int *__restrict__ F)
+// Pairs.  One wave per chunk; slot j = chunk * CH + it * 64 + lane (it = 0 .. 7), so that the rows of the slots are read
+// with full-width loads.  A slot starts a pair when it is the chunk's first or its row differs from the row of the slot
+// before it (the lane below, or lane 63 of the round before); m[it] = the ballot of the starts of round it.
+constexpr int SLAB_ROUNDS = SLAB_CH / WAVE;
+__device__ __forceinline__ void chunk_starts(const int *__restrict__ srow, long long base, int lane,
+                                             unsigned long long (&m)[SLAB_ROUNDS], int (&r)[SLAB_ROUNDS])
 {
-    const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (j >= nmax) return;
-    const int n = meta[0];
-    int f = 0;
-    if (j < n) f = (j % SLAB_CH == 0 || srow[j] != srow[j - 1]) ? 1 : 0;
-    F[j] = f;
+#pragma unroll
+    for (int it = 0; it < SLAB_ROUNDS; ++it) r[it] = srow[base + it * WAVE + lane];
+    int last = 0;
+#pragma unroll
+    for (int it = 0; it < SLAB_ROUNDS; ++it) {
+        int prev = __shfl_up(r[it], 1, WAVE);
+        if (lane == 0) prev = last;
+        m[it] = __ballot((it == 0 && lane == 0) || r[it] != prev);
+        last = rl(r[it], WAVE - 1);
+    }
 }
 
-// I = inclusive scan of F: slot j belongs to pair I[j] - 1.  Sets the end-of-pair bit, the chunk table, and
-// marks the CSR position of every real pair's first slot (mark[p] = 1, pair_at[p] = pair) for the row lists.
+// cnt[c] = number of pairs of chunk c for c < nslots / CH (nslots = meta[0]), 0 for the entries up to `nmaxchunks`
+// (the array is scanned over its whole length: its exclusive scan is chunk_pair).
+__global__ __launch_bounds__(256) void k_slab_count(const int *__restrict__ meta, const int *__restrict__ srow,
+                                                    int nmaxchunks, int *__restrict__ cnt)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int c = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    if (c > nmaxchunks) return;
+    const int nch = meta[0] / SLAB_CH;
+    int total = 0;
+    if (c < nch) {
+        unsigned long long m[SLAB_ROUNDS];
+        int r[SLAB_ROUNDS];
+        chunk_starts(srow, (long long)c * SLAB_CH, lane, m, r);
+#pragma unroll
+        for (int it = 0; it < SLAB_ROUNDS; ++it) total += __popcll(m[it]);
+    }
+    if (lane == 0) cnt[c] = total;
+}
+
+// With chunk_pair = the exclusive scan of cnt: sets the end-of-pair bit of every pair's last slot (the slot before a
+// start, and the chunk's last slot) and, for the first slot of every pair of a real row, leaves the pair's number + 1 at
+// the CSR position the slot came from (pair_at, zero elsewhere), from which the row lists are formed.
 // meta[1] = number of pairs.
-__global__ __launch_bounds__(256) void k_slab_finish(const int *__restrict__ meta_in, const int *__restrict__ I,
-                                                     const int *__restrict__ srow, const int *__restrict__ src,
-                                                     unsigned short *__restrict__ scol, int *__restrict__ chunk_pair,
-                                                     int *__restrict__ mark, int *__restrict__ pair_at,
-                                                     int *__restrict__ meta)
+__global__ __launch_bounds__(256) void k_slab_close(const int *__restrict__ meta_in, const int *__restrict__ srow,
+                                                    const int *__restrict__ src, const int *__restrict__ chunk_pair,
+                                                    unsigned short *__restrict__ scol, int *__restrict__ pair_at,
+                                                    int *__restrict__ meta)
 {
-    const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
-    const int n = meta_in[0];
-    if (j >= n) return;
-    const int mine = I[j];
-    const bool start = j == 0 || I[j - 1] != mine;
-    const bool end = j == n - 1 || I[j + 1] != mine;
-    if (end) scol[j] = (unsigned short)(scol[j] | 0x8000u);
-    if (j % SLAB_CH == 0) chunk_pair[j / SLAB_CH] = mine - 1;
-    if (j == n - 1) {
-        chunk_pair[n / SLAB_CH] = mine;
-        meta[1] = mine;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int c = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const int nch = meta_in[0] / SLAB_CH;
+    if (c >= nch) return;
+    const long long base = (long long)c * SLAB_CH;
+    unsigned long long m[SLAB_ROUNDS];
+    int r[SLAB_ROUNDS];
+    chunk_starts(srow, base, lane, m, r);
+    const int cp = chunk_pair[c];
+    int before = 0;                                         // pairs of the chunk that start in earlier rounds
+#pragma unroll
+    for (int it = 0; it < SLAB_ROUNDS; ++it) {
+        const long long j = base + it * WAVE + lane;
+        const bool start = (m[it] >> lane) & 1ull;
+        const bool end = lane < WAVE - 1 ? (m[it] >> (lane + 1)) & 1ull
+                                         : (it < SLAB_ROUNDS - 1 ? m[it + 1 < SLAB_ROUNDS ? it + 1 : it] & 1ull : 1ull);
+        if (end) scol[j] = (unsigned short)(scol[j] | 0x8000u);
+        if (start && r[it] >= 0) {
+            const int mine = cp + before + __popcll(m[it] & (~0ull >> (WAVE - 1 - lane))) - 1;     // this slot's pair
+            pair_at[src[j]] = mine + 1;
+        }
+        before += __popcll(m[it]);
     }
-    if (start && srow[j] >= 0) {
-        mark[src[j]] = 1;
-        pair_at[src[j]] = mine - 1;
-    }
+    if (c == nch - 1 && lane == 0) meta[1] = chunk_pair[nch];
 }
 
-// R = exclusive scan of mark over nnz + 1 entries: R[p] = number of pairs whose first slot comes from a CSR
-// position below p.  Rows list their pairs in that order: qpos[r] = R[pos[r]], qidx[R[p]] = pair_at[p].
+// R = exclusive scan of (pair_at != 0) over nnz + 1 entries: R[p] = number of pairs whose first slot comes from a CSR
+// position below p.  Rows list their pairs in that order: qpos[r] = R[pos[r]], qidx[R[p]] = pair_at[p] - 1.
 // meta[2] = number of listed pairs.
 __global__ __launch_bounds__(256) void k_slab_rows(int rows, int nnz, const int *__restrict__ pos,
                                                    const int *__restrict__ R, const int *__restrict__ pair_at,
@@ -537,7 +580,7 @@ __global__ __launch_bounds__(256) void k_slab_rows(int rows, int nnz, const int 
     const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
     if (g < nnz) {
         const int a = R[g];
-        if (R[g + 1] != a) qidx[a] = pair_at[g];
+        if (R[g + 1] != a) qidx[a] = pair_at[g] - 1;
     }
     if (g <= rows) qpos[g] = R[pos[g]];
     if (g == 0) meta[2] = R[nnz];
@@ -574,11 +617,10 @@ SlabBuildSpace carve_slab_build(void *base, int64_t rows, int64_t cols, int64_t 
     w.H = reinterpret_cast<int32_t *>(take((size_t)(S * nblk + 1) * 4));
     w.srow = reinterpret_cast<int32_t *>(take((size_t)(nmax + 1) * 4));
     w.src = reinterpret_cast<int32_t *>(take((size_t)(nmax + 1) * 4));
-    w.F = reinterpret_cast<int32_t *>(take((size_t)(nmax + 1) * 4));
+    w.F = reinterpret_cast<int32_t *>(take((size_t)(nmax / SLAB_CH + 2) * 4));       // pairs per chunk
     w.mark = reinterpret_cast<int32_t *>(take((size_t)(nnz + 1) * 4));
     w.pair_at = reinterpret_cast<int32_t *>(take((size_t)(nnz + 1) * 4));
     size_t tmp = scan_tmp_ints(S * nblk + 1);
-    if (scan_tmp_ints(nmax + 1) > tmp) tmp = scan_tmp_ints(nmax + 1);
     if (scan_tmp_ints(nnz + 1) > tmp) tmp = scan_tmp_ints(nnz + 1);
     w.scan_tmp = reinterpret_cast<int32_t *>(take(tmp * 4));
     w.bytes = o;
@@ -609,17 +651,17 @@ static hipError_t launch_slab_build_t(int32_t rows, int32_t cols, int32_t nnz, c
     PSK_LAUNCH(k_slab_pads<T>, dim3(S), dim3(64), 0, s, w.H, nblk, slab_chunk, svals, scol_d, w.srow, w.src);
     PSK_LAUNCH(k_slab_scatter<T>, dim3(nblk), dim3(64), (unsigned)(lds + SCATTER_ROWS * 4), s, rows, nnz, pos, crd, vals,
                w.tile_row, w.H, slab_chunk, S, nblk, nbits, svals, scol_d, w.srow, w.src);
-    PSK_LAUNCH(k_slab_starts, dim3((unsigned)((nmax + 1 + 255) / 256)), dim3(256), 0, s, w.meta, w.srow,
-               (long long)(nmax + 1), w.F);
-    launch_scan(w.F, w.F, nmax + 1, w.scan_tmp, true, s);
+    const int nmaxchunks = (int)(nmax / SLAB_CH);
+    PSK_LAUNCH(k_slab_count, dim3((unsigned)(nmaxchunks / 4 + 1)), dim3(256), 0, s, w.meta, w.srow, nmaxchunks, w.F);
+    launch_scan(w.F, chunk_pair, (int64_t)nmaxchunks + 1, w.scan_tmp, false, s);
     {
         int64_t blocks = ((int64_t)nnz + 1 + 255) / 256;
         if (blocks > 65536) blocks = 65536;
-        PSK_LAUNCH(k_fill_int, dim3((unsigned)blocks), dim3(256), 0, s, w.mark, (long long)nnz + 1, 0);
+        PSK_LAUNCH(k_fill_int, dim3((unsigned)blocks), dim3(256), 0, s, w.pair_at, (long long)nnz + 1, 0);
     }
-    PSK_LAUNCH(k_slab_finish, dim3((unsigned)((nmax + 255) / 256)), dim3(256), 0, s, w.meta, w.F, w.srow, w.src, scol_d,
-               chunk_pair, w.mark, w.pair_at, w.meta);
-    launch_scan(w.mark, w.mark, (int64_t)nnz + 1, w.scan_tmp, false, s);
+    PSK_LAUNCH(k_slab_close, dim3((unsigned)(nmaxchunks / 4 + 1)), dim3(256), 0, s, w.meta, w.srow, w.src, chunk_pair,
+               scol_d, w.pair_at, w.meta);
+    launch_scan(w.pair_at, w.mark, (int64_t)nnz + 1, w.scan_tmp, true, s);
     const int64_t span = ((int64_t)nnz > (int64_t)rows + 1 ? (int64_t)nnz : (int64_t)rows + 1);
     PSK_LAUNCH(k_slab_rows, dim3((unsigned)((span + 255) / 256)), dim3(256), 0, s, rows, nnz, pos, w.mark, w.pair_at,
                qpos, qidx, w.meta);
