@@ -204,3 +204,17 @@ def test_slab_unaligned_vector_split_phases_own_buffers_and_stream():
     ref, mag = oracle.spmv_csr_f64(A.pos, A.crd, v64, x64h, threads=8)
     ok, worst = oracle.within_tolerance(y64.cpu().numpy(), ref, mag, 1e-14, 1e-300)
     assert ok, "fp64, unaligned x, split phases: worst |err|/bound = %.3g" % worst
+
+
+def test_slab_many_slabs():
+    """A hundred million columns: 3 055 slabs (the bucketing kernels keep one counter per slab in LDS and rank lanes with one
+    ballot per bit of the slab number: 12 bits here), most of them empty, a few entries each in the others."""
+    rows, cols = 5000, 100_000_000
+    rng = np.random.default_rng(33)
+    L = rng.integers(0, 80, size=rows)
+    L[17] = 3000
+    A = wl.csr_from_lengths(L, cols, seed=33)
+    S = build_and_compare(A, "%d x %d" % (rows, cols))
+    assert S.desc.nslabs == -(-cols // 32736)
+    x = wl.dense_uniform(cols, 34, wl.S_X)
+    product_ok(S, A, x, "many slabs")
