@@ -241,8 +241,8 @@ hipError_t launch_slab_pairs_f64(const double *svals, const uint16_t *scol, cons
 }
 
 // ------------------------------------------------------------------ prefix sums over int32 arrays
-// Three kernels: sums of blocks of 4096, a single-workgroup scan of those sums, then every block scans its
-// own elements on top of its offset.  In place (out == in) is allowed.
+// Exclusive scans.  Three kernels: sums of blocks of 4096, a single-workgroup scan of those sums, then every block
+// scans its own elements on top of its offset.  In place (out == in) is allowed.
 constexpr int SCAN_EPT = 16, SCAN_BLOCK = 256 * SCAN_EPT;
 
 __device__ __forceinline__ int block_scan_256(int v, int *s_w, int *total)
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(256) void k_scan_spine(int *__restrict__ bsum, long
     }
 }
 
-template <bool INCLUSIVE, bool NONZERO>
+template <bool NONZERO>
 __global__ __launch_bounds__(256) void k_scan_apply(const int *__restrict__ in, int *__restrict__ out, long long n,
                                                     const int *__restrict__ bsum)
 {
@@ -328,9 +328,8 @@ __global__ __launch_bounds__(256) void k_scan_apply(const int *__restrict__ in, 
     int o[SCAN_EPT];
 #pragma unroll
     for (int i = 0; i < SCAN_EPT; ++i) {
-        if (INCLUSIVE) run += v[i];
         o[i] = run;
-        if (!INCLUSIVE) run += v[i];
+        run += v[i];
     }
     if (base + SCAN_EPT <= n) {
 #pragma unroll
@@ -353,8 +352,8 @@ static void launch_scan(const int32_t *in, int32_t *out, int64_t n, int32_t *bsu
     if (nonzero) PSK_LAUNCH(k_scan_reduce<true>, dim3((unsigned)nb), dim3(256), 0, s, in, (long long)n, bsum);
     else PSK_LAUNCH(k_scan_reduce<false>, dim3((unsigned)nb), dim3(256), 0, s, in, (long long)n, bsum);
     PSK_LAUNCH(k_scan_spine, dim3(1), dim3(256), 0, s, bsum, nb);
-    if (nonzero) PSK_LAUNCH((k_scan_apply<false, true>), dim3((unsigned)nb), dim3(256), 0, s, in, out, (long long)n, bsum);
-    else PSK_LAUNCH((k_scan_apply<false, false>), dim3((unsigned)nb), dim3(256), 0, s, in, out, (long long)n, bsum);
+    if (nonzero) PSK_LAUNCH(k_scan_apply<true>, dim3((unsigned)nb), dim3(256), 0, s, in, out, (long long)n, bsum);
+    else PSK_LAUNCH(k_scan_apply<false>, dim3((unsigned)nb), dim3(256), 0, s, in, out, (long long)n, bsum);
 }
 
 // ------------------------------------------------------------------ the analysis step: CSR -> slab hierarchy
