@@ -494,6 +494,135 @@ __global__ __launch_bounds__(64) void k_slab_scatter(int rows, int nnz, const in
     }
 }
 
+// The same bucketing for matrices of at most STAGE_SLABS slabs, with coalesced stores: a workgroup of four waves takes
+// the block, wave w its w-th quarter (8 steps of 64 positions).  The waves first count their positions per slab; from
+// the counts every (wave, slab) gets its place in a staging area in LDS that holds the block's entries ordered by slab
+// (and inside a slab by CSR position: wave after wave, step after step, lane after lane -- the same stable order).  The
+// entries are then ranked as above, staged, and written out in staging order, so that a slab's entries of this block
+// (33 on average for 62 slabs) leave as one run of consecutive slots instead of 64 scattered stores per step.
+constexpr int STAGE_SLABS = 512;
+template <typename T>
+__global__ __launch_bounds__(256) void k_slab_scatter_staged(int rows, int nnz, const int *__restrict__ pos,
+                                                            const int *__restrict__ crd, const T *__restrict__ vals,
+                                                            const int *__restrict__ tile_row,
+                                                            const int *__restrict__ E,
+                                                            const int *__restrict__ slab_chunk, int nslabs, int nblk,
+                                                            int nbits, T *__restrict__ svals,
+                                                            unsigned short *__restrict__ scol,
+                                                            int *__restrict__ srow, int *__restrict__ src)
+{
+    constexpr int W = SlabOf<T>::W, NW = 4, QUART = BUILD_BT / NW, STEPS = QUART / WAVE;
+    __shared__ int woff[NW][STAGE_SLABS];        // entries of (wave, slab); later: where that wave's next entry of the slab goes
+    __shared__ int lbase[STAGE_SLABS + 1];       // first staging index of each slab
+    __shared__ int gbase[STAGE_SLABS];           // first slot (global) of this block's entries of each slab
+    __shared__ int spos[SCATTER_ROWS];
+    __shared__ T s_val[BUILD_BT];
+    __shared__ int s_row[BUILD_BT];
+    __shared__ unsigned short s_col[BUILD_BT], s_idx[BUILD_BT], s_slab[BUILD_BT];
+    __shared__ int s_w[4];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
+    const long long p0 = (long long)b * BUILD_BT;
+    const int nvalid = (int)min((long long)BUILD_BT, (long long)nnz - p0);
+    const int r_lo = tile_row[b], r_hi = tile_row[b + 1];
+    const bool local = r_hi - r_lo < SCATTER_ROWS;
+    for (int i = tid; i < NW * STAGE_SLABS; i += 256) (&woff[0][0])[i] = 0;
+    if (local)
+        for (int i = tid; i <= r_hi - r_lo; i += 256) spos[i] = pos[r_lo + i];
+    for (int sl = tid; sl < nslabs; sl += 256)
+        gbase[sl] = slab_chunk[sl] * SLAB_CH + (E[(long long)sl * nblk + b] - E[(long long)sl * nblk]);
+    __syncthreads();
+    // this lane's positions: wave * QUART + st * 64 + lane
+    int c[STEPS], r[STEPS];
+    T v[STEPS];
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+        const int i = wave * QUART + st * WAVE + lane;
+        c[st] = 0; v[st] = T(0);
+        if (i < nvalid) { c[st] = crd[p0 + i]; v[st] = vals[p0 + i]; }
+    }
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+        const int i = wave * QUART + st * WAVE + lane;
+        r[st] = 0;
+        if (i < nvalid) {
+            const int p = (int)(p0 + i);
+            atomicAdd(&woff[wave][c[st] / W], 1);
+            int lo = r_lo, hi = r_hi;
+            if (local) {
+                while (lo < hi) {
+                    const int mid = lo + ((hi - lo + 1) >> 1);
+                    if (spos[mid - r_lo] <= p) lo = mid; else hi = mid - 1;
+                }
+            } else {
+                while (lo < hi) {
+                    const int mid = lo + ((hi - lo + 1) >> 1);
+                    if (pos[mid] <= p) lo = mid; else hi = mid - 1;
+                }
+            }
+            r[st] = lo;
+        }
+    }
+    __syncthreads();
+    // staging index of each slab = exclusive scan of the block's count per slab (two slabs per thread), then the
+    // waves' places inside each slab
+    {
+        const int s0 = 2 * tid, s1 = 2 * tid + 1;
+        int n0 = 0, n1 = 0;
+        if (s0 < nslabs) n0 = woff[0][s0] + woff[1][s0] + woff[2][s0] + woff[3][s0];
+        if (s1 < nslabs) n1 = woff[0][s1] + woff[1][s1] + woff[2][s1] + woff[3][s1];
+        int total;
+        const int inc = block_scan_256(n0 + n1, s_w, &total);
+        const int b0 = inc - n0 - n1;
+        if (s0 < nslabs) {
+            lbase[s0] = b0;
+            int o = b0;
+            for (int w = 0; w < NW; ++w) { const int t = woff[w][s0]; woff[w][s0] = o; o += t; }
+        }
+        if (s1 < nslabs) {
+            lbase[s1] = b0 + n0;
+            int o = b0 + n0;
+            for (int w = 0; w < NW; ++w) { const int t = woff[w][s1]; woff[w][s1] = o; o += t; }
+        }
+    }
+    __syncthreads();
+    // rank and stage (a wave touches only its own row of woff; its LDS operations execute in program order)
+    const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+        const int i = wave * QUART + st * WAVE + lane;
+        const bool valid = i < nvalid;
+        const int sl = valid ? c[st] / W : 0;
+        unsigned long long peers = __ballot(valid);
+        for (int k = 0; k < nbits; ++k) {
+            const bool one = (sl >> k) & 1;
+            const unsigned long long m = __ballot(valid && one);
+            peers &= one ? m : ~m;
+        }
+        int li = 0;
+        if (valid) li = woff[wave][sl] + __popcll(peers & below);
+        __builtin_amdgcn_wave_barrier();
+        if (valid && (peers & below) == 0) woff[wave][sl] += __popcll(peers);
+        __builtin_amdgcn_wave_barrier();
+        if (valid) {
+            s_val[li] = v[st];
+            s_col[li] = (unsigned short)(c[st] - sl * W);
+            s_row[li] = r[st];
+            s_idx[li] = (unsigned short)i;
+            s_slab[li] = (unsigned short)sl;
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < nvalid; i += 256) {
+        const int sl = s_slab[i];
+        const int dst = gbase[sl] + (i - lbase[sl]);
+        svals[slab_value_index<SlabOf<T>::G>(dst)] = s_val[i];
+        scol[dst] = s_col[i];
+        srow[dst] = s_row[i];
+        src[dst] = (int)(p0 + s_idx[i]);
+    }
+}
+
 // Pairs.  One wave per chunk; slot j = chunk * CH + it * 64 + lane (it = 0 .. 7), so that the rows of the slots are read
 // with full-width loads.  A slot starts a pair when it is the chunk's first or its row differs from the row of the slot
 // before it (the lane below, or lane 63 of the round before); m[it] = the ballot of the starts of round it.
@@ -648,8 +777,12 @@ static hipError_t launch_slab_build_t(int32_t rows, int32_t cols, int32_t nnz, c
     launch_scan(w.H, w.H, (int64_t)S * nblk + 1, w.scan_tmp, false, s);
     PSK_LAUNCH(k_slab_bases, dim3(1), dim3(256), 0, s, w.H, S, nblk, slab_chunk, w.meta);
     PSK_LAUNCH(k_slab_pads<T>, dim3(S), dim3(64), 0, s, w.H, nblk, slab_chunk, svals, scol_d, w.srow, w.src);
-    PSK_LAUNCH(k_slab_scatter<T>, dim3(nblk), dim3(64), (unsigned)(lds + SCATTER_ROWS * 4), s, rows, nnz, pos, crd, vals,
-               w.tile_row, w.H, slab_chunk, S, nblk, nbits, svals, scol_d, w.srow, w.src);
+    if (S <= STAGE_SLABS)
+        PSK_LAUNCH(k_slab_scatter_staged<T>, dim3(nblk), dim3(256), 0, s, rows, nnz, pos, crd, vals, w.tile_row, w.H,
+                   slab_chunk, S, nblk, nbits, svals, scol_d, w.srow, w.src);
+    else
+        PSK_LAUNCH(k_slab_scatter<T>, dim3(nblk), dim3(64), (unsigned)(lds + SCATTER_ROWS * 4), s, rows, nnz, pos, crd, vals,
+                   w.tile_row, w.H, slab_chunk, S, nblk, nbits, svals, scol_d, w.srow, w.src);
     const int nmaxchunks = (int)(nmax / SLAB_CH);
     PSK_LAUNCH(k_slab_count, dim3((unsigned)(nmaxchunks / 4 + 1)), dim3(256), 0, s, w.meta, w.srow, nmaxchunks, w.F);
     launch_scan(w.F, chunk_pair, (int64_t)nmaxchunks + 1, w.scan_tmp, false, s);
