@@ -500,7 +500,7 @@ __global__ __launch_bounds__(64) void k_slab_scatter(int rows, int nnz, const in
 // (and inside a slab by CSR position: wave after wave, step after step, lane after lane -- the same stable order).  The
 // entries are then ranked as above, staged, and written out in staging order, so that a slab's entries of this block
 // (33 on average for 62 slabs) leave as one run of consecutive slots instead of 64 scattered stores per step.
-constexpr int STAGE_SLABS = 512;
+constexpr int STAGE_SLABS = 256;
 template <typename T>
 __global__ __launch_bounds__(256) void k_slab_scatter_staged(int rows, int nnz, const int *__restrict__ pos,
                                                             const int *__restrict__ crd, const T *__restrict__ vals,

@@ -139,3 +139,16 @@ def test_slab_f64_rejects_bad_arguments_and_mixed_types():
     y64 = torch.zeros(3, dtype=torch.float64, device="cuda")
     assert L.psk_spmv_slab_f64(ctypes.byref(S32.desc), x64.data_ptr(), y64.data_ptr(), 7, ws.data_ptr(), ws.numel(), None) == 2
     assert L.psk_spmv_slab(ctypes.byref(S64.desc), x64.data_ptr(), y64.data_ptr(), 7, ws.data_ptr(), ws.numel(), None) == 2
+
+
+def test_slab_f64_many_slabs():
+    """Ten million columns: 612 slabs, more than the staged scatter of the analysis step takes (the bucketing then
+    goes through the one-wave-per-block kernel)."""
+    rows, cols = 4000, 10_000_000
+    L = np.random.default_rng(35).integers(0, 70, size=rows)
+    L[9] = 5000
+    A = wl.csr_from_lengths(L, cols, seed=35)
+    vals, x = operands(A, 35)
+    S = build_and_compare(A, vals, "%d x %d" % (rows, cols))
+    assert S.desc.nslabs == -(-cols // W64)
+    product_ok(S, A, vals, x, "many slabs")
