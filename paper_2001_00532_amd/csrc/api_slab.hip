@@ -19,6 +19,8 @@ struct SlabMem {
 
 // columns per slab for values of vbytes bytes (4: float, 8: double)
 inline int32_t slab_w(int vbytes) { return vbytes == 8 ? kSlabColsF64 : kSlabCols; }
+// position tile of the row sums
+inline int32_t slab_tile(int vbytes) { return vbytes == 8 ? kSlabTileF64 : kSlabTile; }
 
 SlabMem carve_slab_mem(void *base, int64_t rows, int64_t cols, int64_t nnz, int vbytes)
 {
@@ -35,7 +37,7 @@ SlabMem carve_slab_mem(void *base, int64_t rows, int64_t cols, int64_t nnz, int 
     m.slab_chunk = reinterpret_cast<int32_t *>(take((size_t)(S + 1) * 4));
     m.qpos = reinterpret_cast<int32_t *>(take((size_t)(rows + 1) * 4));
     m.qidx = reinterpret_cast<int32_t *>(take((size_t)(nnz + 1) * 4));                     // at most one listed pair per entry
-    m.qtile_row = reinterpret_cast<int32_t *>(take((size_t)(nnz / kSlabTile + 2) * 4));
+    m.qtile_row = reinterpret_cast<int32_t *>(take((size_t)(nnz / slab_tile(vbytes) + 2) * 4));
     m.bytes = o;
     return m;
 }
@@ -87,7 +89,7 @@ int build_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const
     psk_slab d;
     d.rows = rows; d.cols = cols; d.nnz = nnz;
     d.nslabs = S; d.nslots = 0; d.nchunks = 0; d.npairs = 0; d.nq = 0;
-    d.slab_cols = W; d.chunk = kSlabChunk; d.tile = kSlabTile; d.value_bytes = vbytes;
+    d.slab_cols = W; d.chunk = kSlabChunk; d.tile = slab_tile(vbytes); d.value_bytes = vbytes;
     d.svals = m.svals; d.scol = m.scol; d.chunk_pair = m.chunk_pair; d.slab_chunk = m.slab_chunk;
     d.qpos = m.qpos; d.qidx = m.qidx; d.qtile_row = m.qtile_row;
     hipError_t e = hipSuccess;
@@ -116,7 +118,7 @@ int build_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const
     d.npairs = meta[1];
     d.nq = meta[2];
     // the position cut of the row lists, kept with the structure (it depends only on A)
-    e = launch_partition(rows, d.nq, m.qpos, kSlabTile, 0, m.qtile_row, s);
+    e = launch_partition(rows, d.nq, m.qpos, slab_tile(vbytes), 0, m.qtile_row, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     *out = d;
     return hip_status(e);
@@ -128,7 +130,7 @@ int spmv_slab(const psk_slab *S, const void *x, void *y, int vbytes, int phases,
     if (!S) return PSK_ERR_NULL;
     if (phases <= 0 || (phases & ~PSK_PHASE_ALL)) return PSK_ERR_UNSUPPORTED;
     if (S->rows < 0 || S->cols < 0 || S->nnz < 0 || S->npairs < 0 || S->nq < 0 || S->nchunks < 0 ||
-        S->value_bytes != vbytes || S->slab_cols != slab_w(vbytes) || S->chunk != kSlabChunk || S->tile != kSlabTile)
+        S->value_bytes != vbytes || S->slab_cols != slab_w(vbytes) || S->chunk != kSlabChunk || S->tile != slab_tile(vbytes))
         return PSK_ERR_SIZE;
     if ((S->rows > 0 && !y) || (S->nnz > 0 && !x)) return PSK_ERR_NULL;
     if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) & (uintptr_t)(vbytes - 1)) return PSK_ERR_ALIGNMENT;
@@ -142,7 +144,8 @@ int spmv_slab(const psk_slab *S, const void *x, void *y, int vbytes, int phases,
         workspace_bytes < psk_slab_spmv_workspace_bytes(S))
         return PSK_ERR_WORKSPACE;
     const size_t p_bytes = align256((size_t)(S->npairs + 1) * (size_t)vbytes);
-    const int32_t ntiles = (int32_t)psk_num_tiles(S->nq, kSlabTile);
+    const int32_t tile = slab_tile(vbytes);
+    const int32_t ntiles = (int32_t)psk_num_tiles(S->nq, tile);
     Workspace ws = carve(static_cast<char *>(workspace) + p_bytes, ntiles, vbytes / 4);
     ws.tile_row = const_cast<int32_t *>(S->qtile_row);         // the table is part of the structure; only read
     // step 1: one persistent workgroup per compute unit (a workgroup holds the CU's LDS)
@@ -161,10 +164,10 @@ int spmv_slab(const psk_slab *S, const void *x, void *y, int vbytes, int phases,
                                       (int32_t)S->nchunks, cus, ws.gap, s);
             if (e == hipSuccess) {
                 if (ntiles == 0) e = launch_fill_zero(static_cast<float *>(y), zero_words, s);
-                else e = launch_spmv_csr_f64_ones((int32_t)S->rows, (int32_t)S->nq, S->qpos, S->qidx, P, yd, ws, s);
+                else e = launch_spmv_csr_f64_ones((int32_t)S->rows, (int32_t)S->nq, S->qpos, S->qidx, P, yd, tile, ws, s);
             }
         }
-        if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup_f64(ntiles, kSlabTile, S->qpos, ws, yd, s, true);
+        if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess) e = launch_carry_fixup_f64(ntiles, tile, S->qpos, ws, yd, s, true);
         return hip_status(e);
     }
     float *P = static_cast<float *>(workspace);
@@ -180,7 +183,7 @@ int spmv_slab(const psk_slab *S, const void *x, void *y, int vbytes, int phases,
         }
     }
     if ((phases & PSK_PHASE_FIXUP) && e == hipSuccess)
-        e = launch_carry_fixup(ntiles, 1, 1, 1, kSlabTile, S->qpos, ws, yf, s, nullptr, nullptr, true);
+        e = launch_carry_fixup(ntiles, 1, 1, 1, tile, S->qpos, ws, yf, s, nullptr, nullptr, true);
     return hip_status(e);
 }
 
@@ -204,7 +207,7 @@ size_t psk_slab_spmv_workspace_bytes(const psk_slab *S)
 {
     if (!S || S->npairs < 0 || S->nq < 0 || (S->value_bytes != 4 && S->value_bytes != 8)) return 0;
     return align256((size_t)(S->npairs + 1) * (size_t)S->value_bytes) +
-           carve(nullptr, psk_num_tiles(S->nq, kSlabTile), S->value_bytes / 4).bytes;
+           carve(nullptr, psk_num_tiles(S->nq, slab_tile(S->value_bytes)), S->value_bytes / 4).bytes;
 }
 
 int psk_slab_build_csr(int64_t rows, int64_t cols, int64_t nnz, const int32_t *pos, const int32_t *crd,

@@ -156,6 +156,7 @@ constexpr int32_t kSlabChunk = 512;         // slots per chunk (one wave: 8 per 
 constexpr int32_t kSlabBuildBlock = 2048;   // CSR positions per block of the bucketing kernels
 constexpr int32_t kSlabMaxSlabs = 8192;     // the bucketing kernels keep one counter per slab in LDS
 constexpr int32_t kSlabTile = 2048;         // position tile of the second step (pairs per workgroup)
+constexpr int32_t kSlabTileF64 = 1024;      // the same for fp64 (its tile kernel holds twice the LDS per position)
 inline int64_t slab_max_slots(int64_t cols, int64_t nnz, int32_t W)
 {
     const int64_t S = (cols + W - 1) / W;
@@ -185,7 +186,7 @@ hipError_t launch_fill_int(int32_t *p, int64_t n, int32_t v, hipStream_t s);
 hipError_t launch_spmv_csr_ones(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
                                 const float *x, float *y, const Workspace &w, hipStream_t s);
 hipError_t launch_spmv_csr_f64_ones(int32_t rows, int32_t nnz, const int32_t *pos, const int32_t *crd, const double *x,
-                                    double *y, const Workspace &w, hipStream_t s);
+                                    double *y, int32_t tile, const Workspace &w, hipStream_t s);
 
 #ifdef PSK_CU_TRACE
 hipError_t cu_trace_set_spmv_csr(void *buf, unsigned records);

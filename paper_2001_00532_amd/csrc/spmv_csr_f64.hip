@@ -287,21 +287,23 @@ hipError_t launch_spmv_csr_f64_main(int32_t rows, int32_t cols, int32_t nnz, con
     return take_launch_status();
 }
 
-// y = Q * P with unit values over (pos, crd) = the row lists of the slab structure; tile 2048
+// y = Q * P with unit values over (pos, crd) = the row lists of the slab structure; tile 1024 or 2048
 hipError_t launch_spmv_csr_f64_ones(int32_t rows, int32_t nnz, const int32_t *pos, const int32_t *crd, const double *x,
-                                    double *y, const Workspace &w, hipStream_t s)
+                                    double *y, int32_t tile, const Workspace &w, hipStream_t s)
 {
-    const int ntiles = (int)(((int64_t)nnz + 2047) / 2048);
+    if (tile != 1024 && tile != 2048) return hipErrorInvalidValue;
+    const int ntiles = (int)(((int64_t)nnz + tile - 1) / tile);
     if (ntiles == 0) return hipSuccess;
     const int grid = xcd_grid(ntiles);
     const double *none = nullptr;
     double *cv = reinterpret_cast<double *>(w.carry_val);
-    if ((reinterpret_cast<uintptr_t>(crd) & 15) == 0)
-        PSK_LAUNCH((k_spmv_pos_f64<256, 8, true, false, true>), dim3(grid), dim3(256), 0, s, rows, nnz, pos, crd, none, x, y,
-                   w.tile_row, w.carry_row, cv, ntiles, 0, 0x7fffffff, 0, w.tile_cols, w.gap);
-    else
-        PSK_LAUNCH((k_spmv_pos_f64<256, 8, false, false, true>), dim3(grid), dim3(256), 0, s, rows, nnz, pos, crd, none, x,
-                   y, w.tile_row, w.carry_row, cv, ntiles, 0, 0x7fffffff, 0, w.tile_cols, w.gap);
+    const bool vec = (reinterpret_cast<uintptr_t>(crd) & 15) == 0;
+#define PSK_GO(NPT, V)                                                                                                   \
+    PSK_LAUNCH((k_spmv_pos_f64<256, NPT, V, false, true>), dim3(grid), dim3(256), 0, s, rows, nnz, pos, crd, none, x, y, \
+               w.tile_row, w.carry_row, cv, ntiles, 0, 0x7fffffff, 0, w.tile_cols, w.gap)
+    if (tile == 2048) { if (vec) PSK_GO(8, true); else PSK_GO(8, false); }
+    else { if (vec) PSK_GO(4, true); else PSK_GO(4, false); }
+#undef PSK_GO
     return take_launch_status();
 }
 
