@@ -422,11 +422,11 @@ typedef struct psk_slab {
 } psk_slab;
 
 /* Bytes of device memory for the structure of a rows x cols matrix with nnz entries (an upper bound: the
- * exact size depends on how the entries fall into slabs and chunks; about 10 bytes per entry + 4 per row);
+ * exact size depends on how the entries fall into slabs and chunks; about 10 bytes per entry + 4 per row; with fp64 values about 14 per entry);
  * 0 when the sizes are outside the limits above. */
 size_t psk_slab_mem_bytes(int64_t rows, int64_t cols, int64_t nnz);
 size_t psk_slab_mem_bytes_f64(int64_t rows, int64_t cols, int64_t nnz);
-/* Bytes of scratch memory psk_slab_build_csr needs (about 20 bytes per entry); free to reuse afterwards. */
+/* Bytes of scratch memory psk_slab_build_csr needs (about 16 bytes per entry); free to reuse afterwards. */
 size_t psk_slab_build_workspace_bytes(int64_t rows, int64_t cols, int64_t nnz);
 size_t psk_slab_build_workspace_bytes_f64(int64_t rows, int64_t cols, int64_t nnz);
 /* Bytes of workspace a product over S needs (the pair sums and the carry records); 0 if S is NULL. */
@@ -434,7 +434,7 @@ size_t psk_slab_spmv_workspace_bytes(const psk_slab *S);
 
 /*
  * The analysis step: builds the structure from a CSR matrix, entirely on the device (a histogram of the
- * slabs per block of 2048 positions, prefix sums, a stable scatter, pair flags and their prefix sums, the
+ * slabs per block of 2048 positions, prefix sums, a stable scatter, the pairs of every chunk and their prefix sums, the
  * row lists and their position cut).  `mem` (psk_slab_mem_bytes, 256-byte aligned) receives the arrays and
  * must stay allocated while *out is used; `workspace` (psk_slab_build_workspace_bytes, 256-byte aligned) is
  * scratch.  *out (HOST pointer) receives the sizes and the device pointers.  pos, crd, vals: as for
