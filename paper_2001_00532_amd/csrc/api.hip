@@ -384,7 +384,7 @@ int psk_spmv_csr_divide(int64_t rows, int64_t cols, int64_t nnz, const int32_t *
     hipError_t e = hipSuccess;
     if (phases & PSK_PHASE_MAIN) {
         if (nparts == 0) e = launch_fill_zero(y, rows, s);
-        else e = launch_spmv_csr_divide((int32_t)rows, (int32_t)nnz, pos, crd, vals, x, y, nparts, (int32_t)cpp, ws, s);
+        else e = launch_spmv_csr_divide((int32_t)rows, (int32_t)cols, (int32_t)nnz, pos, crd, vals, x, y, nparts, (int32_t)cpp, ws, s);
     }
     // two or more parts: cpp < nchunks, hence cpp * tile < nnz <= 2^31 - 1 (one part has no carries to add)
     const int64_t part_len = cpp * (int64_t)tile;

@@ -110,7 +110,7 @@ hipError_t launch_spmv_rowsplit(int32_t rows, const int32_t *pos, const int32_t 
 // CSR SpMV with the position space divided into `parts` pieces of chunks_per_part * 2048 positions
 // (persistent workgroups, in-kernel search, no table); carry records: one per part
 constexpr int32_t kDivideChunk = 2048;
-hipError_t launch_spmv_csr_divide(int32_t rows, int32_t nnz, const int32_t *pos, const int32_t *crd,
+hipError_t launch_spmv_csr_divide(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
                                   const float *vals, const float *x, float *y, int32_t parts,
                                   int32_t chunks_per_part, const Workspace &w, hipStream_t s);
 

@@ -28,36 +28,6 @@ __device__ __forceinline__ int tile_index(int g, int tid)
     return ((g / 4) * THREADS + tid) * 4 + (g & 3);
 }
 
-// Gathering x for four consecutive positions held by one lane.
-//
-// The vector-memory address unit takes about one clock per active lane for a gather whatever the
-// width of the access (4, 8 or 16 bytes per lane cost the same), so the cheapest gather is the one
-// with the fewest lane requests.  Positions whose columns are contiguous (c, c+1, ...: stencils,
-// bands, dense blocks) can be served by one 16-byte load of their lane.  run_plan() looks at a lane's
-// four columns: run A starts at position 0, run B right after it; if A and B together cover all four
-// positions two wide loads replace four narrow ones.  The choice is made per wave (one ballot) so that
-// both variants stay straight-line code with every load issued before the first use; unstructured
-// matrices never take the wide path and keep their 4-byte gathers.
-typedef float v4f_u __attribute__((ext_vector_type(4), aligned(4)));
-struct RunPlan { int lenA; int colB; bool ok; };
-__device__ __forceinline__ RunPlan run_plan(v4i c, int cols)
-{
-    const bool e1 = c.y == c.x + 1, e2 = c.z == c.y + 1, e3 = c.w == c.z + 1;
-    RunPlan p;
-    p.lenA = e1 ? (e2 ? (e3 ? 4 : 3) : 2) : 1;
-    p.colB = p.lenA == 1 ? c.y : (p.lenA == 2 ? c.z : c.w);
-    const bool covered = p.lenA >= 3 || (p.lenA == 2 && e3) || (p.lenA == 1 && e2 && e3);
-    p.ok = covered && c.x <= cols - 4 && p.colB <= cols - 4;
-    return p;
-}
-__device__ __forceinline__ void run_select(const RunPlan &p, v4f_u wA, v4f_u wB, float (&g)[4])
-{
-    g[0] = wA.x;
-    g[1] = p.lenA >= 2 ? wA.y : wB.x;
-    g[2] = p.lenA >= 3 ? wA.z : (p.lenA == 2 ? wB.x : wB.y);
-    g[3] = p.lenA == 4 ? wA.w : (p.lenA == 3 ? wB.x : (p.lenA == 2 ? wB.y : wB.z));
-}
-
 // VARIANT 0: one pass, carries.  1: a column pass (window [clo, chi), accum adds to earlier passes).
 // 2: one pass with the schedule's atomics instead of carries (baseline).
 // 4: one pass over a DCSR operand: `rows` counts the stored rows, row s of the hierarchy is row rowmap[s]

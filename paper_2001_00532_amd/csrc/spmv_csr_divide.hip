@@ -13,7 +13,7 @@
 namespace psk {
 
 template <int THREADS, int NPT, bool VEC>
-__global__ __launch_bounds__(THREADS) void k_spmv_div(int rows, int nnz, const int *__restrict__ pos,
+__global__ __launch_bounds__(THREADS) void k_spmv_div(int rows, int cols, int nnz, const int *__restrict__ pos,
                                                       const int *__restrict__ crd,
                                                       const float *__restrict__ vals,
                                                       const float *__restrict__ x, float *__restrict__ y,
@@ -83,17 +83,37 @@ __global__ __launch_bounds__(THREADS) void k_spmv_div(int rows, int nnz, const i
                     cv[g] = ld_stream(reinterpret_cast<const v4i *>(crd + off));
                     vv[g] = ld_stream(reinterpret_cast<const v4f *>(vals + off));
                 }
-                float xg[NPT];
+                // two 16-byte gathers per four positions when every lane of the wave holds two runs of consecutive
+                // columns (run_plan), four 4-byte gathers otherwise: as in the tiled kernel
+                float xg[NPT / 4][4];
+                RunPlan plan[NPT / 4];
+                bool ok = true;
 #pragma unroll
                 for (int g = 0; g < NPT / 4; ++g) {
-                    xg[4 * g] = x[cv[g].x]; xg[4 * g + 1] = x[cv[g].y]; xg[4 * g + 2] = x[cv[g].z]; xg[4 * g + 3] = x[cv[g].w];
+                    plan[g] = run_plan(cv[g], cols);
+                    ok = ok && plan[g].ok;
+                }
+                if (__ballot(!ok) == 0ull) {
+                    v4f_u wA[NPT / 4], wB[NPT / 4];
+#pragma unroll
+                    for (int g = 0; g < NPT / 4; ++g) {
+                        wA[g] = *reinterpret_cast<const v4f_u *>(x + cv[g].x);
+                        wB[g] = *reinterpret_cast<const v4f_u *>(x + plan[g].colB);
+                    }
+#pragma unroll
+                    for (int g = 0; g < NPT / 4; ++g) run_select(plan[g], wA[g], wB[g], xg[g]);
+                } else {
+#pragma unroll
+                    for (int g = 0; g < NPT / 4; ++g) {
+                        xg[g][0] = x[cv[g].x]; xg[g][1] = x[cv[g].y]; xg[g][2] = x[cv[g].z]; xg[g][3] = x[cv[g].w];
+                    }
                 }
 #pragma unroll
                 for (int g = 0; g < NPT / 4; ++g) {
-                    prod[4 * g] = vv[g].x * xg[4 * g];
-                    prod[4 * g + 1] = vv[g].y * xg[4 * g + 1];
-                    prod[4 * g + 2] = vv[g].z * xg[4 * g + 2];
-                    prod[4 * g + 3] = vv[g].w * xg[4 * g + 3];
+                    prod[4 * g] = vv[g].x * xg[g][0];
+                    prod[4 * g + 1] = vv[g].y * xg[g][1];
+                    prod[4 * g + 2] = vv[g].z * xg[g][2];
+                    prod[4 * g + 3] = vv[g].w * xg[g][3];
                 }
             } else {
                 int c[NPT];
@@ -181,17 +201,17 @@ __global__ __launch_bounds__(THREADS) void k_spmv_div(int rows, int nnz, const i
     }
 }
 
-hipError_t launch_spmv_csr_divide(int32_t rows, int32_t nnz, const int32_t *pos, const int32_t *crd,
+hipError_t launch_spmv_csr_divide(int32_t rows, int32_t cols, int32_t nnz, const int32_t *pos, const int32_t *crd,
                                   const float *vals, const float *x, float *y, int32_t parts,
                                   int32_t chunks_per_part, const Workspace &w, hipStream_t s)
 {
     if (parts <= 0) return hipSuccess;
     const bool vec = ((reinterpret_cast<uintptr_t>(crd) | reinterpret_cast<uintptr_t>(vals)) & 15) == 0;
     if (vec)
-        PSK_LAUNCH((k_spmv_div<256, 8, true>), dim3(parts), dim3(256), 0, s, rows, nnz, pos, crd, vals, x, y,
+        PSK_LAUNCH((k_spmv_div<256, 8, true>), dim3(parts), dim3(256), 0, s, rows, cols, nnz, pos, crd, vals, x, y,
                            w.carry_row, w.carry_val, chunks_per_part);
     else
-        PSK_LAUNCH((k_spmv_div<256, 8, false>), dim3(parts), dim3(256), 0, s, rows, nnz, pos, crd, vals, x, y,
+        PSK_LAUNCH((k_spmv_div<256, 8, false>), dim3(parts), dim3(256), 0, s, rows, cols, nnz, pos, crd, vals, x, y,
                            w.carry_row, w.carry_val, chunks_per_part);
     return take_launch_status();
 }
