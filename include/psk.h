@@ -456,6 +456,8 @@ int psk_slab_build_csr_f64(int64_t rows, int64_t cols, int64_t nnz, const int32_
  * (pair sums, row sums, carry fix-up) and returns; allocates nothing, never synchronises.  `phases`:
  * PSK_PHASE_MAIN = the two sum kernels, PSK_PHASE_FIXUP = the fix-up (PSK_PHASE_ALL for a product;
  * PSK_PHASE_PARTITION does nothing: the cut of the row lists is part of the structure).
+ * PSK_ERR_SIZE for a struct whose sizes are not consistent with each other (they decide grids and index ranges);
+ * what the arrays hold is the caller's contract: only psk_slab_build_csr makes them.
  */
 int psk_spmv_slab(const psk_slab *S, const float *x, float *y, int phases, void *workspace,
                   size_t workspace_bytes, void *stream);

@@ -132,6 +132,12 @@ int spmv_slab(const psk_slab *S, const void *x, void *y, int vbytes, int phases,
     if (S->rows < 0 || S->cols < 0 || S->nnz < 0 || S->npairs < 0 || S->nq < 0 || S->nchunks < 0 ||
         S->value_bytes != vbytes || S->slab_cols != slab_w(vbytes) || S->chunk != kSlabChunk || S->tile != slab_tile(vbytes))
         return PSK_ERR_SIZE;
+    // the sizes a build leaves are consistent with each other; a struct that is not was not made by psk_slab_build_csr
+    if (S->rows > kMaxI32 - 1 || S->cols > kMaxI32 || S->nnz > kMaxI32 || S->nslots > kMaxI32 ||
+        S->nslabs != (S->cols + S->slab_cols - 1) / S->slab_cols || S->nslots != S->nchunks * kSlabChunk ||
+        S->nslots < S->nnz || S->nslots > slab_max_slots(S->cols, S->nnz, S->slab_cols) || S->npairs > S->nslots ||
+        S->nq > S->npairs || S->nq > S->nnz || (S->nnz > 0 && S->npairs < 1))
+        return PSK_ERR_SIZE;
     if ((S->rows > 0 && !y) || (S->nnz > 0 && !x)) return PSK_ERR_NULL;
     if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) & (uintptr_t)(vbytes - 1)) return PSK_ERR_ALIGNMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);

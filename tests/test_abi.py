@@ -137,3 +137,37 @@ def test_binding_refuses_partial_products_on_a_temporary_workspace():
             fn(*args, phases=psk.PSK_PHASE_MAIN | psk.PSK_PHASE_FIXUP)
     with pytest.raises(ValueError):
         psk.psk_spmv_csr_divide(4, 4, 4, None, None, None, None, None, phases=psk.PSK_PHASE_MAIN)
+
+
+def test_slab_product_refuses_a_struct_that_no_build_made():
+    """The product over the slab structure checks, on the host and before any launch, that the sizes in the struct are
+    the kind a build leaves (they decide grids and index ranges of its kernels)."""
+    L = psk.lib()
+    one = ctypes.c_void_p(256)
+
+    def struct(**over):
+        d = psk.psk_slab()
+        d.rows, d.cols, d.nnz = 1000, 100_000, 5000
+        d.slab_cols, d.chunk, d.tile, d.value_bytes = 32736, 512, 2048, 4
+        d.nslabs = 4
+        d.nchunks = 12
+        d.nslots = 12 * 512
+        d.npairs, d.nq = 5200, 5000
+        for name in ("svals", "scol", "chunk_pair", "slab_chunk", "qpos", "qidx", "qtile_row"):
+            setattr(d, name, 256)
+        for k, v in over.items():
+            setattr(d, k, v)
+        return d
+
+    def product(d, f64=False):
+        fn = L.psk_spmv_slab_f64 if f64 else L.psk_spmv_slab
+        return fn(ctypes.byref(d), one, one, 7, None, 0, None)
+
+    assert product(struct()) == 4                       # consistent sizes: only the workspace is missing
+    for over in (dict(nslabs=3), dict(nchunks=13), dict(nslots=12 * 512 + 1), dict(nslots=8 * 512, nchunks=8),
+                 dict(npairs=12 * 512 + 1), dict(nq=5201), dict(nq=5300, npairs=5300), dict(npairs=0, nq=0),
+                 dict(slab_cols=16352), dict(chunk=256), dict(tile=1024), dict(value_bytes=8), dict(rows=-1),
+                 dict(nslots=40 * 512, nchunks=40)):
+        assert product(struct(**over)) == 2, over
+    assert product(struct(), f64=True) == 2             # a structure of the other value type
+    assert product(struct(value_bytes=8, slab_cols=16352, tile=1024, nslabs=7), f64=True) == 4
