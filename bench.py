@@ -783,6 +783,9 @@ def main():
         slab_us = statistics.median(all_ms) * 1e3
         analysis["repaid_after_products"] = (int(np.ceil(analysis["ms_median"] * 1e3 / (csr_us - slab_us)))
                                              if csr_us > slab_us else None)
+        # the same throughput with the analysis charged to the products of one matrix (10, 100, 1000 of them)
+        analysis["gflops_with_analysis_over_products"] = {
+            str(n): round(fl * n / ((n * slab_us + analysis["ms_median"] * 1e3) * 1e-6) / 1e9, 1) for n in (10, 100, 1000)}
         rec["analysis"] = analysis
         rec["csr_path"] = {"call": "psk_spmv_csr_f64" if f64 else "psk_spmv_csr", "tile": csr_tile, "col_passes": csr_passes,
                            "us_median": round(csr_us, 2), "gflops": round(fl / (csr_us * 1e-6) / 1e9, 3),
